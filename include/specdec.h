@@ -1,0 +1,209 @@
+/*
+ * specdec.h -- C ABI of the MI355X (gfx950) draft-verify-correct round of
+ * speculative decoding with adaptive candidate length (SpecDec++).
+ *
+ * The library implements Algorithm 2 of the paper (Sec. 4.3) with Algorithm 1's
+ * verify / correct tail (Appendix C) as hand-written HIP kernels.  PyTorch (or
+ * any other allocator) only provides device memory for the weights; every step
+ * of the path runs in this library's kernels on `hip_stream`.
+ *
+ * Conventions
+ *   - "DEVICE" pointers are HIP device pointers owned by the caller and must stay
+ *     alive and unchanged while a context that was given them exists.
+ *   - "HOST" pointers are ordinary host memory, read or written before return.
+ *   - Matrices are row-major [out, in]; dtype is SD_F32 or SD_BF16 for every
+ *     tensor of one model (weights, activations and KV cache share it).
+ *   - Every function returns an sd_status; 0 is success, negative is an error.
+ *     Nothing throws or aborts.  Host out-parameters are written only on SD_OK.
+ *     On an error the sequences' committed state (tokens, lengths) is unchanged.
+ *   - Calls on one context must not overlap.
+ */
+#ifndef SPECDEC_H
+#define SPECDEC_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef int32_t sd_status;
+enum {
+  SD_OK = 0,
+  SD_EINVAL = -1,     /* null pointer, bad shape, unsupported dtype or size        */
+  SD_ENOMEM = -2,     /* device or host allocation failed                          */
+  SD_ERANGE = -3,     /* sequence would overflow max_seq, or a token id >= vocab   */
+  SD_ENONFINITE = -4, /* a kernel saw NaN/Inf logits (sticky until sd_prefill)      */
+  SD_EDEVICE = -5     /* a HIP call failed                                          */
+};
+enum { SD_F32 = 0, SD_BF16 = 1 };
+
+#define SD_MAX_K 32          /* largest supported k_max                           */
+#define SD_MAX_HEAD_LAYERS 8
+
+/* Llama-style decoder (the paper's model family, Sec. 5.1): token embedding,
+ * n_layers x [RMSNorm, q|k|v projection, rotary embedding (rotate-half pairing),
+ * causal grouped-query attention, output projection, residual, RMSNorm, SwiGLU MLP,
+ * residual], final RMSNorm, LM head.  All pointers DEVICE. */
+typedef struct {
+  int32_t n_layers, d_model, n_heads, n_kv_heads, head_dim, d_ffn, vocab, dtype;
+  float rope_theta, rms_eps;
+  const void *tok_emb;             /* [vocab, d_model]                                 */
+  const void *lm_head;             /* [vocab, d_model]                                 */
+  const void *final_norm;          /* [d_model]                                        */
+  const void *const *wqkv;         /* HOST array[n_layers] of DEVICE [(Hq+2Hkv)*hd, d] (q rows, k rows, v rows) */
+  const void *const *wo;           /* HOST array[n_layers] of DEVICE [d, Hq*hd]        */
+  const void *const *w_gate_up;    /* HOST array[n_layers] of DEVICE [2*d_ffn, d] (gate rows, then up rows) */
+  const void *const *w_down;       /* HOST array[n_layers] of DEVICE [d, d_ffn]        */
+  const void *const *norm_attn;    /* HOST array[n_layers] of DEVICE [d]               */
+  const void *const *norm_mlp;     /* HOST array[n_layers] of DEVICE [d]               */
+} sd_model;
+
+/* Acceptance-prediction head f_theta (Eq. 3; "(D+1)-layer ResNet with SiLU",
+ * Sec. 5.1): z <- SiLU(W_j z + b_j) for j < n_layers-1 (z <- z + SiLU(..) when
+ * `residual` and the layer is square), then one linear layer to a single logit;
+ * the library applies the sigmoid.  Input: the draft's final-RMSNorm output for
+ * the last ingested token.  dims[0] must equal the draft's d_model and
+ * dims[n_layers] must be 1.  May be NULL in sd_create: then the predicted
+ * acceptance is 1 and only k_max, EOS and cache capacity end the draft loop. */
+typedef struct {
+  int32_t n_layers;                /* 1..SD_MAX_HEAD_LAYERS                            */
+  const int32_t *dims;             /* HOST array[n_layers+1]                           */
+  int32_t residual;
+  int32_t dtype;                   /* must equal the draft model's dtype               */
+  const void *const *W;            /* HOST array[n_layers] of DEVICE [dims[j+1], dims[j]] */
+  const void *const *b;            /* HOST array[n_layers] of DEVICE [dims[j+1]]       */
+} sd_head;
+
+typedef struct {
+  int32_t batch;                   /* sequences decoded together (>= 1)                */
+  int32_t max_seq;                 /* KV-cache capacity per sequence, in tokens        */
+  int32_t k_max;                   /* cap on candidates per round (Sec. 5.1), 1..SD_MAX_K */
+  void *hip_stream;                /* hipStream_t all work is enqueued on (NULL = default) */
+} sd_config;
+
+/* Per-call decoding parameters: threshold h of the stop rule (stop when
+ * 1 - prod p_hat > h, Sec. 4.3), softmax temperature (Appendix D.1 uses 1),
+ * greedy mode (Sec. 4.1), optional EOS (manual stop, Sec. 4.2 footnote), and the
+ * Philox seed.  Uniforms are Philox4x32-10 with key = seed and counter
+ * (slot i, round index, sequence id, stream), stream 0 = draft sample,
+ * 1 = accept test r_i, 2 = residual / bonus sample;
+ * u = (word0 >> 8) * 2^-24. */
+typedef struct {
+  float h;
+  float temperature;
+  int32_t greedy;
+  int32_t eos_id;                  /* < 0: none                                        */
+  uint64_t seed;
+} sd_params;
+
+/* Result of one round for one sequence (Algorithm 2's return): K candidates were
+ * drawn, the first n_accepted were kept, and tokens[0..n_new) = y_1..y_n, y'. */
+typedef struct {
+  int32_t K, n_accepted, n_new;
+  int32_t tokens[SD_MAX_K + 1];
+  int32_t cand[SD_MAX_K];          /* y_1..y_K as drawn                                */
+  float p_hat;                     /* cumulative predicted acceptance at the stop      */
+} sd_round_out;
+
+/* Counters of Sec. 3.2 (N_draft + N_target = N + N_discarded for whole rounds)
+ * and measured phase times, summed over the rounds of the call. */
+typedef struct {
+  int64_t N, N_draft, N_target, N_discarded, rounds;
+  double t_draft_s, t_target_s, t_accept_s, t_total_s;
+} sd_stats;
+
+typedef struct sd_ctx sd_ctx;
+
+/* Build a context: copies the model descriptions, allocates both KV caches,
+ * the stored draft rows q_1..q_K, the target rows p_1..p_{K+1} and all scratch on
+ * the current HIP device.  `head` may be NULL.  SD_EINVAL for inconsistent shapes
+ * (vocab mismatch between the models, head_dim not in {64,128} for bf16, ...). */
+sd_status sd_create(sd_ctx **out, const sd_model *target, const sd_model *draft,
+                    const sd_head *head, const sd_config *cfg);
+sd_status sd_destroy(sd_ctx *ctx);
+
+/* Reset sequence `seq` to the prompt (HOST ids, n_prompt >= 1): runs both models
+ * over prompt[0 .. n_prompt-1) so that each cache holds every finalised token but
+ * the last, which the first round ingests.  Resets the sequence's round index to
+ * 0 and clears the sticky non-finite flag.  SD_ERANGE if n_prompt + 2 > max_seq
+ * or an id is outside [0, vocab). */
+sd_status sd_prefill(sd_ctx *ctx, int32_t seq, const int32_t *prompt_host, int32_t n_prompt);
+
+/* One draft-verify-correct round for every sequence of the batch (Algorithm 2):
+ * adaptive draft loop with the head's stop rule, one target pass over the K+1
+ * positions, accept / residual resample, KV rollback.  out_per_seq: HOST
+ * array[batch].  The candidate cap of a sequence is min(k_max, max_seq - P - 1);
+ * SD_ERANGE if that is < 1 for any sequence (nothing is changed). */
+sd_status specdec_round(sd_ctx *ctx, const sd_params *params, sd_round_out *out_per_seq);
+
+/* Rounds until every sequence has max_new_tokens new tokens (or emitted EOS).  A
+ * round may overshoot; outputs are truncated to max_new_tokens and N counts kept
+ * tokens only.  out_tokens_host: HOST [batch, max_new_tokens]; out_lens: HOST
+ * [batch]; stats may be NULL. */
+sd_status specdec_generate(sd_ctx *ctx, const sd_params *params, int32_t max_new_tokens,
+                           int32_t *out_tokens_host, int32_t *out_lens, sd_stats *stats);
+
+/* The accept / residual-resample step on its own (Algorithm 1's tail, Appendix C):
+ * for each sequence b with K_b = K_per_seq_dev[b] candidates cand_dev[b, 0..K_b),
+ * n_out_dev[b] = number accepted, tok_out_dev[b] = y', accept_flags_dev[b, i] =
+ * outcome of the (i+1)-th accept test taken on its own (0 for i >= K_b).
+ * p_logits_dev: DEVICE fp32 [B, Kmax+1, V]; q_logits_dev: DEVICE fp32 [B, Kmax, V];
+ * cand_dev: DEVICE int32 [B, Kmax]; K_per_seq_dev: DEVICE int32 [B];
+ * outputs DEVICE int32 [B], int32 [B], uint8 [B, Kmax].  `stats_ws_dev` is DEVICE
+ * scratch of sd_accept_workspace_bytes(B, Kmax) bytes.  Enqueued on `hip_stream`;
+ * does not synchronise. */
+sd_status sd_accept_resample(const float *p_logits_dev, const float *q_logits_dev,
+                             const int32_t *cand_dev, const int32_t *K_per_seq_dev,
+                             int32_t B, int32_t Kmax, int32_t V, const sd_params *params,
+                             int32_t round_idx, void *stats_ws_dev, void *hip_stream,
+                             int32_t *n_out_dev, int32_t *tok_out_dev, uint8_t *accept_flags_dev);
+int64_t sd_accept_workspace_bytes(int32_t B, int32_t Kmax);
+
+/* Teacher-forced forward for parity checks and timing: ingest `n` tokens (HOST
+ * ids) of sequence `seq` into model `which` (0 = target, 1 = draft) at cache
+ * positions start .. start+n-1 (start <= that cache's current length; later
+ * positions are discarded first) and copy the n rows of fp32 logits [n, vocab]
+ * (and, if non-NULL, the final-RMSNorm hidden rows [n, d_model] as fp32) to HOST.
+ * n <= 32.  Leaves the cache length at start + n. */
+sd_status sd_forward(sd_ctx *ctx, int32_t which, int32_t seq, int32_t start, const int32_t *tokens_host,
+                     int32_t n, float *logits_host, float *hidden_host);
+
+/* Introspection of sequence state (HOST outs, any may be NULL): P = finalised
+ * tokens, cache lengths of target and draft, round index. */
+sd_status sd_seq_state(sd_ctx *ctx, int32_t seq, int32_t *P, int32_t *kv_len_target,
+                       int32_t *kv_len_draft, int32_t *round_idx);
+
+/* The fp32 rows the last round used (for decision replay): copies q_logits
+ * [K, vocab], p_logits [K+1, vocab] and the head's K-1 sigmoid outputs of
+ * sequence `seq` to HOST buffers (any may be NULL). */
+sd_status sd_last_round_rows(sd_ctx *ctx, int32_t seq, float *q_logits_host, float *p_logits_host,
+                             float *head_s_host);
+
+/* Per-launch timing of the weight-streaming GEMM kernels of the target pass.
+ * sd_profile_enable(ctx, every) brackets the GEMM launches of every `every`-th
+ * target layer (and the LM head) with HIP events from then on (0 = off).
+ * sd_profile_read sums, since the last read, the sampled launches' streamed weight
+ * bytes and durations per matrix kind (0 qkv, 1 o, 2 gate_up, 3 down, 4 lm_head):
+ * HOST arrays of 5. */
+sd_status sd_profile_enable(sd_ctx *ctx, int32_t every);
+sd_status sd_profile_read(sd_ctx *ctx, int64_t *launches, double *seconds, double *weight_bytes);
+
+/* The weight-streaming skinny GEMM on its own (the kernel the target pass over
+ * M = K+1 rows and the M = 1 draft steps spend their time in; Algorithm 2's
+ * "compute in parallel" step): Y[m, n] = sum_k X[m, k] * W[n, k], fp32 out.
+ * W: DEVICE [N, K] and X: DEVICE [M, K], both `dtype`; Y: DEVICE fp32 [M, N]; ws: DEVICE
+ * scratch of sd_gemm_workspace_bytes(...) bytes (per-K-slice partial sums, added in
+ * slice order).  1 <= M <= 160; for SD_BF16, K % 128 == 0 and N % 16 == 0, pointers
+ * 16-byte aligned.  Enqueued on `hip_stream`; does not synchronise. */
+sd_status sd_gemm_skinny(int32_t dtype, const void *W_dev, const void *X_dev, int32_t M, int32_t N, int32_t K,
+                         float *Y_dev, void *ws_dev, void *hip_stream);
+int64_t sd_gemm_workspace_bytes(int32_t dtype, int32_t M, int32_t N, int32_t K);
+
+const char *sd_strerror(sd_status s);
+const char *sd_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SPECDEC_H */

@@ -1,0 +1,384 @@
+// Causal attention of a block of query rows against the KV cache with grouped
+// queries (the target pass attends K+1 candidate positions at once; a draft step
+// attends 1 or 2).
+//
+// Cache layout (chosen for this kernel): keys  [seq, kv_head, max_seq, hd]
+//                                        values [seq, kv_head, hd, max_seq]  (transposed)
+// so that both MFMA operands below are 16-byte loads straight from HBM/L2 and the
+// probabilities never change lanes:
+//
+//   S^T = K Q^T : A operand = 16 keys x 32 d (a lane loads its key's row),
+//                 B operand = 32 d x 16 query vectors.  Result lane (qv = lane%16,
+//                 g = lane/16) holds scores of one query vector for 4 keys per tile.
+//                 The 16 rows of key tile t are the keys key0 + 16*(i/4) + 4t + i%4,
+//                 so after 4 tiles lane group g owns the 16 consecutive keys
+//                 key0 + 16g .. key0 + 16g + 15.
+//   O^T = V^T P^T: A operand = 16 d x 32 keys = two 16-byte loads of a transposed
+//                 value row; B operand = 32 keys x 16 query vectors = exactly the
+//                 registers the scores sit in (after exp and rounding to bf16).
+//
+// Query vectors of one (sequence, kv head) are the G = Hq/Hkv heads of every row of
+// the sequence's row group: up to 17 x 8 = 136 vectors share each streamed K/V tile.
+// Keys are split over workgroups and wavefronts; a second kernel merges the
+// (max, sum, O) partials in fixed order.
+#include "common.hpp"
+#include "kernels.hpp"
+
+#include <cstdlib>
+
+namespace sd {
+
+namespace {
+
+constexpr int SPL = 256;        // keys per workgroup
+constexpr int KB = 64;          // keys per inner block
+constexpr float NEG_BIG = -1.0e30f;
+
+__device__ __forceinline__ uint4 ld16(const bf16_t* p) { return *reinterpret_cast<const uint4*>(p); }
+__device__ __forceinline__ bf16x8 as_bf16x8(const uint4& v) {
+  union { uint4 u; bf16x8 b; } c;
+  c.u = v;
+  return c.b;
+}
+__device__ __forceinline__ uint32_t pack2(float lo, float hi) { return (uint32_t)f2bf(lo) | ((uint32_t)f2bf(hi) << 16); }
+
+// ------------------------------------------------------------------ MFMA kernel (bf16)
+template <int HD, int QTW>
+__global__ __launch_bounds__(256) void attn_mfma_k(const bf16_t* __restrict__ qbuf, const bf16_t* __restrict__ kcache,
+                                                   const bf16_t* __restrict__ vcache,
+                                                   const int32_t* __restrict__ row_seq,
+                                                   const int32_t* __restrict__ row_pos, float* __restrict__ scratch,
+                                                   int RS, int Hq, int Hkv, int max_seq, int QW, int NQG, int NSP) {
+  constexpr int DT = HD / 16;          // 16-wide tiles of the head dimension
+  constexpr int KS = HD / 32;          // MFMA k-steps of the score product
+  constexpr int STRIDE = HD + 4;       // floats per partial: O[HD], max, sum, pad
+  __shared__ int s_info[2];            // cache sequence id, kv_end of the group
+
+  const int kh = blockIdx.x / NQG, qg = blockIdx.x % NQG;
+  const int grp = blockIdx.y, c = blockIdx.z;
+  const int G = Hq / Hkv;
+  if (threadIdx.x == 0) {
+    int seq = -1, kv_end = 0;
+    for (int rr = 0; rr < RS; ++rr) {
+      const int m = grp * RS + rr;
+      if (row_seq[m] >= 0) {
+        seq = row_seq[m];
+        kv_end = max(kv_end, row_pos[m] + 1);
+      }
+    }
+    s_info[0] = seq;
+    s_info[1] = kv_end;
+  }
+  __syncthreads();
+  const int seq = s_info[0], kv_end = s_info[1];
+  if (seq < 0) return;
+
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int li = lane & 15, g = lane >> 4;
+  const int KW = 4 / QW;
+  const int qw = wave % QW, kw = wave / QW;
+  const int keys_per_wave = SPL / KW;
+  const int kbeg = c * SPL + kw * keys_per_wave;
+  if (kbeg >= kv_end) return;
+  const int kend = min(kbeg + keys_per_wave, kv_end);
+  const int sp = c * KW + kw;
+
+  const bf16_t* kbase = kcache + ((size_t)seq * Hkv + kh) * (size_t)max_seq * HD;
+  const bf16_t* vbase = vcache + ((size_t)seq * Hkv + kh) * (size_t)HD * max_seq;
+  const int QV = RS * G;
+  const float scale = rsqrtf((float)HD);
+
+  // this lane's query vector in each of the wave's tiles
+  uint4 qf[QTW][KS];
+  int limit[QTW], orow[QTW], ohead[QTW];
+#pragma unroll
+  for (int q = 0; q < QTW; ++q) {
+    const int qt = qg * (QW * QTW) + qw + QW * q;
+    const int qv = qt * 16 + li;
+    limit[q] = -1;
+    orow[q] = -1;
+    ohead[q] = 0;
+#pragma unroll
+    for (int j = 0; j < KS; ++j) qf[q][j] = uint4{0u, 0u, 0u, 0u};
+    if (qv < QV) {
+      const int rr = qv / G, gh = qv - rr * G;
+      const int m = grp * RS + rr;
+      if (row_seq[m] >= 0) {
+        limit[q] = row_pos[m];
+        orow[q] = m;
+        ohead[q] = kh * G + gh;
+        const bf16_t* qp = qbuf + ((size_t)m * Hq + ohead[q]) * HD + g * (HD / 4);
+#pragma unroll
+        for (int j = 0; j < KS; ++j) qf[q][j] = ld16(qp + j * 8);
+      }
+    }
+  }
+
+  floatx4 o[QTW][DT];
+  float mrun[QTW], lrun[QTW];
+#pragma unroll
+  for (int q = 0; q < QTW; ++q) {
+    mrun[q] = NEG_BIG;
+    lrun[q] = 0.f;
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt) o[q][dt] = floatx4{0.f, 0.f, 0.f, 0.f};
+  }
+
+  for (int key0 = kbeg; key0 < kend; key0 += KB) {
+    // ---- scores: 4 key tiles x QTW query tiles
+    floatx4 sacc[QTW][4];
+#pragma unroll
+    for (int q = 0; q < QTW; ++q)
+#pragma unroll
+      for (int kt = 0; kt < 4; ++kt) sacc[q][kt] = floatx4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int kt = 0; kt < 4; ++kt) {
+      const int key = key0 + 16 * (li >> 2) + 4 * kt + (li & 3);          // < max_seq (multiple of 64)
+      const bf16_t* kp = kbase + (size_t)key * HD + g * (HD / 4);
+      uint4 kf[KS];
+#pragma unroll
+      for (int j = 0; j < KS; ++j) kf[j] = ld16(kp + j * 8);
+#pragma unroll
+      for (int j = 0; j < KS; ++j)
+#pragma unroll
+        for (int q = 0; q < QTW; ++q)
+          sacc[q][kt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(kf[j]), as_bf16x8(qf[q][j]),
+                                                                sacc[q][kt], 0, 0, 0);
+    }
+    // ---- online softmax; lane (li, g) holds keys key0 + 16 g + 4 kt + r of query vector li
+    uint4 pf[QTW][2];
+#pragma unroll
+    for (int q = 0; q < QTW; ++q) {
+      float bmax = NEG_BIG;
+#pragma unroll
+      for (int kt = 0; kt < 4; ++kt)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const int key = key0 + 16 * g + 4 * kt + r;
+          const float s = sacc[q][kt][r] * scale;
+          sacc[q][kt][r] = s;
+          if (key <= limit[q]) bmax = fmaxf(bmax, s);
+        }
+      bmax = fmaxf(bmax, __shfl_xor(bmax, 16, WAVE));
+      bmax = fmaxf(bmax, __shfl_xor(bmax, 32, WAVE));
+      const float mnew = fmaxf(mrun[q], bmax);
+      const float alpha = __expf(mrun[q] - mnew);
+      float p[4][4];
+      float lsum = 0.f;
+#pragma unroll
+      for (int kt = 0; kt < 4; ++kt)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const int key = key0 + 16 * g + 4 * kt + r;
+          const float e = (key <= limit[q]) ? __expf(sacc[q][kt][r] - mnew) : 0.f;
+          p[kt][r] = e;
+          lsum += e;
+        }
+      lsum += __shfl_xor(lsum, 16, WAVE);
+      lsum += __shfl_xor(lsum, 32, WAVE);
+      lrun[q] = lrun[q] * alpha + lsum;
+      mrun[q] = mnew;
+#pragma unroll
+      for (int dt = 0; dt < DT; ++dt) o[q][dt] *= alpha;
+#pragma unroll
+      for (int u = 0; u < 2; ++u)
+        pf[q][u] = uint4{pack2(p[2 * u][0], p[2 * u][1]), pack2(p[2 * u][2], p[2 * u][3]),
+                         pack2(p[2 * u + 1][0], p[2 * u + 1][1]), pack2(p[2 * u + 1][2], p[2 * u + 1][3])};
+    }
+    // ---- O^T += V^T P^T
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt) {
+      const bf16_t* vp = vbase + (size_t)(dt * 16 + li) * max_seq + key0 + 16 * g;
+      const uint4 v0 = ld16(vp), v1 = ld16(vp + 8);
+#pragma unroll
+      for (int q = 0; q < QTW; ++q) {
+        o[q][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(v0), as_bf16x8(pf[q][0]), o[q][dt], 0, 0, 0);
+        o[q][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(v1), as_bf16x8(pf[q][1]), o[q][dt], 0, 0, 0);
+      }
+    }
+  }
+
+  // partials: lane (qv = li, d = 16 dt + 4 g + r)
+#pragma unroll
+  for (int q = 0; q < QTW; ++q) {
+    if (orow[q] < 0) continue;
+    float* dst = scratch + (((size_t)orow[q] * Hq + ohead[q]) * NSP + sp) * STRIDE;
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt) *reinterpret_cast<floatx4*>(dst + dt * 16 + 4 * g) = o[q][dt];
+    if (g == 0) {
+      dst[HD] = mrun[q];
+      dst[HD + 1] = lrun[q];
+    }
+  }
+}
+
+template <int HD>
+__global__ __launch_bounds__(HD) void attn_merge_k(const float* __restrict__ scratch, const int32_t* __restrict__ row_seq,
+                                                   const int32_t* __restrict__ row_pos, bf16_t* __restrict__ out, int RS,
+                                                   int Hq, int KW, int NSP) {
+  constexpr int STRIDE = HD + 4;
+  const int m = blockIdx.x, h = blockIdx.y, d = threadIdx.x;
+  bf16_t* dst = out + ((size_t)m * Hq + h) * HD + d;
+  if (row_seq[m] < 0) {
+    *dst = 0;
+    return;
+  }
+  const int grp = m / RS;
+  int kv_end = 0;
+  for (int rr = 0; rr < RS; ++rr) {
+    const int mm = grp * RS + rr;
+    if (row_seq[mm] >= 0) kv_end = max(kv_end, row_pos[mm] + 1);
+  }
+  const float* src = scratch + ((size_t)m * Hq + h) * NSP * STRIDE;
+  const int keys_per_wave = SPL / KW;
+  float mx = NEG_BIG;
+  int nsp = 0;
+  for (int sp = 0; sp < NSP; ++sp) {
+    const int kbeg = (sp / KW) * SPL + (sp % KW) * keys_per_wave;
+    if (kbeg >= kv_end) break;
+    mx = fmaxf(mx, src[sp * STRIDE + HD]);
+    nsp = sp + 1;
+  }
+  float num = 0.f, den = 0.f;
+  for (int sp = 0; sp < nsp; ++sp) {
+    const float w = __expf(src[sp * STRIDE + HD] - mx);
+    num = fmaf(w, src[sp * STRIDE + d], num);
+    den = fmaf(w, src[sp * STRIDE + HD + 1], den);
+  }
+  *dst = f2bf(den > 0.f ? num / den : 0.f);
+}
+
+// ------------------------------------------------------------------ plain kernel (any dtype)
+// One workgroup per (query head, row group); rows one after another; scores of the
+// whole prefix in LDS.  Used for fp32 models, where sizes are tiny.
+template <typename T>
+__global__ __launch_bounds__(256) void attn_plain_k(const T* __restrict__ qbuf, const T* __restrict__ kcache,
+                                                    const T* __restrict__ vcache, const int32_t* __restrict__ row_seq,
+                                                    const int32_t* __restrict__ row_pos, T* __restrict__ out, int RS,
+                                                    int Hq, int Hkv, int hd, int max_seq) {
+  extern __shared__ float sm[];
+  float* sc = sm;                       // [max_kv_len]
+  float* qs = sm + max_seq;             // [hd]
+  float* red = qs + hd;                 // [256]
+  const int h = blockIdx.x, grp = blockIdx.y;
+  const int kh = h / (Hq / Hkv);
+  const float scale = 1.0f / sqrtf((float)hd);
+  for (int rr = 0; rr < RS; ++rr) {
+    const int m = grp * RS + rr;
+    const int seq = row_seq[m];
+    T* dst = out + ((size_t)m * Hq + h) * hd;
+    if (seq < 0) {
+      for (int d = threadIdx.x; d < hd; d += 256) Elem<T>::st(dst + d, 0.f);
+      continue;
+    }
+    const int n = row_pos[m] + 1;
+    const T* kb = kcache + ((size_t)seq * Hkv + kh) * (size_t)max_seq * hd;
+    const T* vb = vcache + ((size_t)seq * Hkv + kh) * (size_t)hd * max_seq;
+    __syncthreads();
+    for (int d = threadIdx.x; d < hd; d += 256) qs[d] = Elem<T>::ld(qbuf + ((size_t)m * Hq + h) * hd + d);
+    __syncthreads();
+    float mx = NEG_BIG;
+    for (int key = threadIdx.x; key < n; key += 256) {
+      float s = 0.f;
+      for (int d = 0; d < hd; ++d) s = fmaf(qs[d], Elem<T>::ld(kb + (size_t)key * hd + d), s);
+      s *= scale;
+      sc[key] = s;
+      mx = fmaxf(mx, s);
+    }
+    mx = block_max(mx, red);
+    float l = 0.f;
+    for (int key = threadIdx.x; key < n; key += 256) {
+      const float e = expf(sc[key] - mx);
+      sc[key] = e;
+      l += e;
+    }
+    l = block_sum(l, red);
+    // value product: thread (d, part) sums a strided subset of keys, parts combined in order
+    const int parts = 256 / hd;                         // hd in {32, 64, 128}
+    const int d = threadIdx.x % hd, part = threadIdx.x / hd;
+    float acc = 0.f;
+    if (part < parts)
+      for (int key = part; key < n; key += parts) acc = fmaf(sc[key], Elem<T>::ld(vb + (size_t)d * max_seq + key), acc);
+    red[threadIdx.x] = acc;
+    __syncthreads();
+    if (threadIdx.x < hd) {
+      float t = 0.f;
+      for (int p = 0; p < parts; ++p) t += red[p * hd + threadIdx.x];
+      Elem<T>::st(dst + threadIdx.x, t / l);
+    }
+  }
+}
+
+struct MfmaShape { int QW, QTW, NQG; };
+
+MfmaShape mfma_shape(int RS, int G) {
+  const int n_qt = (RS * G + 15) / 16;
+  MfmaShape s;
+  if (n_qt <= 1) s = {1, 1, 1};
+  else if (n_qt <= 2) s = {2, 1, 1};
+  else if (n_qt <= 4) s = {4, 1, 1};
+  else s = {4, 2, (n_qt + 7) / 8};
+  return s;
+}
+
+bool use_plain(int dtype) {
+  static const bool forced = std::getenv("SD_ATTN_PLAIN") != nullptr;
+  return dtype == DT_F32 || forced;
+}
+
+}  // namespace
+
+size_t attn_scratch_floats(int M, int Hq, int hd, int max_seq) {
+  const int nsp = ((max_seq + SPL - 1) / SPL) * 4;
+  return (size_t)M * Hq * nsp * (hd + 4);
+}
+
+hipError_t launch_attention(hipStream_t st, int dtype, const void* qbuf, const void* kcache, const void* vcache,
+                            const RowPlan& rows, void* out, float* scratch, int M, int RS, int Hq, int Hkv, int hd,
+                            int max_seq, int max_kv_len) {
+  if (M < 1 || M > MAX_ROWS || RS < 1 || M % RS != 0 || Hq < 1 || Hkv < 1 || Hq % Hkv != 0 || max_kv_len < 1 ||
+      max_kv_len > max_seq || !qbuf || !kcache || !vcache || !out || !rows.seq || !rows.pos)
+    return hipErrorInvalidValue;
+  const int ngroups = M / RS;
+  if (use_plain(dtype)) {
+    if (hd != 32 && hd != 64 && hd != 128) return hipErrorInvalidValue;
+    const size_t lds = ((size_t)max_seq + hd + 256) * sizeof(float);
+    if (lds > 64 * 1024) return hipErrorInvalidValue;
+    if (dtype == DT_F32)
+      hipLaunchKernelGGL(attn_plain_k<float>, dim3(Hq, ngroups), dim3(256), lds, st, (const float*)qbuf,
+                         (const float*)kcache, (const float*)vcache, rows.seq, rows.pos, (float*)out, RS, Hq, Hkv, hd,
+                         max_seq);
+    else
+      hipLaunchKernelGGL(attn_plain_k<bf16_t>, dim3(Hq, ngroups), dim3(256), lds, st, (const bf16_t*)qbuf,
+                         (const bf16_t*)kcache, (const bf16_t*)vcache, rows.seq, rows.pos, (bf16_t*)out, RS, Hq, Hkv,
+                         hd, max_seq);
+    return hipGetLastError();
+  }
+  if (dtype != DT_BF16 || (hd != 64 && hd != 128) || max_seq % KB != 0 || !scratch) return hipErrorInvalidValue;
+  const MfmaShape sh = mfma_shape(RS, Hq / Hkv);
+  const int KW = 4 / sh.QW;
+  const int nsplit = (max_kv_len + SPL - 1) / SPL;
+  const int NSP = ((max_seq + SPL - 1) / SPL) * 4;
+  const dim3 grid(Hkv * sh.NQG, ngroups, nsplit);
+  const bf16_t *q = (const bf16_t*)qbuf, *k = (const bf16_t*)kcache, *v = (const bf16_t*)vcache;
+#define SD_ATTN_LAUNCH(HD_, QTW_)                                                                              \
+  hipLaunchKernelGGL((attn_mfma_k<HD_, QTW_>), grid, dim3(256), 0, st, q, k, v, rows.seq, rows.pos, scratch, RS, \
+                     Hq, Hkv, max_seq, sh.QW, sh.NQG, NSP)
+  if (hd == 128) {
+    if (sh.QTW == 1) SD_ATTN_LAUNCH(128, 1); else SD_ATTN_LAUNCH(128, 2);
+  } else {
+    if (sh.QTW == 1) SD_ATTN_LAUNCH(64, 1); else SD_ATTN_LAUNCH(64, 2);
+  }
+#undef SD_ATTN_LAUNCH
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  if (hd == 128)
+    hipLaunchKernelGGL(attn_merge_k<128>, dim3(M, Hq), dim3(128), 0, st, scratch, rows.seq, rows.pos, (bf16_t*)out,
+                       RS, Hq, KW, NSP);
+  else
+    hipLaunchKernelGGL(attn_merge_k<64>, dim3(M, Hq), dim3(64), 0, st, scratch, rows.seq, rows.pos, (bf16_t*)out, RS,
+                       Hq, KW, NSP);
+  return hipGetLastError();
+}
+
+}  // namespace sd

@@ -1,0 +1,218 @@
+// Small fused kernels around the weight-streaming GEMMs.  Each consumes the GEMM's
+// per-K-slice partial sums (added in slice order, so results are reproducible) and
+// fuses the next elementwise step of the Llama-style decoder layer: RMSNorm,
+// rotary embedding + KV-cache append, SiLU * up, residual add, head activation.
+#include "common.hpp"
+#include "kernels.hpp"
+
+namespace sd {
+
+namespace {
+
+constexpr int EW_THREADS = 256;
+
+template <typename T>
+__global__ __launch_bounds__(EW_THREADS) void embed_norm_k(const T* __restrict__ emb, const T* __restrict__ g,
+                                                           float eps, const int32_t* __restrict__ tok,
+                                                           float* __restrict__ x, T* __restrict__ xn, int d,
+                                                           int vocab) {
+  __shared__ float red[EW_THREADS / 64];
+  const int m = blockIdx.x;
+  int t = tok[m];
+  t = t < 0 ? 0 : (t >= vocab ? vocab - 1 : t);
+  const T* e = emb + (size_t)t * d;
+  float ss = 0.f;
+  for (int i = threadIdx.x; i < d; i += EW_THREADS) {
+    const float v = Elem<T>::ld(e + i);
+    x[(size_t)m * d + i] = v;
+    ss = fmaf(v, v, ss);
+  }
+  ss = block_sum(ss, red);
+  const float inv = 1.0f / sqrtf(ss / (float)d + eps);
+  for (int i = threadIdx.x; i < d; i += EW_THREADS)
+    Elem<T>::st(xn + (size_t)m * d + i, x[(size_t)m * d + i] * inv * Elem<T>::ld(g + i));
+}
+
+template <typename T>
+__global__ __launch_bounds__(EW_THREADS) void add_norm_k(const float* __restrict__ part, int S,
+                                                         const T* __restrict__ g, float eps,
+                                                         float* __restrict__ x, T* __restrict__ xn, int M,
+                                                         int d) {
+  __shared__ float red[EW_THREADS / 64];
+  const int m = blockIdx.x;
+  float ss = 0.f;
+  for (int i = threadIdx.x; i < d; i += EW_THREADS) {
+    float v = x[(size_t)m * d + i];
+    for (int s = 0; s < S; ++s) v += part[((size_t)s * M + m) * d + i];
+    x[(size_t)m * d + i] = v;
+    ss = fmaf(v, v, ss);
+  }
+  ss = block_sum(ss, red);
+  const float inv = 1.0f / sqrtf(ss / (float)d + eps);
+  for (int i = threadIdx.x; i < d; i += EW_THREADS)
+    Elem<T>::st(xn + (size_t)m * d + i, x[(size_t)m * d + i] * inv * Elem<T>::ld(g + i));
+}
+
+// One block per (row, head slot): slots [0, Hq) are query heads, [Hq, Hq+Hkv) key
+// heads, [Hq+Hkv, Hq+2Hkv) value heads.
+template <typename T>
+__global__ __launch_bounds__(64) void rope_kv_k(const float* __restrict__ part, int S,
+                                                const int32_t* __restrict__ row_seq,
+                                                const int32_t* __restrict__ row_pos,
+                                                const float* __restrict__ cos_sin, T* __restrict__ qbuf,
+                                                T* __restrict__ kcache, T* __restrict__ vcache, int M, int Hq,
+                                                int Hkv, int hd, int max_seq) {
+  const int m = blockIdx.x, slot = blockIdx.y;
+  const int seq = row_seq[m];
+  if (seq < 0) return;
+  const int pos = row_pos[m];
+  const int ncols = (Hq + 2 * Hkv) * hd;
+  const int half = hd >> 1;
+  const float* p0 = part + (size_t)m * ncols + (size_t)slot * hd;
+  const size_t sstride = (size_t)M * ncols;
+  if (slot < Hq + Hkv) {
+    for (int i = threadIdx.x; i < half; i += 64) {
+      float a = 0.f, b = 0.f;
+      for (int s = 0; s < S; ++s) {
+        a += p0[s * sstride + i];
+        b += p0[s * sstride + i + half];
+      }
+      const float c = cos_sin[((size_t)pos * half + i) * 2], sn = cos_sin[((size_t)pos * half + i) * 2 + 1];
+      const float ra = a * c - b * sn, rb = b * c + a * sn;
+      if (slot < Hq) {
+        T* q = qbuf + ((size_t)m * Hq + slot) * hd;
+        Elem<T>::st(q + i, ra);
+        Elem<T>::st(q + i + half, rb);
+      } else {
+        T* k = kcache + (((size_t)seq * Hkv + (slot - Hq)) * max_seq + pos) * hd;
+        Elem<T>::st(k + i, ra);
+        Elem<T>::st(k + i + half, rb);
+      }
+    }
+  } else {
+    T* v = vcache + ((size_t)seq * Hkv + (slot - Hq - Hkv)) * hd * (size_t)max_seq + pos;
+    for (int i = threadIdx.x; i < hd; i += 64) {
+      float a = 0.f;
+      for (int s = 0; s < S; ++s) a += p0[s * sstride + i];
+      Elem<T>::st(v + (size_t)i * max_seq, a);            // value cache is stored transposed: [hd, max_seq]
+    }
+  }
+}
+
+template <typename T>
+__global__ __launch_bounds__(EW_THREADS) void silu_mul_k(const float* __restrict__ part, int S,
+                                                         T* __restrict__ act, int M, int ffn) {
+  const int m = blockIdx.y;
+  const int f = blockIdx.x * EW_THREADS + threadIdx.x;
+  if (f >= ffn) return;
+  float g = 0.f, u = 0.f;
+  for (int s = 0; s < S; ++s) {
+    const float* p = part + ((size_t)s * M + m) * (2 * (size_t)ffn);
+    g += p[f];
+    u += p[ffn + f];
+  }
+  Elem<T>::st(act + (size_t)m * ffn + f, g / (1.0f + expf(-g)) * u);
+}
+
+__global__ __launch_bounds__(EW_THREADS) void reduce_rows_k(const float* __restrict__ part, int S,
+                                                            float* __restrict__ out, int64_t ldo, int M,
+                                                            int N) {
+  const int m = blockIdx.y;
+  const int n = blockIdx.x * EW_THREADS + threadIdx.x;
+  if (n >= N) return;
+  float v = 0.f;
+  for (int s = 0; s < S; ++s) v += part[((size_t)s * M + m) * N + n];
+  out[(size_t)m * ldo + n] = v;
+}
+
+template <typename T>
+__global__ __launch_bounds__(EW_THREADS) void head_act_k(const float* __restrict__ part, int S,
+                                                         const T* __restrict__ bias, const T* __restrict__ z_in,
+                                                         const int* __restrict__ z_in_rows, T* __restrict__ z_out,
+                                                         int residual, int M, int n) {
+  const int m = blockIdx.y;
+  const int i = blockIdx.x * EW_THREADS + threadIdx.x;
+  if (i >= n) return;
+  float a = Elem<T>::ld(bias + i);
+  for (int s = 0; s < S; ++s) a += part[((size_t)s * M + m) * n + i];
+  a = a / (1.0f + expf(-a));
+  if (residual) a += Elem<T>::ld(z_in + (size_t)(z_in_rows ? z_in_rows[m] : m) * n + i);
+  Elem<T>::st(z_out + (size_t)m * n + i, a);
+}
+
+inline bool bad_rows(int M) { return M < 1 || M > MAX_ROWS; }
+
+}  // namespace
+
+#define SD_DISPATCH_T(dtype, CALL_F32, CALL_BF16) \
+  if ((dtype) == DT_F32) { CALL_F32; } else if ((dtype) == DT_BF16) { CALL_BF16; } else return hipErrorInvalidValue;
+
+hipError_t launch_embed_norm(hipStream_t st, int dtype, const void* emb, const void* g, float eps,
+                             const int32_t* tok, float* x, void* xn, int M, int d, int vocab) {
+  if (bad_rows(M) || d < 1 || !emb || !g || !tok || !x || !xn) return hipErrorInvalidValue;
+  SD_DISPATCH_T(dtype,
+                hipLaunchKernelGGL(embed_norm_k<float>, dim3(M), dim3(EW_THREADS), 0, st, (const float*)emb,
+                                   (const float*)g, eps, tok, x, (float*)xn, d, vocab),
+                hipLaunchKernelGGL(embed_norm_k<bf16_t>, dim3(M), dim3(EW_THREADS), 0, st, (const bf16_t*)emb,
+                                   (const bf16_t*)g, eps, tok, x, (bf16_t*)xn, d, vocab));
+  return hipGetLastError();
+}
+
+hipError_t launch_add_norm(hipStream_t st, int dtype, const float* part, int S, const void* g, float eps,
+                           float* x, void* xn, int M, int d) {
+  if (bad_rows(M) || d < 1 || S < 1 || !part || !g || !x || !xn) return hipErrorInvalidValue;
+  SD_DISPATCH_T(dtype,
+                hipLaunchKernelGGL(add_norm_k<float>, dim3(M), dim3(EW_THREADS), 0, st, part, S,
+                                   (const float*)g, eps, x, (float*)xn, M, d),
+                hipLaunchKernelGGL(add_norm_k<bf16_t>, dim3(M), dim3(EW_THREADS), 0, st, part, S,
+                                   (const bf16_t*)g, eps, x, (bf16_t*)xn, M, d));
+  return hipGetLastError();
+}
+
+hipError_t launch_rope_kv(hipStream_t st, int dtype, const float* part, int S, const RowPlan& rows,
+                          const float* cos_sin, void* qbuf, void* kcache, void* vcache, int M, int Hq,
+                          int Hkv, int hd, int max_seq) {
+  if (bad_rows(M) || S < 1 || Hq < 1 || Hkv < 1 || (hd & 1) || !part || !cos_sin || !qbuf || !kcache || !vcache)
+    return hipErrorInvalidValue;
+  const dim3 grid(M, Hq + 2 * Hkv);
+  SD_DISPATCH_T(dtype,
+                hipLaunchKernelGGL(rope_kv_k<float>, grid, dim3(64), 0, st, part, S, rows.seq, rows.pos,
+                                   cos_sin, (float*)qbuf, (float*)kcache, (float*)vcache, M, Hq, Hkv, hd,
+                                   max_seq),
+                hipLaunchKernelGGL(rope_kv_k<bf16_t>, grid, dim3(64), 0, st, part, S, rows.seq, rows.pos,
+                                   cos_sin, (bf16_t*)qbuf, (bf16_t*)kcache, (bf16_t*)vcache, M, Hq, Hkv, hd,
+                                   max_seq));
+  return hipGetLastError();
+}
+
+hipError_t launch_silu_mul(hipStream_t st, int dtype, const float* part, int S, void* act, int M, int ffn) {
+  if (bad_rows(M) || S < 1 || ffn < 1 || !part || !act) return hipErrorInvalidValue;
+  const dim3 grid((ffn + EW_THREADS - 1) / EW_THREADS, M);
+  SD_DISPATCH_T(dtype,
+                hipLaunchKernelGGL(silu_mul_k<float>, grid, dim3(EW_THREADS), 0, st, part, S, (float*)act, M, ffn),
+                hipLaunchKernelGGL(silu_mul_k<bf16_t>, grid, dim3(EW_THREADS), 0, st, part, S, (bf16_t*)act, M,
+                                   ffn));
+  return hipGetLastError();
+}
+
+hipError_t launch_reduce_rows(hipStream_t st, const float* part, int S, float* out, int64_t ldo, int M, int N) {
+  if (bad_rows(M) || S < 1 || N < 1 || ldo < N || !part || !out) return hipErrorInvalidValue;
+  const dim3 grid((N + EW_THREADS - 1) / EW_THREADS, M);
+  hipLaunchKernelGGL(reduce_rows_k, grid, dim3(EW_THREADS), 0, st, part, S, out, ldo, M, N);
+  return hipGetLastError();
+}
+
+hipError_t launch_head_act(hipStream_t st, int dtype, const float* part, int S, const void* bias,
+                           const void* z_in, const int* z_in_rows, void* z_out, int residual, int M, int n) {
+  if (bad_rows(M) || S < 1 || n < 1 || !part || !bias || !z_out || (residual && !z_in)) return hipErrorInvalidValue;
+  const dim3 grid((n + EW_THREADS - 1) / EW_THREADS, M);
+  SD_DISPATCH_T(dtype,
+                hipLaunchKernelGGL(head_act_k<float>, grid, dim3(EW_THREADS), 0, st, part, S, (const float*)bias,
+                                   (const float*)z_in, z_in_rows, (float*)z_out, residual, M, n),
+                hipLaunchKernelGGL(head_act_k<bf16_t>, grid, dim3(EW_THREADS), 0, st, part, S,
+                                   (const bf16_t*)bias, (const bf16_t*)z_in, z_in_rows, (bf16_t*)z_out, residual,
+                                   M, n));
+  return hipGetLastError();
+}
+
+}  // namespace sd

@@ -1,0 +1,107 @@
+// Host-side launchers of the HIP kernels.  Every launcher validates the shapes the
+// kernel and its grid assume and returns hipErrorInvalidValue instead of launching
+// when they do not hold.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace sd {
+
+enum { DT_F32 = 0, DT_BF16 = 1 };
+constexpr int MAX_ROWS = 160;          // most activation rows one forward call carries
+
+// ---------------------------------------------------------------- skinny GEMM
+// part[s, m, n] = sum over the s-th K-slice of X[m, :] * W[n, :]   (fp32)
+// W: [N, K] row-major in dtype; X: [M, K] rows (row stride ldx elements) in dtype,
+// optionally gathered through xrow (device int32 [M], may be null).
+// The number of K-slices is gemm_splits(dtype, M, N, K); consumers add the slices
+// in slice order.
+int gemm_splits(int dtype, int M, int N, int K);
+hipError_t launch_gemm(hipStream_t st, int dtype, const void* W, const void* X, int ldx, const int* xrow,
+                       float* part, int M, int N, int K);
+
+// ---------------------------------------------------------------- row plans
+struct RowPlan {           // device arrays, one entry per activation row
+  int32_t* seq;            // sequence of the row, -1 = padding row
+  int32_t* pos;            // absolute position of the row's token
+  int32_t* tok;            // token id
+};
+
+// ---------------------------------------------------------------- elementwise
+// x[m,:] = E[tok[m],:]; xn[m,:] = rmsnorm(x[m,:]) * g
+hipError_t launch_embed_norm(hipStream_t st, int dtype, const void* emb, const void* g, float eps,
+                             const int32_t* tok, float* x, void* xn, int M, int d, int vocab);
+// x[m,:] += sum_s part[s,m,:]; xn[m,:] = rmsnorm(x[m,:]) * g
+hipError_t launch_add_norm(hipStream_t st, int dtype, const float* part, int S, const void* g, float eps,
+                           float* x, void* xn, int M, int d);
+// q,k,v = sum_s part[s,m,:]; rotary embedding on q,k at pos[m]; q -> qbuf [M, Hq*hd];
+// k -> kcache[seq, kvh, pos, :]; v -> vcache[seq, kvh, :, pos] (transposed), rows with seq < 0 skipped
+hipError_t launch_rope_kv(hipStream_t st, int dtype, const float* part, int S, const RowPlan& rows,
+                          const float* cos_sin, void* qbuf, void* kcache, void* vcache, int M, int Hq,
+                          int Hkv, int hd, int max_seq);
+// act[m,f] = silu(sum_s part[s,m,f]) * (sum_s part[s,m,ffn+f])
+hipError_t launch_silu_mul(hipStream_t st, int dtype, const float* part, int S, void* act, int M, int ffn);
+// out[m*ldo + n] = sum_s part[s,m,n]     (fp32 logits rows)
+hipError_t launch_reduce_rows(hipStream_t st, const float* part, int S, float* out, int64_t ldo, int M, int N);
+// z_out[m,:] = silu(sum_s part + b) (+ z_in when residual)       (acceptance head hidden layer)
+hipError_t launch_head_act(hipStream_t st, int dtype, const float* part, int S, const void* bias,
+                           const void* z_in, const int* z_in_rows, void* z_out, int residual, int M, int n);
+
+// ---------------------------------------------------------------- attention
+// out[m, h*hd:(h+1)*hd] = softmax_j<=pos[m]( q[m,h,:] . K[seq,kvh,j,:] / sqrt(hd) ) V
+// Rows come in groups of RS consecutive rows that belong to one sequence (padding
+// rows have seq < 0).  `scratch` holds split partials: attn_scratch_floats(...) floats.
+// max_kv_len: upper bound on pos + 1 over all rows (sizes the grid).
+size_t attn_scratch_floats(int M, int Hq, int hd, int max_seq);
+hipError_t launch_attention(hipStream_t st, int dtype, const void* qbuf, const void* kcache,
+                            const void* vcache, const RowPlan& rows, void* out, float* scratch, int M,
+                            int RS, int Hq, int Hkv, int hd, int max_seq, int max_kv_len);
+
+// ---------------------------------------------------------------- sampling / accept
+struct SeqState {          // device arrays, one entry per sequence unless noted
+  int32_t* P;              // finalised tokens
+  int32_t* kv_t;           // target cache length
+  int32_t* kv_d;           // draft cache length
+  int32_t* K;              // candidates drawn so far this round
+  int32_t* kcap;           // candidate cap of this round
+  int32_t* stopped;        // draft loop ended
+  float* p_hat;            // cumulative predicted acceptance
+  int32_t* cand;           // [B, 32] y_1..y_K
+  int32_t* n_acc;          // accepted candidates
+  int32_t* y_new;          // correction / bonus token
+  int32_t* tokens;         // [B, max_seq] finalised tokens
+  float* head_s;           // [B, 32] head outputs used this round
+  uint8_t* flags;          // [B, 32] accept-test outcomes
+  int32_t* round;          // round index
+  int32_t* last_row;       // activation row holding the sequence's newest token
+  int32_t* err;            // [1] sticky: non-finite logits seen
+  int32_t* active;         // 0: the sequence sits this round out (finished)
+};
+
+struct DecodeParams { float h, temperature; int greedy, eos_id; uint64_t seed; };
+
+hipError_t launch_begin_round(hipStream_t st, const SeqState& s, int B, int k_max, int max_seq);
+hipError_t launch_plan_draft(hipStream_t st, const SeqState& s, const RowPlan& rows, int B, int step,
+                             int max_seq);
+hipError_t launch_plan_verify(hipStream_t st, const SeqState& s, const RowPlan& rows, int B, int k_max,
+                              int max_seq);
+// draw y_i from the draft logits row, update p_hat with the head's logit, apply the stop rule
+hipError_t launch_sample_stop(hipStream_t st, int dtype, const SeqState& s, const float* q_logits,
+                              int64_t ld_seq, const void* z, const int* z_rows, int z_dim, const void* w_last,
+                              const void* b_last, int have_head, const DecodeParams& p, int B, int V,
+                              int step);
+// softmax statistics of the live rows of a [B, rows_per_seq, V] logits array (row j of
+// sequence b is live when j < K[b] + extra): stats[row] = {max, sum exp((l-max)/T), argmax, 0}
+hipError_t launch_row_stats(hipStream_t st, const float* logits, int rows_per_seq, int extra, const int32_t* K,
+                            int B, int V, float temperature, float* stats, int32_t* err);
+// accept tests, n, and the residual / bonus sample y' for every sequence
+hipError_t launch_accept(hipStream_t st, const float* p_logits, const float* q_logits, const float* p_stats,
+                         const float* q_stats, const int32_t* cand, int cand_ld, const int32_t* K,
+                         const int32_t* round, int round_const, const DecodeParams& p, int B, int Kmax,
+                         int V, int32_t* n_out, int32_t* tok_out, uint8_t* flags, int flags_ld);
+// append y_1..y_n, y' to the token history and roll both cache lengths back
+// and pack {K, n, y', p_hat, cand[32], P, kv_t, kv_d, err} (40 ints per sequence) for the host
+hipError_t launch_commit(hipStream_t st, const SeqState& s, int32_t* result, int B, int max_seq);
+constexpr int RESULT_INTS = 40;
+
+}  // namespace sd

@@ -1,0 +1,422 @@
+// Device-resident control of a round (Algorithm 2): row plans for the draft steps
+// and the target pass, the draft sample + acceptance-head stop rule, the softmax /
+// accept / residual-resample step (Algorithm 1's tail, Appendix C), and the commit
+// that appends the new tokens and rolls both KV caches back.
+//
+// A sample from non-negative weights f with one uniform u is the inverse CDF in
+// index order: the first v whose running sum exceeds u * total.  The running sum
+// is taken in a fixed order (each of 1024 threads sums one contiguous chunk left to
+// right, chunk totals are scanned in thread order), so a draw never depends on
+// scheduling.
+#include "common.hpp"
+#include "kernels.hpp"
+
+namespace sd {
+
+namespace {
+
+constexpr int SB = 1024;            // threads of the vocab-wide kernels
+constexpr int CAND_LD = 32;         // row stride of the per-sequence candidate arrays
+constexpr int RES_LD = 40;          // ints per sequence in the packed round result
+
+struct ArgMax { float v; int i; };
+
+__device__ __forceinline__ ArgMax better(ArgMax a, ArgMax b) {
+  return (b.v > a.v || (b.v == a.v && b.i < a.i)) ? b : a;      // ties go to the lowest id
+}
+
+// Block-wide argmax (lowest index among equal maxima).  sh: SB/64 floats + SB/64 ints.
+__device__ ArgMax block_argmax(ArgMax a, float* shv, int* shi) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    ArgMax b{__shfl_xor(a.v, o, WAVE), __shfl_xor(a.i, o, WAVE)};
+    a = better(a, b);
+  }
+  const int w = threadIdx.x >> 6, nw = blockDim.x >> 6;
+  if ((threadIdx.x & 63) == 0) { shv[w] = a.v; shi[w] = a.i; }
+  __syncthreads();
+  ArgMax r{shv[0], shi[0]};
+  for (int k = 1; k < nw; ++k) r = better(r, ArgMax{shv[k], shi[k]});
+  __syncthreads();
+  return r;
+}
+
+// Inverse-CDF draw over v in [0, V) with weight f(v) >= 0; returns -1 when the total
+// mass is not positive.  sh_incl: SB floats, sh_w: SB/64 floats, sh_res: 1 int.
+template <typename F>
+__device__ int block_sample(F f, int V, float u, float* sh_incl, float* sh_w, int* sh_res) {
+  const int t = threadIdx.x, lane = t & 63, w = t >> 6;
+  const int C = (V + SB - 1) / SB;
+  const int v0 = min(t * C, V), v1 = min(v0 + C, V);
+  float local = 0.f;
+  for (int v = v0; v < v1; ++v) local += f(v);
+  float s = local;
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    const float n = __shfl_up(s, o, WAVE);
+    if (lane >= o) s += n;
+  }
+  if (lane == 63) sh_w[w] = s;
+  if (t == 0) *sh_res = -1;
+  __syncthreads();
+  float off = 0.f;
+  for (int k = 0; k < w; ++k) off += sh_w[k];
+  const float incl = off + s;
+  sh_incl[t] = incl;
+  __syncthreads();
+  const float total = sh_incl[SB - 1];
+  if (!(total > 0.f)) return -1;
+  const float target = u * total;
+  const float excl = t == 0 ? 0.f : sh_incl[t - 1];
+  if (excl <= target && target < incl) {
+    float run = excl;
+    int pick = -1, last_pos = -1;
+    for (int v = v0; v < v1; ++v) {
+      const float fv = f(v);
+      run += fv;
+      if (fv > 0.f) last_pos = v;
+      if (run > target) { pick = v; break; }
+    }
+    *sh_res = pick >= 0 ? pick : last_pos;
+  }
+  __syncthreads();
+  int res = *sh_res;
+  if (res < 0) {                      // rounding left no bucket: largest v with mass
+    int best = -1;
+    for (int v = v0; v < v1; ++v)
+      if (f(v) > 0.f) best = v;
+    __syncthreads();
+    atomicMax(sh_res, best);
+    __syncthreads();
+    res = *sh_res;
+  }
+  return res;
+}
+
+// ------------------------------------------------------------------ round bookkeeping
+__global__ void begin_round_k(SeqState s, int B, int k_max, int max_seq) {
+  const int b = blockIdx.x * blockDim.x + threadIdx.x;
+  if (b >= B) return;
+  s.K[b] = 0;
+  s.stopped[b] = s.active[b] ? 0 : 1;
+  s.p_hat[b] = 1.0f;
+  s.kcap[b] = min(k_max, max_seq - s.P[b] - 1);
+}
+
+// Draft step `step` (1-based): 2 row slots per sequence.  Step 1 ingests the 1 or 2
+// finalised tokens the draft cache has not seen; later steps ingest y_{step-1}.
+__global__ void plan_draft_k(SeqState s, RowPlan rows, int B, int step, int max_seq) {
+  const int b = blockIdx.x * blockDim.x + threadIdx.x;
+  if (b >= B) return;
+  const int m0 = 2 * b;
+  rows.seq[m0] = rows.seq[m0 + 1] = -1;
+  rows.pos[m0] = rows.pos[m0 + 1] = 0;
+  rows.tok[m0] = rows.tok[m0 + 1] = 0;
+  s.last_row[b] = m0;
+  if (s.stopped[b]) return;
+  const int P = s.P[b];
+  if (step == 1) {
+    const int kv = s.kv_d[b];
+    const int cnt = min(max(P - kv, 1), 2);
+    for (int j = 0; j < cnt; ++j) {
+      const int pos = P - cnt + j;
+      rows.seq[m0 + j] = b;
+      rows.pos[m0 + j] = pos;
+      rows.tok[m0 + j] = s.tokens[(size_t)b * max_seq + pos];
+    }
+    s.last_row[b] = m0 + cnt - 1;
+    s.kv_d[b] = P;
+  } else {
+    const int pos = P + step - 2;
+    rows.seq[m0] = b;
+    rows.pos[m0] = pos;
+    rows.tok[m0] = s.cand[b * CAND_LD + step - 2];
+    s.kv_d[b] = pos + 1;
+  }
+}
+
+// Target pass: k_max + 1 row slots per sequence holding x_last, y_1 .. y_K.
+__global__ void plan_verify_k(SeqState s, RowPlan rows, int B, int k_max, int max_seq) {
+  const int b = blockIdx.x;
+  const int j = threadIdx.x;
+  if (b >= B || j > k_max) return;
+  const int m = b * (k_max + 1) + j;
+  const int P = s.P[b], K = s.K[b];
+  if (j <= K && s.active[b]) {
+    rows.seq[m] = b;
+    rows.pos[m] = P - 1 + j;
+    rows.tok[m] = j == 0 ? s.tokens[(size_t)b * max_seq + P - 1] : s.cand[b * CAND_LD + j - 1];
+  } else {
+    rows.seq[m] = -1;
+    rows.pos[m] = 0;
+    rows.tok[m] = 0;
+  }
+}
+
+// ------------------------------------------------------------------ draft sample + stop rule
+template <typename T>
+__global__ __launch_bounds__(SB) void sample_stop_k(SeqState s, const float* __restrict__ q_logits, int64_t ld_seq,
+                                                    const T* __restrict__ z, const int* __restrict__ z_rows, int z_dim,
+                                                    const T* __restrict__ w_last, const T* __restrict__ b_last,
+                                                    int have_head, DecodeParams p, int V, int step) {
+  __shared__ float sh_incl[SB];
+  __shared__ float sh_w[SB / 64];
+  __shared__ int sh_i[SB / 64];
+  __shared__ int sh_res;
+  const int b = blockIdx.x;
+  if (s.stopped[b]) return;
+  const float* l = q_logits + (size_t)b * ld_seq + (size_t)(step - 1) * V;
+
+  // row maximum (and argmax), non-finite check
+  ArgMax am{-INFINITY, 0x7fffffff};
+  bool bad = false;
+  for (int v = threadIdx.x; v < V; v += SB) {
+    const float x = l[v];
+    bad |= !isfinite(x);
+    am = better(am, ArgMax{x, v});
+  }
+  am = block_argmax(am, sh_w, sh_i);
+  if (bad) atomicOr(s.err, 1);
+
+  int y;
+  if (p.greedy) {
+    y = am.i;
+  } else {
+    const float mx = am.v, inv_t = 1.0f / p.temperature;
+    const float u = philox_uniform(p.seed, (uint32_t)step, (uint32_t)s.round[b], (uint32_t)b, STREAM_DRAFT);
+    y = block_sample([&](int v) { return expf((l[v] - mx) * inv_t); }, V, u, sh_incl, sh_w, &sh_res);
+    if (y < 0) y = am.i;                // only reachable with non-finite logits
+  }
+
+  // acceptance head: last (linear) layer, sigmoid, cumulative product (nothing at step 1)
+  float dot = 0.f;
+  if (have_head && step > 1) {
+    const T* zr = z + (size_t)(z_rows ? z_rows[b] : b) * z_dim;
+    for (int i = threadIdx.x; i < z_dim; i += SB) dot = fmaf(Elem<T>::ld(zr + i), Elem<T>::ld(w_last + i), dot);
+    dot = block_sum(dot, sh_incl);
+  }
+  if (threadIdx.x == 0) {
+    float ph = s.p_hat[b];
+    if (have_head && step > 1) {
+      const float a = dot + Elem<T>::ld(b_last);
+      const float sg = 1.0f / (1.0f + expf(-a));
+      s.head_s[b * CAND_LD + step - 2] = sg;
+      ph *= sg;
+      s.p_hat[b] = ph;
+    }
+    s.cand[b * CAND_LD + step - 1] = y;
+    s.K[b] = step;
+    const bool stop = (1.0f - ph > p.h) || (p.eos_id >= 0 && y == p.eos_id) || (step >= s.kcap[b]);
+    s.stopped[b] = stop ? 1 : 0;
+  }
+}
+
+// ------------------------------------------------------------------ softmax statistics per row
+// stats[row] = {max, sum_v exp((l_v - max)/T), argmax (int bits), 0}.  Row (b, j) of a
+// [B, rows_per_seq, V] array is live when j < K[b] + extra.
+__global__ __launch_bounds__(SB) void row_stats_k(const float* __restrict__ logits, int rows_per_seq, int extra,
+                                                  const int32_t* __restrict__ K, int V, float inv_t,
+                                                  float* __restrict__ stats, int32_t* __restrict__ err) {
+  __shared__ float sh_w[SB / 64];
+  __shared__ int sh_i[SB / 64];
+  const int j = blockIdx.x, b = blockIdx.y;
+  if (j >= K[b] + extra) return;
+  const size_t row = (size_t)b * rows_per_seq + j;
+  const float* l = logits + row * V;
+  ArgMax am{-INFINITY, 0x7fffffff};
+  bool bad = false;
+  for (int v = threadIdx.x; v < V; v += SB) {
+    const float x = l[v];
+    bad |= !isfinite(x);
+    am = better(am, ArgMax{x, v});
+  }
+  am = block_argmax(am, sh_w, sh_i);
+  if (bad && err) atomicOr(err, 1);
+  // contiguous chunk per thread, then a fixed-order block reduction
+  const int C = (V + SB - 1) / SB;
+  const int v0 = min((int)threadIdx.x * C, V), v1 = min(v0 + C, V);
+  float local = 0.f;
+  for (int v = v0; v < v1; ++v) local += expf((l[v] - am.v) * inv_t);
+  const float total = block_sum(local, sh_w);
+  if (threadIdx.x == 0) {
+    stats[row * 4 + 0] = am.v;
+    stats[row * 4 + 1] = total;
+    stats[row * 4 + 2] = __int_as_float(am.i);
+    stats[row * 4 + 3] = 0.f;
+  }
+}
+
+// ------------------------------------------------------------------ accept + resample
+__global__ __launch_bounds__(SB) void accept_k(const float* __restrict__ p_logits, const float* __restrict__ q_logits,
+                                               const float* __restrict__ p_stats, const float* __restrict__ q_stats,
+                                               const int32_t* __restrict__ cand, int cand_ld,
+                                               const int32_t* __restrict__ Karr, const int32_t* __restrict__ round_arr,
+                                               int round_const, DecodeParams p, int Kmax, int V,
+                                               int32_t* __restrict__ n_out, int32_t* __restrict__ tok_out,
+                                               uint8_t* __restrict__ flags, int flags_ld) {
+  __shared__ float sh_incl[SB];
+  __shared__ float sh_w[SB / 64];
+  __shared__ int sh_res;
+  __shared__ int sh_n;
+  const int b = blockIdx.x;
+  const int K = Karr[b];
+  const int rnd = round_arr ? round_arr[b] : round_const;
+  const float inv_t = 1.0f / p.temperature;
+  const float* pl = p_logits + (size_t)b * (Kmax + 1) * V;
+  const float* ql = q_logits + (size_t)b * Kmax * V;
+  const float* ps = p_stats + (size_t)b * (Kmax + 1) * 4;
+  const float* qs = q_stats + (size_t)b * Kmax * 4;
+
+  // the K accept tests, each on its own (thread i-1 takes test i)
+  if (threadIdx.x < Kmax) {
+    const int i = threadIdx.x + 1;
+    uint8_t ok = 0;
+    if (i <= K) {
+      const int y = cand[b * cand_ld + i - 1];
+      if (p.greedy) {
+        ok = (y == __float_as_int(ps[(i - 1) * 4 + 2])) ? 1 : 0;
+      } else {
+        const float py = expf((pl[(size_t)(i - 1) * V + y] - ps[(i - 1) * 4]) * inv_t) / ps[(i - 1) * 4 + 1];
+        const float qy = expf((ql[(size_t)(i - 1) * V + y] - qs[(i - 1) * 4]) * inv_t) / qs[(i - 1) * 4 + 1];
+        const float r = philox_uniform(p.seed, (uint32_t)i, (uint32_t)rnd, (uint32_t)b, STREAM_ACCEPT);
+        ok = (r * qy < py) ? 1 : 0;                      // accept iff r < p(y)/q(y)
+      }
+    }
+    flags[b * flags_ld + i - 1] = ok;
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    int n = K;
+    for (int i = 1; i <= K; ++i)
+      if (!flags[b * flags_ld + i - 1]) { n = i - 1; break; }
+    sh_n = n;
+  }
+  __syncthreads();
+  const int n = sh_n;
+
+  int y;
+  if (p.greedy) {
+    y = __float_as_int(ps[n * 4 + 2]);
+  } else {
+    const float* prow = pl + (size_t)n * V;
+    const float pmx = ps[n * 4], pinv = 1.0f / ps[n * 4 + 1];
+    const float u = philox_uniform(p.seed, (uint32_t)(n + 1), (uint32_t)rnd, (uint32_t)b, STREAM_RESAMPLE);
+    y = -1;
+    if (n < K) {                                         // residual Norm[(p_{n+1} - q_{n+1})_+]
+      const float* qrow = ql + (size_t)n * V;
+      const float qmx = qs[n * 4], qinv = 1.0f / qs[n * 4 + 1];
+      y = block_sample(
+          [&](int v) {
+            return fmaxf(expf((prow[v] - pmx) * inv_t) * pinv - expf((qrow[v] - qmx) * inv_t) * qinv, 0.f);
+          },
+          V, u, sh_incl, sh_w, &sh_res);
+      __syncthreads();
+    }
+    if (y < 0)                                           // bonus token from p_{K+1}, or a residual with no mass
+      y = block_sample([&](int v) { return expf((prow[v] - pmx) * inv_t) * pinv; }, V, u, sh_incl, sh_w, &sh_res);
+    if (y < 0) y = __float_as_int(ps[n * 4 + 2]);
+  }
+  if (threadIdx.x == 0) {
+    n_out[b] = n;
+    tok_out[b] = y;
+  }
+}
+
+// ------------------------------------------------------------------ commit + rollback
+// x <- x, y_1..y_n, y';  target cache keeps P + n positions, the draft cache
+// min(P + n, P + K - 1); P grows by n + 1.  Also packs the round result for the host.
+__global__ void commit_k(SeqState s, int32_t* __restrict__ result, int B, int max_seq) {
+  const int b = blockIdx.x * blockDim.x + threadIdx.x;
+  if (b >= B) return;
+  int32_t* r = result + b * RES_LD;
+  if (!s.active[b]) {
+    for (int i = 0; i < RES_LD; ++i) r[i] = 0;
+    r[36] = s.P[b];
+    r[37] = s.kv_t[b];
+    r[38] = s.kv_d[b];
+    r[39] = *s.err;
+    return;
+  }
+  const int P = s.P[b], K = s.K[b], n = s.n_acc[b], y = s.y_new[b];
+  int32_t* tk = s.tokens + (size_t)b * max_seq;
+  for (int i = 0; i < n; ++i) tk[P + i] = s.cand[b * CAND_LD + i];
+  tk[P + n] = y;
+  s.kv_t[b] = P + n;
+  s.kv_d[b] = min(P + n, P + K - 1);
+  s.P[b] = P + n + 1;
+  s.round[b] += 1;
+  r[0] = K;
+  r[1] = n;
+  r[2] = y;
+  r[3] = __float_as_int(s.p_hat[b]);
+  for (int i = 0; i < CAND_LD; ++i) r[4 + i] = i < K ? s.cand[b * CAND_LD + i] : -1;
+  r[36] = s.P[b];
+  r[37] = s.kv_t[b];
+  r[38] = s.kv_d[b];
+  r[39] = *s.err;
+}
+
+}  // namespace
+
+hipError_t launch_begin_round(hipStream_t st, const SeqState& s, int B, int k_max, int max_seq) {
+  if (B < 1 || k_max < 1 || k_max > CAND_LD) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(begin_round_k, dim3((B + 63) / 64), dim3(64), 0, st, s, B, k_max, max_seq);
+  return hipGetLastError();
+}
+
+hipError_t launch_plan_draft(hipStream_t st, const SeqState& s, const RowPlan& rows, int B, int step, int max_seq) {
+  if (B < 1 || 2 * B > MAX_ROWS || step < 1 || step > CAND_LD) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(plan_draft_k, dim3((B + 63) / 64), dim3(64), 0, st, s, rows, B, step, max_seq);
+  return hipGetLastError();
+}
+
+hipError_t launch_plan_verify(hipStream_t st, const SeqState& s, const RowPlan& rows, int B, int k_max, int max_seq) {
+  if (B < 1 || k_max < 1 || k_max > CAND_LD || B * (k_max + 1) > MAX_ROWS) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(plan_verify_k, dim3(B), dim3(64), 0, st, s, rows, B, k_max, max_seq);
+  return hipGetLastError();
+}
+
+hipError_t launch_sample_stop(hipStream_t st, int dtype, const SeqState& s, const float* q_logits, int64_t ld_seq,
+                              const void* z, const int* z_rows, int z_dim, const void* w_last, const void* b_last,
+                              int have_head, const DecodeParams& p, int B, int V, int step) {
+  if (B < 1 || V < 1 || step < 1 || step > CAND_LD || !q_logits || !(p.temperature > 0.f)) return hipErrorInvalidValue;
+  if (have_head && (!z || !w_last || !b_last || z_dim < 1)) return hipErrorInvalidValue;
+  if (dtype == DT_F32)
+    hipLaunchKernelGGL(sample_stop_k<float>, dim3(B), dim3(SB), 0, st, s, q_logits, ld_seq, (const float*)z, z_rows,
+                       z_dim, (const float*)w_last, (const float*)b_last, have_head, p, V, step);
+  else if (dtype == DT_BF16)
+    hipLaunchKernelGGL(sample_stop_k<bf16_t>, dim3(B), dim3(SB), 0, st, s, q_logits, ld_seq, (const bf16_t*)z, z_rows,
+                       z_dim, (const bf16_t*)w_last, (const bf16_t*)b_last, have_head, p, V, step);
+  else
+    return hipErrorInvalidValue;
+  return hipGetLastError();
+}
+
+hipError_t launch_row_stats(hipStream_t st, const float* logits, int rows_per_seq, int extra, const int32_t* K, int B,
+                            int V, float temperature, float* stats, int32_t* err) {
+  if (B < 1 || rows_per_seq < 1 || V < 1 || !logits || !K || !stats || !(temperature > 0.f))
+    return hipErrorInvalidValue;
+  hipLaunchKernelGGL(row_stats_k, dim3(rows_per_seq, B), dim3(SB), 0, st, logits, rows_per_seq, extra, K, V,
+                     1.0f / temperature, stats, err);
+  return hipGetLastError();
+}
+
+hipError_t launch_accept(hipStream_t st, const float* p_logits, const float* q_logits, const float* p_stats,
+                         const float* q_stats, const int32_t* cand, int cand_ld, const int32_t* K,
+                         const int32_t* round, int round_const, const DecodeParams& p, int B, int Kmax, int V,
+                         int32_t* n_out, int32_t* tok_out, uint8_t* flags, int flags_ld) {
+  if (B < 1 || Kmax < 1 || Kmax > CAND_LD || V < 1 || cand_ld < Kmax || flags_ld < Kmax || !p_logits || !q_logits ||
+      !p_stats || !q_stats || !cand || !K || !n_out || !tok_out || !flags || !(p.temperature > 0.f))
+    return hipErrorInvalidValue;
+  hipLaunchKernelGGL(accept_k, dim3(B), dim3(SB), 0, st, p_logits, q_logits, p_stats, q_stats, cand, cand_ld, K, round,
+                     round_const, p, Kmax, V, n_out, tok_out, flags, flags_ld);
+  return hipGetLastError();
+}
+
+hipError_t launch_commit(hipStream_t st, const SeqState& s, int32_t* result, int B, int max_seq) {
+  if (B < 1 || !result) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(commit_k, dim3((B + 63) / 64), dim3(64), 0, st, s, result, B, max_seq);
+  return hipGetLastError();
+}
+
+}  // namespace sd

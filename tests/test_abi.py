@@ -1,0 +1,45 @@
+"""The C-ABI library loads and exports every symbol the public header declares
+(no compute calls: this runs without a GPU)."""
+import ctypes
+import os
+import re
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "specdec.h")
+LIB = os.path.join(ROOT, "paper_2405_19715_amd", "libspecdec.so")
+
+
+def _declared():
+    src = open(HEADER).read()
+    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+    return sorted(set(re.findall(r"\b((?:sd_|specdec_)\w+)\s*\(", src)))
+
+
+def test_library_exports_every_declared_symbol():
+    if not os.path.exists(LIB):
+        from paper_2405_19715_amd import build
+        build.build(verbose=False)
+    lib = ctypes.CDLL(LIB)
+    names = _declared()
+    assert {"sd_create", "sd_destroy", "sd_prefill", "specdec_round", "specdec_generate",
+            "sd_accept_resample", "sd_gemm_skinny", "sd_forward"} <= set(names)
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def test_binding_covers_the_header():
+    from paper_2405_19715_amd import binding
+    assert sorted(binding.EXPORTS) == _declared()
+
+
+def test_host_side_argument_checks_need_no_gpu():
+    from paper_2405_19715_amd import binding as B
+    assert B.lib.sd_strerror(B.SD_ERANGE).decode().startswith("sequence")
+    assert B.lib.sd_destroy(None) == B.SD_EINVAL
+    assert B.lib.sd_create(None, None, None, None, None) == B.SD_EINVAL
+    h = ctypes.c_void_p()
+    assert B.lib.sd_create(ctypes.byref(h), None, None, None, ctypes.byref(B.sd_config(1, 64, 4, None))) == B.SD_EINVAL
+    assert B.lib.sd_accept_workspace_bytes(4, 16) == 4 * 33 * 16 + 16
+    assert B.lib.sd_gemm_workspace_bytes(B.SD_BF16, 17, 8192, 8192) % (17 * 8192 * 4) == 0
+    assert B.lib.sd_gemm_workspace_bytes(B.SD_BF16, 500, 8192, 8192) == 0
+    assert B.lib.sd_version().decode().startswith("specdec")

@@ -1,0 +1,47 @@
+"""Parity of the weight-streaming skinny GEMM (HIP, through the C ABI) with the
+oracle's plain fp64 matrix product on the same seeded inputs."""
+import numpy as np
+import pytest
+import torch
+
+pytestmark = pytest.mark.gpu
+
+
+def _check(M, N, K, dtype, seed, tol):
+    from paper_2405_19715_amd import binding as B
+    g = torch.Generator().manual_seed(seed)
+    W = (torch.randn((N, K), generator=g) * 0.05).to(dtype)
+    X = torch.randn((M, K), generator=g).to(dtype)
+    want = X.double().numpy() @ W.double().numpy().T            # the definition, in fp64
+    got = B.sd_gemm_skinny(W.cuda(), X.cuda()).cpu().double().numpy()
+    scale = np.abs(want).max()
+    err = np.abs(got - want).max() / scale
+    assert err < tol, (M, N, K, dtype, err)
+
+
+@pytest.mark.parametrize("M", [1, 2, 3, 4, 5, 9, 16, 17, 31, 32, 33, 48, 136])
+def test_bf16_rows(M):
+    # several 64-row workgroup tiles, a ragged last workgroup (N = 16 * 13), several K slices
+    _check(M, 16 * 13, 1024, torch.bfloat16, M, 2e-5)
+    _check(M, 256, 128, torch.bfloat16, 100 + M, 2e-5)
+
+
+@pytest.mark.parametrize("shape", [(17, 512, 8192), (17, 1024, 28672 // 4), (1, 4096, 4096), (2, 1024, 11008),
+                                   (17, 2560, 2048), (8, 32000, 256)])
+def test_bf16_model_shapes(shape):
+    _check(*shape, torch.bfloat16, 7, 3e-5)
+
+
+@pytest.mark.parametrize("shape", [(1, 256, 256), (9, 1024, 256), (17, 688 * 2, 256), (32, 256, 688), (3, 7, 5)])
+def test_fp32(shape):
+    _check(*shape, torch.float32, 11, 2e-6)
+
+
+def test_rejects_shapes_the_kernel_cannot_take():
+    from paper_2405_19715_amd import binding as B
+    W = torch.zeros((16, 100), dtype=torch.bfloat16, device="cuda")      # K not a multiple of 128
+    X = torch.zeros((1, 100), dtype=torch.bfloat16, device="cuda")
+    Y = torch.zeros((1, 16), dtype=torch.float32, device="cuda")
+    ws = torch.zeros(1 << 16, dtype=torch.uint8, device="cuda")
+    with pytest.raises(B.SpecDecError):
+        B.sd_gemm_skinny(W, X, out=(Y, ws))

@@ -1,0 +1,259 @@
+"""Parity of whole draft-verify-correct rounds (Algorithm 2) between the HIP path
+and the oracle: free-running token streams on the tiny fp32 pair in greedy and
+sampling mode, greedy identity with target-only decoding (Sec. 4.1), the counter
+identity (Sec. 3.2), the fixed-K special case, and decision replay on bf16 pairs."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import head as OH
+from oracle import rounds as R
+from oracle import sampling
+from paper_2405_19715_amd import synth
+from tests._parity import run_free_running
+from tests._util import oracle_head, oracle_model
+
+pytestmark = pytest.mark.gpu
+
+
+def _cuda_model(m, share=None):
+    out = dict(m)
+    for k in ("tok_emb", "lm_head", "final_norm"):
+        out[k] = share[k] if share is not None and m[k] is share["_src"][k] else m[k].cuda()
+    out["layers"] = [{k: v.cuda() for k, v in lay.items()} for lay in m["layers"]]
+    out["_src"] = m
+    return out
+
+
+def _cuda_head(h):
+    out = dict(h)
+    out["W"] = [w.cuda() for w in h["W"]]
+    out["b"] = [b.cuda() for b in h["b"]]
+    return out
+
+
+def tiny_pair(seed=0):
+    """The tiny fp32 pair: 2-layer target, draft = its first layer perturbed, shared
+    embedding / LM head, head 256 -> 64 -> 1 with output bias logit(0.8)."""
+    t = synth.make_model(synth.TINY_TARGET, seed, dtype=torch.float32)
+    d = synth.make_perturbed_draft(t, 1, seed + 1, std=0.005)
+    h = synth.make_head([256, 64, 1], seed + 2, dtype=torch.float32)
+    return t, d, h
+
+
+def _context(t, d, h, k_max, max_seq, batch=1):
+    from paper_2405_19715_amd import binding as B
+    tc = _cuda_model(t)
+    dc = _cuda_model(d, share=tc)
+    return B.Context(tc, dc, _cuda_head(h) if h is not None else None, batch=batch, max_seq=max_seq, k_max=k_max)
+
+
+@pytest.mark.parametrize("greedy", [True, False])
+def test_tiny_pair_free_running_parity(greedy):
+    from paper_2405_19715_amd import binding as B
+    t, d, h = tiny_pair()
+    prompt = synth.make_prompt(64, 1024, 0)
+    ctx = _context(t, d, h, k_max=8, max_seq=256)
+    try:
+        ctx.sd_prefill(0, prompt)
+        op = R.Params(h=0.7, temperature=1.0, greedy=greedy, seed=0)
+        gp = B.make_params(h=0.7, temperature=1.0, greedy=greedy, seed=0)
+        toks, exempt, hist = run_free_running(ctx, oracle_model(t), oracle_model(d), oracle_head(h), prompt, op, gp,
+                                              128, 8, 256)
+        assert len(toks) == 128 and exempt <= 2
+        assert max(k for k, _ in hist) <= 8
+        st = ctx.sd_seq_state(0)
+        assert st["P"] == 64 + sum(n + 1 for _, n in hist)
+        assert st["kv_len_target"] == st["P"] - 1
+    finally:
+        ctx.close()
+
+
+def test_greedy_generate_equals_target_only_greedy_and_counters():
+    from paper_2405_19715_amd import binding as B
+    t, d, h = tiny_pair(seed=3)
+    prompt = synth.make_prompt(20, 1024, 5)
+    want = R.target_greedy_generate(oracle_model(t), prompt, 40)
+    for hh, k_max in [(0.7, 8), (1.0, 4), (-1.0, 8)]:
+        ctx = _context(t, d, h, k_max=k_max, max_seq=128)
+        try:
+            ctx.sd_prefill(0, prompt)
+            seqs, st = ctx.specdec_generate(B.make_params(h=hh, greedy=True), 40)
+            assert seqs[0] == want, (hh, k_max)
+            assert st["N"] == 40
+            # whole rounds satisfy N_draft + N_target = N + N_discarded; the last round may overshoot
+            over = st["N_draft"] + st["N_target"] - st["N"] - st["N_discarded"]
+            assert 0 <= over <= k_max
+            if hh >= 1.0:
+                assert st["N_draft"] == k_max * st["N_target"]
+            if hh < 0:
+                assert st["N_draft"] == st["N_target"]
+        finally:
+            ctx.close()
+
+
+def test_sampled_generate_matches_oracle_generate_and_resumes():
+    """specdec_generate(N) equals the oracle's stream, and equals generate(N1) followed
+    by generate(N - N1) when N1 ends on a round boundary (counter-based uniforms)."""
+    from paper_2405_19715_amd import binding as B
+    t, d, h = tiny_pair(seed=7)
+    prompt = synth.make_prompt(16, 1024, 9)
+    op = R.Params(h=0.5, seed=11)
+    want, ost, rounds = R.oracle_generate(oracle_model(t), oracle_model(d), oracle_head(h), prompt, op, 48, 6, 128,
+                                          cached=True)
+    ctx = _context(t, d, h, k_max=6, max_seq=128)
+    try:
+        ctx.sd_prefill(0, prompt)
+        seqs, st = ctx.specdec_generate(B.make_params(h=0.5, seed=11), 48)
+        assert seqs[0] == want
+        assert (st["N"], st["N_draft"], st["N_target"], st["N_discarded"]) == (ost.N, ost.N_draft, ost.N_target,
+                                                                              ost.N_discarded)
+        n1 = sum(len(r["tokens"]) for r in rounds[:3])
+        ctx.sd_prefill(0, prompt)
+        a, _ = ctx.specdec_generate(B.make_params(h=0.5, seed=11), n1)
+        b, _ = ctx.specdec_generate(B.make_params(h=0.5, seed=11), 48 - n1)
+        assert a[0] + b[0] == want
+    finally:
+        ctx.close()
+
+
+def test_cache_capacity_and_bad_arguments():
+    from paper_2405_19715_amd import binding as B
+    t, d, h = tiny_pair(seed=1)
+    ctx = _context(t, d, h, k_max=8, max_seq=64)
+    try:
+        with pytest.raises(B.SpecDecError) as e:
+            ctx.sd_prefill(0, [5000])                       # token id outside the vocabulary
+        assert e.value.status == B.SD_ERANGE
+        with pytest.raises(B.SpecDecError) as e:
+            ctx.sd_prefill(0, list(range(63)))              # n + 2 > max_seq
+        assert e.value.status == B.SD_ERANGE
+        prompt = synth.make_prompt(58, 1024, 2)
+        ctx.sd_prefill(0, prompt)
+        r = ctx.specdec_round(B.make_params(h=1.0, seed=1))[0]
+        assert r["K"] == 64 - 58 - 1                        # cap = max_seq - P - 1
+        # rounds go on until the cache is full, then the call reports it and changes nothing
+        while True:
+            st = ctx.sd_seq_state(0)
+            if 64 - st["P"] - 1 < 1:
+                break
+            ctx.specdec_round(B.make_params(h=1.0, seed=1))
+        before = ctx.sd_seq_state(0)
+        with pytest.raises(B.SpecDecError) as e:
+            ctx.specdec_round(B.make_params(h=1.0, seed=1))
+        assert e.value.status == B.SD_ERANGE and ctx.sd_seq_state(0) == before
+    finally:
+        ctx.close()
+
+
+def _bf16_pair():
+    ts = synth.ModelShape(2, 512, 8, 1, 64, 640, 2048)
+    ds = synth.ModelShape(1, 256, 2, 2, 128, 384, 2048)
+    t = synth.make_model(ts, 20, dtype=torch.bfloat16, std=0.04)
+    d = synth.make_model(ds, 21, dtype=torch.bfloat16, std=0.04)
+    h = synth.make_head([256, 256, 256, 256, 1], 22, dtype=torch.bfloat16, residual=True, std=0.04)
+    return t, d, h
+
+
+@pytest.mark.parametrize("greedy", [False, True])
+def test_bf16_pair_decision_replay(greedy):
+    """bf16 models: feed the HIP path's own fp32 logits rows and head outputs of each
+    round to the oracle's stop rule and accept / resample step: K, n and y' must match
+    exactly (same exemptions as above)."""
+    from paper_2405_19715_amd import binding as B
+    from oracle import philox
+    t, d, h = _bf16_pair()
+    prompt = synth.make_prompt(40, 2048, 3)
+    k_max, hh, seed = 16, 0.9, 5
+    ctx = _context(t, d, h, k_max=k_max, max_seq=256)
+    try:
+        ctx.sd_prefill(0, prompt)
+        gp = B.make_params(h=hh, greedy=greedy, seed=seed)
+        exempt = 0
+        Ks = []
+        for rho in range(12):
+            g = ctx.specdec_round(gp)[0]
+            K = g["K"]
+            Ks.append(K)
+            q, p, s = ctx.sd_last_round_rows(0, K)
+            q, p, s = q.numpy(), p.numpy(), s.numpy()
+            # stop rule on the head outputs the HIP path used
+            want_K = OH.candidate_length(list(s.astype(np.float64)) + [1.0] * 40, hh, k_max)
+            if want_K != K:
+                ph = np.cumprod(np.concatenate([[1.0], s.astype(np.float64)]))
+                assert np.min(np.abs(1 - ph - hh)) < 1e-5
+                exempt += 1
+            # candidates: inverse CDF / argmax on the HIP path's own draft rows
+            for i in range(1, K + 1):
+                if greedy:
+                    y = sampling.argmax_lowest(q[i - 1])
+                    ok = y == g["cand"][i - 1] or sampling.top2_gap(q[i - 1]) < 1e-6
+                else:
+                    qi = sampling.softmax(q[i - 1])
+                    u = philox.uniform(seed, i, rho, 0, philox.STREAM_DRAFT)
+                    y = sampling.sample_inverse_cdf(qi, u)
+                    ok = y == g["cand"][i - 1] or sampling.cdf_margin(qi, u, y) < 1e-5
+                assert ok, (rho, i)
+                exempt += int(y != g["cand"][i - 1])
+            o = sampling.accept_resample(p, q, g["cand"], K, greedy=greedy, seed=seed, rnd=rho)
+            if o["n"] != g["n"]:
+                i = min(o["n"], g["n"]) + 1
+                assert not greedy and abs(o["r"][i - 1] - o["ratio"][i - 1]) < 1e-3
+                o = sampling.accept_resample(p, q, g["cand"], K, greedy=greedy, seed=seed, rnd=rho,
+                                             forced={("accept", i): 1 if g["n"] >= i else 0})
+                exempt += 1
+            assert o["n"] == g["n"]
+            if o["token"] != g["tokens"][-1]:
+                assert o["margin"] < 1e-5
+                exempt += 1
+            assert g["tokens"][:-1] == g["cand"][: g["n"]]
+        assert exempt <= 3
+        assert min(Ks) >= 2 and max(Ks) <= k_max
+    finally:
+        ctx.close()
+
+
+def test_bf16_round_logits_match_oracle_forward():
+    """Teacher-forced check of a real round: replay the HIP path's tokens through the
+    oracle's fp64 forward and compare the target rows p_1..p_{K+1} and draft rows
+    q_1..q_K the round used (row-wise max-norm relative error)."""
+    from paper_2405_19715_amd import binding as B
+    from oracle.model import forward_full
+    t, d, h = _bf16_pair()
+    prompt = synth.make_prompt(33, 2048, 8)
+    ctx = _context(t, d, h, k_max=16, max_seq=256)
+    try:
+        ctx.sd_prefill(0, prompt)
+        x = list(prompt)
+        tw, dw = oracle_model(t), oracle_model(d)
+        for rho in range(4):
+            g = ctx.specdec_round(B.make_params(h=0.8, seed=2))[0]
+            K = g["K"]
+            q, p, _ = ctx.sd_last_round_rows(0, K)
+            want_p = forward_full(tw, x + g["cand"])[0][-(K + 1):]
+            want_q = forward_full(dw, x + g["cand"][:-1])[0][-K:]
+            for got, want in ((p.numpy(), want_p), (q.numpy(), want_q)):
+                err = (np.abs(got - want).max(-1) / np.abs(want).max(-1)).max()
+                assert err < 2e-2, (rho, err)
+            x += g["tokens"]
+    finally:
+        ctx.close()
+
+
+def test_batch_of_sequences_matches_single_sequence_runs():
+    """Two sequences decoded together give the streams each gives alone (per-sequence
+    stop rule, ragged K, per-sequence rollback; the sequence id keys the uniforms)."""
+    from paper_2405_19715_amd import binding as B
+    t, d, h = tiny_pair(seed=4)
+    prompts = [synth.make_prompt(12, 1024, 1), synth.make_prompt(30, 1024, 2)]
+    tw, dw, hw = oracle_model(t), oracle_model(d), oracle_head(h)
+    want = [R.oracle_generate(tw, dw, hw, prompts[b], R.Params(h=0.6, seed=3), 24, 6, 128, seq=b, cached=True)[0]
+            for b in range(2)]
+    ctx = _context(t, d, h, k_max=6, max_seq=128, batch=2)
+    try:
+        for b in range(2):
+            ctx.sd_prefill(b, prompts[b])
+        seqs, st = ctx.specdec_generate(B.make_params(h=0.6, seed=3), 24)
+        assert seqs == want
+    finally:
+        ctx.close()
