@@ -1,0 +1,198 @@
+"""Benchmark of the draft-verify-correct round (SpecDec++, Algorithm 2) on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload paper|mid|tiny] [--h 0.7]
+
+A step is one whole round over one batch: adaptive draft loop (7B-shaped draft +
+acceptance head + stop rule), one 70B-shaped target pass over the K+1 positions,
+accept / residual resample, KV rollback.  Models are synthetic random-init bf16
+(the paper's llama-2-chat weights and dataset prompts are not available; shapes,
+vocab, temperature and batch follow the paper's setting).  Inputs are resident in HBM
+before the timed region.  Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
+
+
+def _workload(name):
+    from paper_2405_19715_amd import synth
+    if name == "paper":      # Llama-2-70B-shaped target, Llama-2-7B-shaped draft
+        return dict(target=synth.LLAMA_70B, draft=synth.LLAMA_7B, head=[4096, 4096, 4096, 4096, 1], prompt=1024,
+                    gen=512, k_max=16, label="llama2-70b/7b-shaped bf16 random-init, batch 1, prompt 1024, K_max 16")
+    if name == "mid":        # Llama-2-7B-shaped target, 1.1B-shaped draft
+        return dict(target=synth.LLAMA_7B, draft=synth.LLAMA_1B, head=[2048, 2048, 2048, 2048, 1], prompt=512,
+                    gen=256, k_max=16, label="llama2-7b/1.1b-shaped bf16 random-init, batch 1, prompt 512, K_max 16")
+    raise SystemExit(f"unknown workload {name}")
+
+
+def _algorithmic_bytes_verify(shape, P, K, esz=2):
+    """Bytes one target pass must move: every weight once, the KV cache of the P
+    finalised positions, the K+1 new KV rows, and the K+1 fp32 logits rows."""
+    kv_token = 2 * shape.n_layers * shape.n_kv * esz
+    return shape.streamed_params() * esz + kv_token * P + kv_token * (K + 1) + (K + 1) * shape.vocab * 4
+
+
+def _cpu_baseline(tgt, drf, k_mean, n_mean, P, k_max):
+    """The oracle, as it stands, timed on this machine's host cores on a bounded sample of
+    the same workload: one target layer over K_max+1 rows and one draft layer over one
+    row at the real shapes (weights of layer 0 copied from the device), each against a
+    random KV cache of P positions, plus both LM heads; whole-pass times are the layer
+    time times the layer count (extrapolated), and tokens/s follows the paper's time
+    decomposition with the GPU run's mean K and n."""
+    import numpy as np
+    import torch
+    from oracle.model import CachedForward, LayerWeights, ModelWeights
+
+    def one_layer_model(m):
+        s = m["shape"]
+        lay = m["layers"][0]
+        f = lambda t: t.detach().to("cpu", torch.float64).numpy()
+        wqkv, wgu = f(lay["wqkv"]), f(lay["w_gate_up"])
+        lw = LayerWeights(wq=wqkv[: s.n_q], wk=wqkv[s.n_q: s.n_q + s.n_kv], wv=wqkv[s.n_q + s.n_kv:],
+                          wo=f(lay["wo"]), w_gate=wgu[: s.d_ffn], w_up=wgu[s.d_ffn:], w_down=f(lay["w_down"]),
+                          norm_attn=f(lay["norm_attn"]), norm_mlp=f(lay["norm_mlp"]))
+        lm = f(m["lm_head"])
+        return ModelWeights(n_heads=s.n_heads, n_kv_heads=s.n_kv_heads, head_dim=s.head_dim, tok_emb=lm, lm_head=lm,
+                            final_norm=f(m["final_norm"]), layers=[lw], rope_theta=s.rope_theta, rms_eps=s.rms_eps)
+
+    def time_pass(m, rows):
+        w = one_layer_model(m)
+        s = m["shape"]
+        rng = np.random.default_rng(0)
+        fw = CachedForward(w)
+        fw.k = [rng.standard_normal((P, s.n_kv_heads, s.head_dim))]
+        fw.v = [rng.standard_normal((P, s.n_kv_heads, s.head_dim))]
+        fw.len = P
+        toks = rng.integers(0, s.vocab, size=rows)
+        t0 = time.perf_counter()
+        logits, _ = fw.extend(toks)
+        t_all = time.perf_counter() - t0
+        e = rng.standard_normal((rows, s.d_model))
+        t0 = time.perf_counter()
+        _ = e @ w.lm_head.T
+        t_lm = time.perf_counter() - t0
+        t_layer = max(t_all - t_lm, 1e-9)
+        return t_layer * s.n_layers + t_lm, t_layer, t_lm
+
+    t_target, tl_t, lm_t = time_pass(tgt, k_max + 1)
+    t_draft, tl_d, lm_d = time_pass(drf, 1)
+    tps = (n_mean + 1.0) / (k_mean * t_draft + t_target)
+    return dict(value=tps, unit="tokens/s", cores=torch.get_num_threads(), kind="oracle",
+                sample=(f"extrapolated: 1 of {tgt['shape'].n_layers} target layers ({k_max + 1} rows, P={P}) "
+                        f"{tl_t:.3f}s + LM head {lm_t:.3f}s -> t_target {t_target:.1f}s; 1 of "
+                        f"{drf['shape'].n_layers} draft layers (1 row) {tl_d:.3f}s + LM head {lm_d:.3f}s -> "
+                        f"t_draft {t_draft:.2f}s; tokens/s = (n+1)/(K*t_draft + t_target) with the GPU run's "
+                        f"mean K={k_mean:.2f}, n={n_mean:.2f}"),
+                t_target_s=t_target, t_draft_s=t_draft)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=24)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="paper")
+    ap.add_argument("--h", type=float, default=0.7)
+    ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--profile-every", type=int, default=8,
+                    help="bracket the target GEMMs of every n-th layer with HIP events (0 = off)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        raise SystemExit("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)")
+
+    import torch
+    from paper_2405_19715_amd import binding as B
+    from paper_2405_19715_amd import synth
+
+    wl = _workload(args.workload)
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    t_build = time.perf_counter()
+    tgt = synth.make_model(wl["target"], args.seed, device=dev, dtype=torch.bfloat16)
+    drf = synth.make_model(wl["draft"], args.seed + 1, device=dev, dtype=torch.bfloat16)
+    head = synth.make_head(wl["head"], args.seed + 2, device=dev, dtype=torch.bfloat16, residual=True)
+    torch.cuda.synchronize()
+    t_build = time.perf_counter() - t_build
+    max_seq = -(-(wl["prompt"] + wl["gen"] + (args.steps + args.warmup + 16) * (wl["k_max"] + 1) + 2) // 64) * 64
+    ctx = B.Context(tgt, drf, head, batch=1, max_seq=max_seq, k_max=wl["k_max"])
+    prompt = synth.make_prompt(wl["prompt"], wl["target"].vocab, args.seed + 3)
+    ctx.sd_prefill(0, prompt)
+    params = B.make_params(h=args.h, temperature=1.0, greedy=False, seed=args.seed)
+
+    for _ in range(args.warmup):
+        ctx.specdec_round(params)
+    ctx.sd_profile_enable(args.profile_every)
+    ctx.sd_profile_read()
+    P0 = ctx.sd_seq_state(0)["P"]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    # the timed region: exactly `steps` rounds
+    Ks, ns = [], []
+    for _ in range(args.steps):
+        r = ctx.specdec_round(params)[0]
+        Ks.append(r["K"])
+        ns.append(r["n"])
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    prof = ctx.sd_profile_read()
+    ctx.sd_profile_enable(0)
+    n_tok = sum(n + 1 for n in ns)
+    k_mean, n_mean = sum(Ks) / len(Ks), sum(ns) / len(ns)
+    P_mid = (P0 + ctx.sd_seq_state(0)["P"]) // 2
+
+    # phase times of a few more rounds (events inside the library, same stream)
+    _, st2 = ctx.specdec_generate(params, max(8, 4 * int(n_mean + 1)))
+    t_target = st2["t_target_s"] / st2["rounds"]
+    t_draft = st2["t_draft_s"] / max(st2["N_draft"], 1)
+    t_accept = st2["t_accept_s"] / st2["rounds"]
+
+    tot_b = sum(v["weight_bytes"] for v in prof.values())
+    tot_s = sum(v["seconds"] for v in prof.values())
+    tot_n = sum(v["launches"] for v in prof.values())
+    counts = dict(qkv=wl["target"].n_layers, o=wl["target"].n_layers, gate_up=wl["target"].n_layers,
+                  down=wl["target"].n_layers, lm_head=1)
+    est_avg_us = None
+    if all(prof[k]["launches"] for k in counts):
+        est_avg_us = sum(counts[k] * prof[k]["seconds"] / prof[k]["launches"] for k in counts) / sum(counts.values()) * 1e6
+    achieved = tot_b / tot_s / 1e9 if tot_s > 0 else None
+    verify_bytes = _algorithmic_bytes_verify(wl["target"], P_mid, wl["k_max"])
+    roofline = dict(bound="hbm", kernel="gemm_bf16_mfma<2> (target pass, M = K_max+1 = 17 rows)",
+                    achieved=achieved, peak=HBM_PEAK_GBS, unit="GB/s",
+                    frac=(achieved / HBM_PEAK_GBS) if achieved else None, traffic=None,
+                    sampled_launches=tot_n, avg_launch_us=est_avg_us,
+                    per_matrix_GBs={k: (v["weight_bytes"] / v["seconds"] / 1e9 if v["seconds"] > 0 else None)
+                                    for k, v in prof.items()},
+                    verify_pass=dict(algorithmic_bytes=verify_bytes, seconds=t_target,
+                                     achieved_GBs=verify_bytes / t_target / 1e9,
+                                     frac=verify_bytes / t_target / 1e9 / HBM_PEAK_GBS))
+    cpu = None
+    if not args.no_cpu_baseline:
+        cpu = _cpu_baseline(tgt, drf, k_mean, n_mean, wl["prompt"], wl["k_max"])
+    out = dict(metric="generated tokens/s (batch 1, 70B/7B shape) + verify-pass HBM GB/s % of peak",
+               value=n_tok / dt, unit="tokens/s", n_gpus=1, steps=args.steps, warmup=args.warmup,
+               ms_per_step=dt / args.steps * 1e3, higher_is_better=True, scaling="weak", vs_baseline=None,
+               dtype="bf16", data="synthetic",
+               config=dict(workload=wl["label"], h=args.h, temperature=1.0, mean_K=k_mean, mean_n=n_mean,
+                           discard_rate=(sum(Ks) - sum(ns)) / n_tok, verification_rate=len(Ks) / n_tok,
+                           t_draft_ms=t_draft * 1e3, t_target_ms=t_target * 1e3, t_accept_ms=t_accept * 1e3,
+                           eq4_tokens_per_s=1.0 / (t_draft + t_draft * (sum(Ks) - sum(ns)) / n_tok
+                                                   + (t_target - t_draft) * len(Ks) / n_tok),
+                           weights_init_s=t_build),
+               roofline=roofline, cpu_baseline=cpu)
+    ctx.close()
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()
