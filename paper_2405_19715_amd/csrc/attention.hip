@@ -19,8 +19,8 @@
 //
 // Query vectors of one (sequence, kv head) are the G = Hq/Hkv heads of every row of
 // the sequence's row group: up to 17 x 8 = 136 vectors share each streamed K/V tile.
-// Keys are split over workgroups and wavefronts; a second kernel merges the
-// (max, sum, O) partials in fixed order.
+// Every wavefront takes one block of 64 keys (for its share of the query tiles) and
+// writes one (max, sum, O) partial; a second kernel merges the partials in block order.
 #include "common.hpp"
 #include "kernels.hpp"
 
@@ -30,8 +30,7 @@ namespace sd {
 
 namespace {
 
-constexpr int SPL = 256;        // keys per workgroup
-constexpr int KB = 64;          // keys per inner block
+constexpr int KB = 64;          // keys per wavefront: one block, one partial
 constexpr float NEG_BIG = -1.0e30f;
 
 __device__ __forceinline__ uint4 ld16(const bf16_t* p) { return *reinterpret_cast<const uint4*>(p); }
@@ -77,11 +76,10 @@ __global__ __launch_bounds__(256) void attn_mfma_k(const bf16_t* __restrict__ qb
   const int li = lane & 15, g = lane >> 4;
   const int KW = 4 / QW;
   const int qw = wave % QW, kw = wave / QW;
-  const int keys_per_wave = SPL / KW;
-  const int kbeg = c * SPL + kw * keys_per_wave;
+  const int sp = c * KW + kw;              // this wave's key block, also its partial's index
+  const int kbeg = sp * KB;
   if (kbeg >= kv_end) return;
-  const int kend = min(kbeg + keys_per_wave, kv_end);
-  const int sp = c * KW + kw;
+  const int kend = min(kbeg + KB, kv_end);
 
   const bf16_t* kbase = kcache + ((size_t)seq * Hkv + kh) * (size_t)max_seq * HD;
   const bf16_t* vbase = vcache + ((size_t)seq * Hkv + kh) * (size_t)HD * max_seq;
@@ -215,7 +213,7 @@ __global__ __launch_bounds__(256) void attn_mfma_k(const bf16_t* __restrict__ qb
 template <int HD>
 __global__ __launch_bounds__(HD) void attn_merge_k(const float* __restrict__ scratch, const int32_t* __restrict__ row_seq,
                                                    const int32_t* __restrict__ row_pos, bf16_t* __restrict__ out, int RS,
-                                                   int Hq, int KW, int NSP) {
+                                                   int Hq, int NSP) {
   constexpr int STRIDE = HD + 4;
   const int m = blockIdx.x, h = blockIdx.y, d = threadIdx.x;
   bf16_t* dst = out + ((size_t)m * Hq + h) * HD + d;
@@ -230,15 +228,9 @@ __global__ __launch_bounds__(HD) void attn_merge_k(const float* __restrict__ scr
     if (row_seq[mm] >= 0) kv_end = max(kv_end, row_pos[mm] + 1);
   }
   const float* src = scratch + ((size_t)m * Hq + h) * NSP * STRIDE;
-  const int keys_per_wave = SPL / KW;
+  const int nsp = min(NSP, (kv_end + KB - 1) / KB);
   float mx = NEG_BIG;
-  int nsp = 0;
-  for (int sp = 0; sp < NSP; ++sp) {
-    const int kbeg = (sp / KW) * SPL + (sp % KW) * keys_per_wave;
-    if (kbeg >= kv_end) break;
-    mx = fmaxf(mx, src[sp * STRIDE + HD]);
-    nsp = sp + 1;
-  }
+  for (int sp = 0; sp < nsp; ++sp) mx = fmaxf(mx, src[sp * STRIDE + HD]);
   float num = 0.f, den = 0.f;
   for (int sp = 0; sp < nsp; ++sp) {
     const float w = __expf(src[sp * STRIDE + HD] - mx);
@@ -329,7 +321,7 @@ bool use_plain(int dtype) {
 }  // namespace
 
 size_t attn_scratch_floats(int M, int Hq, int hd, int max_seq) {
-  const int nsp = ((max_seq + SPL - 1) / SPL) * 4;
+  const int nsp = (max_seq + KB - 1) / KB;
   return (size_t)M * Hq * nsp * (hd + 4);
 }
 
@@ -357,8 +349,8 @@ hipError_t launch_attention(hipStream_t st, int dtype, const void* qbuf, const v
   if (dtype != DT_BF16 || (hd != 64 && hd != 128) || max_seq % KB != 0 || !scratch) return hipErrorInvalidValue;
   const MfmaShape sh = mfma_shape(RS, Hq / Hkv);
   const int KW = 4 / sh.QW;
-  const int nsplit = (max_kv_len + SPL - 1) / SPL;
-  const int NSP = ((max_seq + SPL - 1) / SPL) * 4;
+  const int nsplit = ((max_kv_len + KB - 1) / KB + KW - 1) / KW;
+  const int NSP = (max_seq + KB - 1) / KB;
   const dim3 grid(Hkv * sh.NQG, ngroups, nsplit);
   const bf16_t *q = (const bf16_t*)qbuf, *k = (const bf16_t*)kcache, *v = (const bf16_t*)vcache;
 #define SD_ATTN_LAUNCH(HD_, QTW_)                                                                              \
@@ -374,10 +366,10 @@ hipError_t launch_attention(hipStream_t st, int dtype, const void* qbuf, const v
   if (e != hipSuccess) return e;
   if (hd == 128)
     hipLaunchKernelGGL(attn_merge_k<128>, dim3(M, Hq), dim3(128), 0, st, scratch, rows.seq, rows.pos, (bf16_t*)out,
-                       RS, Hq, KW, NSP);
+                       RS, Hq, NSP);
   else
     hipLaunchKernelGGL(attn_merge_k<64>, dim3(M, Hq), dim3(64), 0, st, scratch, rows.seq, rows.pos, (bf16_t*)out, RS,
-                       Hq, KW, NSP);
+                       Hq, NSP);
   return hipGetLastError();
 }
 

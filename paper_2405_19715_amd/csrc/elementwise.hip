@@ -11,46 +11,67 @@ namespace {
 
 constexpr int EW_THREADS = 256;
 
+// RMSNorm is split in two launches so that a handful of rows still fills the chip:
+// the first kernel (embedding gather, or residual + partial sums) writes x and one
+// sum of squares per 1024-column block; the second adds those in block order and
+// scales.  Both run (columns / 1024) x rows workgroups.
+constexpr int NORM_COLS = 4 * EW_THREADS;
+
 template <typename T>
-__global__ __launch_bounds__(EW_THREADS) void embed_norm_k(const T* __restrict__ emb, const T* __restrict__ g,
-                                                           float eps, const int32_t* __restrict__ tok,
-                                                           float* __restrict__ x, T* __restrict__ xn, int d,
-                                                           int vocab) {
+__global__ __launch_bounds__(EW_THREADS) void embed_k(const T* __restrict__ emb, const int32_t* __restrict__ tok,
+                                                      float* __restrict__ x, float* __restrict__ ssq, int d,
+                                                      int vocab) {
   __shared__ float red[EW_THREADS / 64];
-  const int m = blockIdx.x;
+  const int m = blockIdx.y;
   int t = tok[m];
   t = t < 0 ? 0 : (t >= vocab ? vocab - 1 : t);
   const T* e = emb + (size_t)t * d;
   float ss = 0.f;
-  for (int i = threadIdx.x; i < d; i += EW_THREADS) {
-    const float v = Elem<T>::ld(e + i);
-    x[(size_t)m * d + i] = v;
-    ss = fmaf(v, v, ss);
+#pragma unroll
+  for (int u = 0; u < 4; ++u) {
+    const int i = blockIdx.x * NORM_COLS + u * EW_THREADS + threadIdx.x;
+    if (i < d) {
+      const float v = Elem<T>::ld(e + i);
+      x[(size_t)m * d + i] = v;
+      ss = fmaf(v, v, ss);
+    }
   }
   ss = block_sum(ss, red);
-  const float inv = 1.0f / sqrtf(ss / (float)d + eps);
-  for (int i = threadIdx.x; i < d; i += EW_THREADS)
-    Elem<T>::st(xn + (size_t)m * d + i, x[(size_t)m * d + i] * inv * Elem<T>::ld(g + i));
+  if (threadIdx.x == 0) ssq[m * gridDim.x + blockIdx.x] = ss;
+}
+
+__global__ __launch_bounds__(EW_THREADS) void add_partials_k(const float* __restrict__ part, int S,
+                                                             float* __restrict__ x, float* __restrict__ ssq, int M,
+                                                             int d) {
+  __shared__ float red[EW_THREADS / 64];
+  const int m = blockIdx.y;
+  float ss = 0.f;
+#pragma unroll
+  for (int u = 0; u < 4; ++u) {
+    const int i = blockIdx.x * NORM_COLS + u * EW_THREADS + threadIdx.x;
+    if (i < d) {
+      float v = x[(size_t)m * d + i];
+      for (int s = 0; s < S; ++s) v += part[((size_t)s * M + m) * d + i];
+      x[(size_t)m * d + i] = v;
+      ss = fmaf(v, v, ss);
+    }
+  }
+  ss = block_sum(ss, red);
+  if (threadIdx.x == 0) ssq[m * gridDim.x + blockIdx.x] = ss;
 }
 
 template <typename T>
-__global__ __launch_bounds__(EW_THREADS) void add_norm_k(const float* __restrict__ part, int S,
-                                                         const T* __restrict__ g, float eps,
-                                                         float* __restrict__ x, T* __restrict__ xn, int M,
-                                                         int d) {
-  __shared__ float red[EW_THREADS / 64];
-  const int m = blockIdx.x;
+__global__ __launch_bounds__(EW_THREADS) void norm_k(const float* __restrict__ x, const float* __restrict__ ssq,
+                                                     const T* __restrict__ g, float eps, T* __restrict__ xn, int d) {
+  const int m = blockIdx.y;
   float ss = 0.f;
-  for (int i = threadIdx.x; i < d; i += EW_THREADS) {
-    float v = x[(size_t)m * d + i];
-    for (int s = 0; s < S; ++s) v += part[((size_t)s * M + m) * d + i];
-    x[(size_t)m * d + i] = v;
-    ss = fmaf(v, v, ss);
-  }
-  ss = block_sum(ss, red);
+  for (int b = 0; b < (int)gridDim.x; ++b) ss += ssq[m * gridDim.x + b];
   const float inv = 1.0f / sqrtf(ss / (float)d + eps);
-  for (int i = threadIdx.x; i < d; i += EW_THREADS)
-    Elem<T>::st(xn + (size_t)m * d + i, x[(size_t)m * d + i] * inv * Elem<T>::ld(g + i));
+#pragma unroll
+  for (int u = 0; u < 4; ++u) {
+    const int i = blockIdx.x * NORM_COLS + u * EW_THREADS + threadIdx.x;
+    if (i < d) Elem<T>::st(xn + (size_t)m * d + i, x[(size_t)m * d + i] * inv * Elem<T>::ld(g + i));
+  }
 }
 
 // One block per (row, head slot): slots [0, Hq) are query heads, [Hq, Hq+Hkv) key
@@ -148,24 +169,33 @@ inline bool bad_rows(int M) { return M < 1 || M > MAX_ROWS; }
   if ((dtype) == DT_F32) { CALL_F32; } else if ((dtype) == DT_BF16) { CALL_BF16; } else return hipErrorInvalidValue;
 
 hipError_t launch_embed_norm(hipStream_t st, int dtype, const void* emb, const void* g, float eps,
-                             const int32_t* tok, float* x, void* xn, int M, int d, int vocab) {
-  if (bad_rows(M) || d < 1 || !emb || !g || !tok || !x || !xn) return hipErrorInvalidValue;
+                             const int32_t* tok, float* x, void* xn, float* ssq, int M, int d, int vocab) {
+  if (bad_rows(M) || d < 1 || !emb || !g || !tok || !x || !xn || !ssq) return hipErrorInvalidValue;
+  const dim3 grid((d + NORM_COLS - 1) / NORM_COLS, M);
+  if (grid.x > NORM_MAX_BLOCKS) return hipErrorInvalidValue;
   SD_DISPATCH_T(dtype,
-                hipLaunchKernelGGL(embed_norm_k<float>, dim3(M), dim3(EW_THREADS), 0, st, (const float*)emb,
-                                   (const float*)g, eps, tok, x, (float*)xn, d, vocab),
-                hipLaunchKernelGGL(embed_norm_k<bf16_t>, dim3(M), dim3(EW_THREADS), 0, st, (const bf16_t*)emb,
-                                   (const bf16_t*)g, eps, tok, x, (bf16_t*)xn, d, vocab));
+                hipLaunchKernelGGL(embed_k<float>, grid, dim3(EW_THREADS), 0, st, (const float*)emb, tok, x, ssq, d,
+                                   vocab);
+                hipLaunchKernelGGL(norm_k<float>, grid, dim3(EW_THREADS), 0, st, x, ssq, (const float*)g, eps,
+                                   (float*)xn, d),
+                hipLaunchKernelGGL(embed_k<bf16_t>, grid, dim3(EW_THREADS), 0, st, (const bf16_t*)emb, tok, x, ssq, d,
+                                   vocab);
+                hipLaunchKernelGGL(norm_k<bf16_t>, grid, dim3(EW_THREADS), 0, st, x, ssq, (const bf16_t*)g, eps,
+                                   (bf16_t*)xn, d));
   return hipGetLastError();
 }
 
 hipError_t launch_add_norm(hipStream_t st, int dtype, const float* part, int S, const void* g, float eps,
-                           float* x, void* xn, int M, int d) {
-  if (bad_rows(M) || d < 1 || S < 1 || !part || !g || !x || !xn) return hipErrorInvalidValue;
+                           float* x, void* xn, float* ssq, int M, int d) {
+  if (bad_rows(M) || d < 1 || S < 1 || !part || !g || !x || !xn || !ssq) return hipErrorInvalidValue;
+  const dim3 grid((d + NORM_COLS - 1) / NORM_COLS, M);
+  if (grid.x > NORM_MAX_BLOCKS) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(add_partials_k, grid, dim3(EW_THREADS), 0, st, part, S, x, ssq, M, d);
   SD_DISPATCH_T(dtype,
-                hipLaunchKernelGGL(add_norm_k<float>, dim3(M), dim3(EW_THREADS), 0, st, part, S,
-                                   (const float*)g, eps, x, (float*)xn, M, d),
-                hipLaunchKernelGGL(add_norm_k<bf16_t>, dim3(M), dim3(EW_THREADS), 0, st, part, S,
-                                   (const bf16_t*)g, eps, x, (bf16_t*)xn, M, d));
+                hipLaunchKernelGGL(norm_k<float>, grid, dim3(EW_THREADS), 0, st, x, ssq, (const float*)g, eps,
+                                   (float*)xn, d),
+                hipLaunchKernelGGL(norm_k<bf16_t>, grid, dim3(EW_THREADS), 0, st, x, ssq, (const bf16_t*)g, eps,
+                                   (bf16_t*)xn, d));
   return hipGetLastError();
 }
 

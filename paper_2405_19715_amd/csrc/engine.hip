@@ -65,7 +65,7 @@ struct sd_ctx {
   // activations (sized for the wider model)
   float* x = nullptr;
   void *xn = nullptr, *qbuf = nullptr, *attn = nullptr, *act = nullptr, *hz[2] = {nullptr, nullptr};
-  float *part = nullptr, *attn_scratch = nullptr;
+  float *part = nullptr, *attn_scratch = nullptr, *ssq = nullptr;
   float *q_logits = nullptr, *p_logits = nullptr, *fw_logits = nullptr, *stats = nullptr;
   RowPlan rows{};
   SeqState s{};
@@ -228,7 +228,7 @@ sd_status forward(sd_ctx* c, ModelRt& rt, int M, int RS, int max_kv_len, const i
   const sd_model& m = rt.m;
   const int dt = m.dtype, d = m.d_model, nq = rt.n_q(), nkv = rt.n_kv();
   hipStream_t st = c->st;
-  SD_HIP(launch_embed_norm(st, dt, m.tok_emb, rt.na[0], m.rms_eps, c->rows.tok, c->x, c->xn, M, d, m.vocab));
+  SD_HIP(launch_embed_norm(st, dt, m.tok_emb, rt.na[0], m.rms_eps, c->rows.tok, c->x, c->xn, c->ssq, M, d, m.vocab));
   for (int l = 0; l < m.n_layers; ++l) {
     const bool pr = profile && c->prof_every > 0 && (l % c->prof_every) == 0;
     sd_status s;
@@ -240,12 +240,12 @@ sd_status forward(sd_ctx* c, ModelRt& rt, int M, int RS, int max_kv_len, const i
     SD_HIP(launch_attention(st, dt, c->qbuf, kc, vc, c->rows, c->attn, c->attn_scratch, M, RS, m.n_heads,
                             m.n_kv_heads, m.head_dim, c->cfg.max_seq, max_kv_len));
     if ((s = gemm(c, rt, rt.wo[l], c->attn, nq, nullptr, M, d, nq, pr ? 1 : -1)) != SD_OK) return s;
-    SD_HIP(launch_add_norm(st, dt, c->part, gemm_splits(dt, M, d, nq), rt.nm[l], m.rms_eps, c->x, c->xn, M, d));
+    SD_HIP(launch_add_norm(st, dt, c->part, gemm_splits(dt, M, d, nq), rt.nm[l], m.rms_eps, c->x, c->xn, c->ssq, M, d));
     if ((s = gemm(c, rt, rt.wgu[l], c->xn, d, nullptr, M, 2 * m.d_ffn, d, pr ? 2 : -1)) != SD_OK) return s;
     SD_HIP(launch_silu_mul(st, dt, c->part, gemm_splits(dt, M, 2 * m.d_ffn, d), c->act, M, m.d_ffn));
     if ((s = gemm(c, rt, rt.wdown[l], c->act, m.d_ffn, nullptr, M, d, m.d_ffn, pr ? 3 : -1)) != SD_OK) return s;
     const void* g_next = (l + 1 < m.n_layers) ? rt.na[l + 1] : m.final_norm;
-    SD_HIP(launch_add_norm(st, dt, c->part, gemm_splits(dt, M, d, m.d_ffn), g_next, m.rms_eps, c->x, c->xn, M, d));
+    SD_HIP(launch_add_norm(st, dt, c->part, gemm_splits(dt, M, d, m.d_ffn), g_next, m.rms_eps, c->x, c->xn, c->ssq, M, d));
   }
   if (logits_out) {
     sd_status s;
@@ -409,6 +409,7 @@ sd_status sd_create(sd_ctx** out, const sd_model* target, const sd_model* draft,
   SD_ALLOC(c->hz[1], (size_t)B * hzmax * 4, true);
   SD_ALLOC(c->part, part_floats(c) * 4, false);
   SD_ALLOC(c->attn_scratch, attn_fl * 4, false);
+  SD_ALLOC(c->ssq, (size_t)MAX_ROWS * NORM_MAX_BLOCKS * 4, true);
   SD_ALLOC(c->q_logits, (size_t)B * cfg->k_max * V * 4, true);
   SD_ALLOC(c->p_logits, (size_t)B * (cfg->k_max + 1) * V * 4, true);
   SD_ALLOC(c->fw_logits, (size_t)PREFILL_CHUNK * V * 4, true);

@@ -3,24 +3,30 @@
 // This is the kernel the verify pass (M = K+1 rows, Algorithm 2's parallel target
 // forward) and the draft steps (M = 1 or 2 rows) spend their time in: every weight
 // is read from HBM exactly once per call and used for M multiply-adds, so the
-// kernel is bound by HBM bandwidth, and its whole design is about keeping many
-// 16-byte weight loads in flight per wavefront.
+// kernel is bound by HBM bandwidth and its design is about how the weight stream
+// is laid over workgroups, wavefronts and time.
 //
 // bf16 layout of the work
-//   workgroup  = 4 wavefronts = 64 consecutive weight rows x one K-slice
-//   wavefront  = 16 weight rows; lane (r = lane % 16, g = lane / 16) loads, per step of
-//                128 k, the 64 contiguous bytes W[row0 + r, k0 + 32 g .. k0 + 32 g + 32),
-//                so the wave reads 16 rows x 256 B per step and walks each row
-//                sequentially.
-//   X slice    = staged once per workgroup into LDS, already in the order the
-//                multiply needs, then read with conflict-free 16-byte LDS loads.
+//   grid       = G row groups x S K-slices.  A workgroup (4 wavefronts) belongs to one
+//                K-slice for its whole life: it stages that slice of X into LDS once
+//                (already in the order the multiply needs) and never synchronises again.
+//   wavefront  = walks its own list of 16-row weight tiles (tile = slot, slot + 4G, ...)
+//                with ONE continuous software pipeline of 16-byte loads that runs across
+//                tile boundaries; lane (r = lane % 16, g = lane / 16) loads, per 128-k
+//                step, 4 x 16 B of row r (instruction j covers the 64 contiguous bytes
+//                k0 + 32 j .. of every row, lane group g the 16 B at + 8 g).
+//   rotation   = each wavefront starts its slice at a different k-step (and wraps), so
+//                that the thousands of concurrent row streams, whose row stride is a
+//                large power of two, do not all hit the same HBM channels at once.
+//   few, long-lived workgroups (about two per CU) measured faster than many short ones:
+//                fewer concurrent DRAM streams and no repeated X staging.
 //   M >= 5     : v_mfma_f32_16x16x32_bf16, weights as the A operand (16 rows x 32 k),
 //                X^T as the B operand (32 k x 16 activation rows), one MFMA per 16-row
-//                tile of X.  The k index inside an MFMA is a permutation of the real
-//                k (lane group g holds k0 + 32 g + 8 j .. + 8 for MFMA j); A and B use
-//                the same permutation, and a dot product does not care.
+//                tile of X; the last tile keeps only its live rows in LDS.
 //   M <= 4     : no MFMA; per-lane fp32 dot products over the same loads, then a
 //                reduction over the 4 lane groups with two wavefront shuffles.
+// Per-slice partial sums go to part[s] and are added by the consumer in slice order,
+// so results do not depend on scheduling.
 // fp32 weights (tiny configuration) take a plain wave-per-output-row kernel.
 #include "common.hpp"
 #include "kernels.hpp"
@@ -32,25 +38,46 @@ namespace sd {
 namespace {
 
 constexpr int GEMM_THREADS = 256;
-constexpr int ROWS_PER_WG = 64;
 constexpr int KSTEP = 128;
-constexpr int LDS_BUDGET = 64 * 1024;
+constexpr int LDS_MAX = 72 * 1024;       // X slice per workgroup: two workgroups fit a CU's 160 KB
 constexpr int PREFETCH = 4;              // steps of weight loads in flight per wave
+constexpr int TARGET_WGS = 512;          // about two resident workgroups per CU
 
-struct Split { int S, steps_per; };
+struct Split { int S, steps_per, G; };
 
+// Pick the K-slice length and the number of row groups: slices as long as LDS allows
+// (fewer partial sums), about TARGET_WGS workgroups, and row tiles / slices that divide
+// evenly over wavefronts so that no wave is left with a longer list than the others.
 Split plan_bf16(int M, int N, int K) {
   const int total = K / KSTEP;
-  int max_steps = LDS_BUDGET / (M * KSTEP * 2);
+  const int ntiles = N / 16;
+  int max_steps = LDS_MAX / (M * KSTEP * 2);
   if (max_steps < 1) max_steps = 1;
   if (max_steps > total) max_steps = total;
-  int S = (total + max_steps - 1) / max_steps;
-  const int wgs_n = (N + ROWS_PER_WG - 1) / ROWS_PER_WG;
-  // more slices until the grid can fill 256 CUs four deep, but keep slices >= 4 steps
-  while (wgs_n * S < 1024 && (total + S) / (S + 1) >= 4) ++S;
-  const int steps_per = (total + S - 1) / S;
-  S = (total + steps_per - 1) / steps_per;
-  return {S, steps_per};
+  const int g_max = (ntiles + 3) / 4;
+  Split best{1, total, 1};
+  double best_score = -1.0;
+  for (int sp = max_steps; sp >= 1; --sp) {
+    const int S = (total + sp - 1) / sp;
+    const double eff_k = (double)total / ((double)S * sp);
+    int g_lo = (TARGET_WGS * 3 / 4) / S, g_hi = (TARGET_WGS * 5 / 4) / S;
+    if (g_lo < 1) g_lo = 1;
+    if (g_hi < g_lo) g_hi = g_lo;
+    if (g_lo > g_max) g_lo = g_max;
+    if (g_hi > g_max) g_hi = g_max;
+    for (int G = g_lo; G <= g_hi; ++G) {
+      const int per = (ntiles + 4 * G - 1) / (4 * G);
+      const double eff_rows = (double)ntiles / ((double)per * 4 * G);
+      double fill = (double)(G * S) / TARGET_WGS;
+      if (fill > 1.0) fill = 1.0 / fill;                       // too many workgroups costs as well
+      const double work = (double)per * sp;                    // steps per wavefront
+      const double ramp = work / (work + 6.0);                 // pipeline fill / drain per wavefront
+      const double partial = 1.0 / (1.0 + 0.55 * M / (16.0 * sp));   // partial-sum traffic vs weight bytes
+      const double score = eff_k * eff_rows * (0.5 + 0.5 * fill) * ramp * partial;
+      if (score > best_score) { best_score = score; best = {S, sp, G}; }
+    }
+  }
+  return best;
 }
 
 __device__ __forceinline__ uint4 ldg128(const bf16_t* p) { return *reinterpret_cast<const uint4*>(p); }
@@ -73,15 +100,16 @@ __device__ __forceinline__ float dot8(const uint4& a, const uint4& b, float acc)
   return acc;
 }
 
-// Stage X[0..M, kbeg .. kbeg + 128*steps) into LDS as 16-byte groups.
-//   MFMA order (mfma = true): group (m, step s, lane group g, j) lands at
+// Stage X[0..M, kbeg .. kbeg + 128*steps) into LDS as 16-byte groups.  Group o of a row
+// covers k = kbeg + 8 o ..; within a 128-k step it is (j = (o / 4) % 4, g = o % 4).
+//   MFMA order: group (m, step s, j, g) lands at
 //     tile_base(m / 16) + (((s*4 + j)*4 + g) * rows_in_tile + m % 16)
 //   so that lane (r, g) of MFMA j reads one 16-byte word at a lane-linear address.
-//   Row-major order (mfma = false): [m][k].
+//   Row-major order (dot path): [m][o].
 template <bool MFMA_ORDER>
 __device__ __forceinline__ void stage_x(uint4* lds, const bf16_t* X, int ldx, const int* xrow, int M, int kbeg,
                                         int steps) {
-  const int groups_per_row = steps * 16;             // 16-byte groups per activation row
+  const int groups_per_row = steps * 16;
   const int last_tile = (M - 1) >> 4;
   const int rows_last = M - (last_tile << 4);
   for (int idx = threadIdx.x; idx < M * groups_per_row; idx += GEMM_THREADS) {
@@ -89,7 +117,7 @@ __device__ __forceinline__ void stage_x(uint4* lds, const bf16_t* X, int ldx, co
     const int src_row = xrow ? xrow[m] : m;
     const uint4 v = ldg128(X + (size_t)src_row * ldx + kbeg + o * 8);
     if (MFMA_ORDER) {
-      const int s = o >> 4, g = (o >> 2) & 3, j = o & 3;
+      const int s = o >> 4, j = (o >> 2) & 3, g = o & 3;
       const int tile = m >> 4, r = m & 15;
       const int rows_in_tile = (tile == last_tile) ? rows_last : 16;
       lds[tile * groups_per_row * 16 + (((s * 4 + j) * 4 + g) * rows_in_tile + r)] = v;
@@ -99,147 +127,140 @@ __device__ __forceinline__ void stage_x(uint4* lds, const bf16_t* X, int ldx, co
   }
 }
 
-// ----------------------------------------------------------------------------- MFMA path
-template <int NT>   // NT = number of 16-row activation tiles, M in (16(NT-1), 16 NT]
-__global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_mfma(const bf16_t* __restrict__ W,
-                                                               const bf16_t* __restrict__ X, int ldx,
-                                                               const int* __restrict__ xrow,
-                                                               float* __restrict__ part, int M, int N, int K,
-                                                               int steps_per) {
+// What a wavefront needs to walk its tiles: see the file comment.
+struct WaveWalk {
+  const bf16_t* base;      // this lane's address at (tile 0 of the wave, step 0, j = 0)
+  size_t tile_stride;      // elements between consecutive tiles of the wave
+  int steps, rot, nwork;
+  __device__ __forceinline__ const bf16_t* at(int idx) const {
+    const int t = idx / steps;
+    int s = idx - t * steps + rot;
+    if (s >= steps) s -= steps;
+    return base + (size_t)t * tile_stride + s * KSTEP;
+  }
+};
+
+// MODE > 0: MFMA with NT = MODE activation tiles.  MODE < 0: dot products over -MODE rows.
+template <int MODE>
+__global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_stream(const bf16_t* __restrict__ W,
+                                                                 const bf16_t* __restrict__ X, int ldx,
+                                                                 const int* __restrict__ xrow,
+                                                                 float* __restrict__ part, int M, int N, int K,
+                                                                 int steps_per, int G) {
+  constexpr bool MFMA = MODE > 0;
+  constexpr int NT = MFMA ? MODE : 1;
+  constexpr int MV = MFMA ? 1 : -MODE;
   extern __shared__ uint4 lds[];
   const int total_steps = K / KSTEP;
-  const int sbeg = blockIdx.y * steps_per;
+  const int ks = blockIdx.y, grp = blockIdx.x;
+  const int sbeg = ks * steps_per;
   const int steps = min(steps_per, total_steps - sbeg);
   const int kbeg = sbeg * KSTEP;
-  stage_x<true>(lds, X, ldx, xrow, M, kbeg, steps);
-  __syncthreads();
-
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int r = lane & 15, g = lane >> 4;
-  const int row0 = blockIdx.x * ROWS_PER_WG + wave * 16;
-  if (row0 >= N) return;                              // N is a multiple of 16: whole tile in or out
-  const bf16_t* wp = W + (size_t)(row0 + r) * K + kbeg + g * 32;
+  const int ntiles = N >> 4;
+  const int wslot = grp * 4 + wave, nslots = G * 4;
+  const int my_tiles = wslot < ntiles ? (ntiles - wslot + nslots - 1) / nslots : 0;
+
+  WaveWalk ww;
+  ww.base = W + ((size_t)wslot * 16 + r) * K + kbeg + g * 8;
+  ww.tile_stride = (size_t)nslots * 16 * K;
+  ww.steps = steps;
+  ww.rot = (wslot * 5 + ks * 3) % steps;
+  ww.nwork = my_tiles * steps;
+
+  // weight loads go out before X is staged, so HBM is busy while the workgroup sets up
+  uint4 a[PREFETCH][4];
+#pragma unroll
+  for (int p = 0; p < PREFETCH; ++p)
+    if (p < ww.nwork) {
+      const bf16_t* q = ww.at(p);
+#pragma unroll
+      for (int j = 0; j < 4; ++j) a[p][j] = ldg128(q + j * 32);
+    }
+
+  stage_x<MFMA>(lds, X, ldx, xrow, M, kbeg, steps);
+  __syncthreads();
+
   const int groups_per_row = steps * 16;
   const int rows_last = M - ((NT - 1) << 4);
-
   floatx4 acc[NT];
+  float dacc[MV];
 #pragma unroll
   for (int t = 0; t < NT; ++t) acc[t] = floatx4{0.f, 0.f, 0.f, 0.f};
-
-  uint4 a[PREFETCH][4];
 #pragma unroll
-  for (int p = 0; p < PREFETCH; ++p)
-    if (p < steps) {
-#pragma unroll
-      for (int j = 0; j < 4; ++j) a[p][j] = ldg128(wp + p * KSTEP + j * 8);
-    }
+  for (int m = 0; m < MV; ++m) dacc[m] = 0.f;
+  float* pout = part + (size_t)ks * M * N;
+  int sl = 0, tile = 0;
 
-  for (int s0 = 0; s0 < steps; s0 += PREFETCH) {
+  for (int i0 = 0; i0 < ww.nwork; i0 += PREFETCH) {
 #pragma unroll
     for (int p = 0; p < PREFETCH; ++p) {
-      const int s = s0 + p;
-      if (s < steps) {
+      const int i = i0 + p;
+      if (i < ww.nwork) {
         uint4 cur[4];
 #pragma unroll
         for (int j = 0; j < 4; ++j) cur[j] = a[p][j];
-        if (s + PREFETCH < steps) {
+        if (i + PREFETCH < ww.nwork) {
+          const bf16_t* q = ww.at(i + PREFETCH);
 #pragma unroll
-          for (int j = 0; j < 4; ++j) a[p][j] = ldg128(wp + (s + PREFETCH) * KSTEP + j * 8);
+          for (int j = 0; j < 4; ++j) a[p][j] = ldg128(q + j * 32);
         }
+        int s = sl + ww.rot;
+        if (s >= steps) s -= steps;
+        if (MFMA) {
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          const bf16x8 av = as_bf16x8(cur[j]);
+          for (int j = 0; j < 4; ++j) {
+            const bf16x8 av = as_bf16x8(cur[j]);
 #pragma unroll
-          for (int t = 0; t < NT; ++t) {
-            uint4 bv;
-            if (t < NT - 1) {
-              bv = lds[t * groups_per_row * 16 + (((s * 4 + j) * 4 + g) * 16 + r)];
-            } else {
-              bv = (r < rows_last)
-                       ? lds[t * groups_per_row * 16 + (((s * 4 + j) * 4 + g) * rows_last + r)]
-                       : uint4{0u, 0u, 0u, 0u};
+            for (int t = 0; t < NT; ++t) {
+              uint4 bv;
+              if (t < NT - 1) {
+                bv = lds[t * groups_per_row * 16 + (((s * 4 + j) * 4 + g) * 16 + r)];
+              } else {
+                bv = (r < rows_last)
+                         ? lds[t * groups_per_row * 16 + (((s * 4 + j) * 4 + g) * rows_last + r)]
+                         : uint4{0u, 0u, 0u, 0u};
+              }
+              acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, as_bf16x8(bv), acc[t], 0, 0, 0);
             }
-            acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, as_bf16x8(bv), acc[t], 0, 0, 0);
           }
+        } else {
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+#pragma unroll
+            for (int m = 0; m < MV; ++m) {
+              const uint4 xv = lds[m * groups_per_row + s * 16 + j * 4 + g];   // one address per lane group
+              dacc[m] = dot8(cur[j], xv, dacc[m]);
+            }
+          }
+        }
+        if (++sl == steps) {                  // tile finished: write its partial sums, start the next
+          const int row0 = (wslot + tile * nslots) * 16;
+          if (MFMA) {
+            // D[i, n]: lane (n = lane % 16, i = 4 * (lane / 16) + 0..3): four consecutive weight
+            // rows for activation row n -> one 16-byte store.
+#pragma unroll
+            for (int t = 0; t < NT; ++t) {
+              const int m = t * 16 + r;
+              if (m < M) *reinterpret_cast<floatx4*>(pout + (size_t)m * N + row0 + 4 * g) = acc[t];
+              acc[t] = floatx4{0.f, 0.f, 0.f, 0.f};
+            }
+          } else {
+#pragma unroll
+            for (int m = 0; m < MV; ++m) {
+              float v = dacc[m];
+              v += __shfl_xor(v, 16, WAVE);
+              v += __shfl_xor(v, 32, WAVE);
+              if (g == 0) pout[(size_t)m * N + row0 + r] = v;
+              dacc[m] = 0.f;
+            }
+          }
+          sl = 0;
+          ++tile;
         }
       }
     }
-  }
-
-  // D[i, n]: lane (n = lane % 16, i = 4 * (lane / 16) + 0..3): four consecutive weight
-  // rows for activation row n -> one 16-byte store.
-  float* pout = part + (size_t)blockIdx.y * M * N;
-#pragma unroll
-  for (int t = 0; t < NT; ++t) {
-    const int m = t * 16 + r;
-    if (m < M) *reinterpret_cast<floatx4*>(pout + (size_t)m * N + row0 + 4 * g) = acc[t];
-  }
-}
-
-// ----------------------------------------------------------------------------- dot-product path
-template <int MV>   // MV = activation rows, 1..4
-__global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_dot(const bf16_t* __restrict__ W,
-                                                              const bf16_t* __restrict__ X, int ldx,
-                                                              const int* __restrict__ xrow,
-                                                              float* __restrict__ part, int N, int K,
-                                                              int steps_per) {
-  extern __shared__ uint4 lds[];
-  const int total_steps = K / KSTEP;
-  const int sbeg = blockIdx.y * steps_per;
-  const int steps = min(steps_per, total_steps - sbeg);
-  const int kbeg = sbeg * KSTEP;
-  stage_x<false>(lds, X, ldx, xrow, MV, kbeg, steps);
-  __syncthreads();
-
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int r = lane & 15, g = lane >> 4;
-  const int row0 = blockIdx.x * ROWS_PER_WG + wave * 16;
-  if (row0 >= N) return;
-  const bf16_t* wp = W + (size_t)(row0 + r) * K + kbeg + g * 32;
-  const int groups_per_row = steps * 16;
-
-  float acc[MV];
-#pragma unroll
-  for (int m = 0; m < MV; ++m) acc[m] = 0.f;
-
-  uint4 a[PREFETCH][4];
-#pragma unroll
-  for (int p = 0; p < PREFETCH; ++p)
-    if (p < steps) {
-#pragma unroll
-      for (int j = 0; j < 4; ++j) a[p][j] = ldg128(wp + p * KSTEP + j * 8);
-    }
-
-  for (int s0 = 0; s0 < steps; s0 += PREFETCH) {
-#pragma unroll
-    for (int p = 0; p < PREFETCH; ++p) {
-      const int s = s0 + p;
-      if (s < steps) {
-        uint4 cur[4];
-#pragma unroll
-        for (int j = 0; j < 4; ++j) cur[j] = a[p][j];
-        if (s + PREFETCH < steps) {
-#pragma unroll
-          for (int j = 0; j < 4; ++j) a[p][j] = ldg128(wp + (s + PREFETCH) * KSTEP + j * 8);
-        }
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-#pragma unroll
-          for (int m = 0; m < MV; ++m) {
-            const uint4 xv = lds[m * groups_per_row + s * 16 + g * 4 + j];   // same for the 16 lanes of a group
-            acc[m] = dot8(cur[j], xv, acc[m]);
-          }
-        }
-      }
-    }
-  }
-  float* pout = part + (size_t)blockIdx.y * MV * N;
-#pragma unroll
-  for (int m = 0; m < MV; ++m) {
-    float v = acc[m];
-    v += __shfl_xor(v, 16, WAVE);
-    v += __shfl_xor(v, 32, WAVE);
-    if (g == 0) pout[(size_t)m * N + row0 + r] = v;
   }
 }
 
@@ -275,23 +296,20 @@ __global__ __launch_bounds__(256) void gemm_f32(const float* __restrict__ W, con
   }
 }
 
-template <int NT>
-hipError_t launch_mfma(hipStream_t st, const bf16_t* W, const bf16_t* X, int ldx, const int* xrow, float* part,
-                       int M, int N, int K, Split sp) {
-  const dim3 grid((N + ROWS_PER_WG - 1) / ROWS_PER_WG, sp.S);
+template <int MODE>
+hipError_t launch_stream(hipStream_t st, const bf16_t* W, const bf16_t* X, int ldx, const int* xrow, float* part, int M,
+                         int N, int K, Split sp) {
+  const dim3 grid(sp.G, sp.S);
   const size_t lds = (size_t)M * sp.steps_per * KSTEP * 2;
-  hipLaunchKernelGGL(gemm_bf16_mfma<NT>, grid, dim3(GEMM_THREADS), lds, st, W, X, ldx, xrow, part, M, N, K,
-                     sp.steps_per);
-  return hipGetLastError();
-}
-
-template <int MV>
-hipError_t launch_dot(hipStream_t st, const bf16_t* W, const bf16_t* X, int ldx, const int* xrow, float* part,
-                      int N, int K, Split sp) {
-  const dim3 grid((N + ROWS_PER_WG - 1) / ROWS_PER_WG, sp.S);
-  const size_t lds = (size_t)MV * sp.steps_per * KSTEP * 2;
-  hipLaunchKernelGGL(gemm_bf16_dot<MV>, grid, dim3(GEMM_THREADS), lds, st, W, X, ldx, xrow, part, N, K,
-                     sp.steps_per);
+  static bool attr_set = false;          // dynamic LDS above 64 KB has to be allowed once per kernel
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_bf16_stream<MODE>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, LDS_MAX + 8 * 1024);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  hipLaunchKernelGGL(gemm_bf16_stream<MODE>, grid, dim3(GEMM_THREADS), lds, st, W, X, ldx, xrow, part, M, N, K,
+                     sp.steps_per, sp.G);
   return hipGetLastError();
 }
 
@@ -320,24 +338,24 @@ hipError_t launch_gemm(hipStream_t st, int dtype, const void* W, const void* X, 
   const bf16_t* x = (const bf16_t*)X;
   if (M <= 4) {
     switch (M) {
-      case 1: return launch_dot<1>(st, w, x, ldx, xrow, part, N, K, sp);
-      case 2: return launch_dot<2>(st, w, x, ldx, xrow, part, N, K, sp);
-      case 3: return launch_dot<3>(st, w, x, ldx, xrow, part, N, K, sp);
-      default: return launch_dot<4>(st, w, x, ldx, xrow, part, N, K, sp);
+      case 1: return launch_stream<-1>(st, w, x, ldx, xrow, part, M, N, K, sp);
+      case 2: return launch_stream<-2>(st, w, x, ldx, xrow, part, M, N, K, sp);
+      case 3: return launch_stream<-3>(st, w, x, ldx, xrow, part, M, N, K, sp);
+      default: return launch_stream<-4>(st, w, x, ldx, xrow, part, M, N, K, sp);
     }
   }
   const int nt = (M + 15) / 16;
   switch (nt) {
-    case 1: return launch_mfma<1>(st, w, x, ldx, xrow, part, M, N, K, sp);
-    case 2: return launch_mfma<2>(st, w, x, ldx, xrow, part, M, N, K, sp);
-    case 3: return launch_mfma<3>(st, w, x, ldx, xrow, part, M, N, K, sp);
-    case 4: return launch_mfma<4>(st, w, x, ldx, xrow, part, M, N, K, sp);
-    case 5: return launch_mfma<5>(st, w, x, ldx, xrow, part, M, N, K, sp);
-    case 6: return launch_mfma<6>(st, w, x, ldx, xrow, part, M, N, K, sp);
-    case 7: return launch_mfma<7>(st, w, x, ldx, xrow, part, M, N, K, sp);
-    case 8: return launch_mfma<8>(st, w, x, ldx, xrow, part, M, N, K, sp);
-    case 9: return launch_mfma<9>(st, w, x, ldx, xrow, part, M, N, K, sp);
-    case 10: return launch_mfma<10>(st, w, x, ldx, xrow, part, M, N, K, sp);
+    case 1: return launch_stream<1>(st, w, x, ldx, xrow, part, M, N, K, sp);
+    case 2: return launch_stream<2>(st, w, x, ldx, xrow, part, M, N, K, sp);
+    case 3: return launch_stream<3>(st, w, x, ldx, xrow, part, M, N, K, sp);
+    case 4: return launch_stream<4>(st, w, x, ldx, xrow, part, M, N, K, sp);
+    case 5: return launch_stream<5>(st, w, x, ldx, xrow, part, M, N, K, sp);
+    case 6: return launch_stream<6>(st, w, x, ldx, xrow, part, M, N, K, sp);
+    case 7: return launch_stream<7>(st, w, x, ldx, xrow, part, M, N, K, sp);
+    case 8: return launch_stream<8>(st, w, x, ldx, xrow, part, M, N, K, sp);
+    case 9: return launch_stream<9>(st, w, x, ldx, xrow, part, M, N, K, sp);
+    case 10: return launch_stream<10>(st, w, x, ldx, xrow, part, M, N, K, sp);
     default: return hipErrorInvalidValue;
   }
 }

@@ -28,12 +28,14 @@ struct RowPlan {           // device arrays, one entry per activation row
 };
 
 // ---------------------------------------------------------------- elementwise
+// `ssq` is scratch for per-block sums of squares: MAX_ROWS * NORM_MAX_BLOCKS floats.
+constexpr int NORM_MAX_BLOCKS = 64;    // d <= 65536
 // x[m,:] = E[tok[m],:]; xn[m,:] = rmsnorm(x[m,:]) * g
 hipError_t launch_embed_norm(hipStream_t st, int dtype, const void* emb, const void* g, float eps,
-                             const int32_t* tok, float* x, void* xn, int M, int d, int vocab);
+                             const int32_t* tok, float* x, void* xn, float* ssq, int M, int d, int vocab);
 // x[m,:] += sum_s part[s,m,:]; xn[m,:] = rmsnorm(x[m,:]) * g
 hipError_t launch_add_norm(hipStream_t st, int dtype, const float* part, int S, const void* g, float eps,
-                           float* x, void* xn, int M, int d);
+                           float* x, void* xn, float* ssq, int M, int d);
 // q,k,v = sum_s part[s,m,:]; rotary embedding on q,k at pos[m]; q -> qbuf [M, Hq*hd];
 // k -> kcache[seq, kvh, pos, :]; v -> vcache[seq, kvh, :, pos] (transposed), rows with seq < 0 skipped
 hipError_t launch_rope_kv(hipStream_t st, int dtype, const float* part, int S, const RowPlan& rows,
