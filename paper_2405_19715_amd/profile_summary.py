@@ -1,0 +1,84 @@
+"""Condense a `rocprofv3 --kernel-trace --output-format csv` trace of bench.py into a
+short text summary per phase of a round.
+
+    python -m paper_2405_19715_amd.profile_summary <..._kernel_trace.csv> [--skip-rounds W]
+
+The whole-process statistics rocprofv3 prints mix the untimed prefill (which runs the
+same GEMM kernel over 32-row prompt chunks of both models) into every average.  This
+script cuts the trace at the kernels that open a round (begin_round_k) and a target
+pass (plan_verify_k) and reports the rounds after the first `--skip-rounds` only.
+"""
+from __future__ import annotations
+
+import argparse
+import collections
+import csv
+import re
+import sys
+
+
+def short_name(name: str) -> str:
+    name = name.replace("(anonymous namespace)::", "")
+    m = re.match(r"(?:void )?([\w:]+(?:<[^(]*>)?)", name)
+    return (m.group(1) if m else name)[:48]
+
+
+def load(path):
+    rows = []
+    with open(path, newline="") as f:
+        for r in csv.DictReader(f):
+            rows.append((short_name(r["Kernel_Name"]), int(r["Start_Timestamp"]), int(r["End_Timestamp"])))
+    rows.sort(key=lambda r: r[1])
+    return rows
+
+
+def table(segments, title, out):
+    """segments: list of launch lists, each one contiguous stretch of the stream."""
+    agg = collections.OrderedDict()
+    for rows in segments:
+        for name, s, e in rows:
+            a = agg.setdefault(name, [0, 0])
+            a[0] += 1
+            a[1] += e - s
+    busy = sum(a[1] for a in agg.values())
+    span = sum(rows[-1][2] - rows[0][1] for rows in segments)
+    out.write(f"{title}: {sum(len(r) for r in segments)} launches, busy {busy / 1e6:.3f} ms, span {span / 1e6:.3f} ms, "
+              f"idle between kernels {(span - busy) / 1e6:.3f} ms\n")
+    for name, (n, t) in sorted(agg.items(), key=lambda kv: -kv[1][1]):
+        out.write(f"  {name:48s} calls {n:6d}  avg {t / n / 1e3:9.2f} us  total {t / 1e6:9.3f} ms  {100.0 * t / span:5.1f}%\n")
+
+
+def main(argv=None):
+    ap = argparse.ArgumentParser()
+    ap.add_argument("trace")
+    ap.add_argument("--skip-rounds", type=int, default=2)
+    args = ap.parse_args(argv)
+    rows = load(args.trace)
+    starts = [i for i, r in enumerate(rows) if "begin_round_k" in r[0]]
+    if len(starts) <= args.skip_rounds:
+        raise SystemExit("trace holds too few rounds")
+    starts = starts[args.skip_rounds:]
+    draft, verify = [], []
+    n_rounds = 0
+    for a, b in zip(starts, starts[1:] + [len(rows)]):
+        rnd = rows[a:b]
+        cut = next((i for i, r in enumerate(rnd) if "plan_verify_k" in r[0]), None)
+        commit = next((i for i, r in enumerate(rnd) if "commit_k" in r[0]), None)
+        if cut is None or commit is None:
+            continue
+        draft.append(rnd[:cut])
+        verify.append(rnd[cut:commit + 1])
+        n_rounds += 1
+    out = sys.stdout
+    out.write(f"rounds summarised: {n_rounds} (first {args.skip_rounds} skipped)\n")
+    d_steps = sum(sum(1 for r in d if "plan_draft_k" in r[0]) for d in draft)
+    d_span = sum(d[-1][2] - d[0][1] for d in draft)
+    v_span = sum(v[-1][2] - v[0][1] for v in verify)
+    out.write(f"draft steps: {d_steps}, mean draft-step span {d_span / max(d_steps, 1) / 1e6:.3f} ms; "
+              f"mean target pass + accept span {v_span / n_rounds / 1e6:.3f} ms\n")
+    table(draft, "draft loops (all summarised rounds)", out)
+    table(verify, "target pass + accept + commit (all summarised rounds)", out)
+
+
+if __name__ == "__main__":
+    main()
