@@ -215,6 +215,9 @@ __global__ __launch_bounds__(HD) void attn_merge_k(const float* __restrict__ scr
                                                    const int32_t* __restrict__ row_pos, bf16_t* __restrict__ out, int RS,
                                                    int Hq, int NSP) {
   constexpr int STRIDE = HD + 4;
+  constexpr int MAXP = 512;            // key blocks whose weights fit the LDS table (32768 keys)
+  __shared__ float s_w[MAXP];
+  __shared__ float s_l[MAXP];
   const int m = blockIdx.x, h = blockIdx.y, d = threadIdx.x;
   bf16_t* dst = out + ((size_t)m * Hq + h) * HD + d;
   if (row_seq[m] < 0) {
@@ -228,14 +231,21 @@ __global__ __launch_bounds__(HD) void attn_merge_k(const float* __restrict__ scr
     if (row_seq[mm] >= 0) kv_end = max(kv_end, row_pos[mm] + 1);
   }
   const float* src = scratch + ((size_t)m * Hq + h) * NSP * STRIDE;
-  const int nsp = min(NSP, (kv_end + KB - 1) / KB);
+  const int nsp = min(min(NSP, MAXP), (kv_end + KB - 1) / KB);
+  // the partials' maxima and sums go through LDS once; every thread then owns one column
+  for (int sp = d; sp < nsp; sp += HD) {
+    s_w[sp] = src[sp * STRIDE + HD];
+    s_l[sp] = src[sp * STRIDE + HD + 1];
+  }
+  __syncthreads();
   float mx = NEG_BIG;
-  for (int sp = 0; sp < nsp; ++sp) mx = fmaxf(mx, src[sp * STRIDE + HD]);
+  for (int sp = 0; sp < nsp; ++sp) mx = fmaxf(mx, s_w[sp]);
   float num = 0.f, den = 0.f;
+#pragma unroll 8
   for (int sp = 0; sp < nsp; ++sp) {
-    const float w = __expf(src[sp * STRIDE + HD] - mx);
+    const float w = __expf(s_w[sp] - mx);
     num = fmaf(w, src[sp * STRIDE + d], num);
-    den = fmaf(w, src[sp * STRIDE + HD + 1], den);
+    den = fmaf(w, s_l[sp], den);
   }
   *dst = f2bf(den > 0.f ? num / den : 0.f);
 }
@@ -346,7 +356,8 @@ hipError_t launch_attention(hipStream_t st, int dtype, const void* qbuf, const v
                          hd, max_seq);
     return hipGetLastError();
   }
-  if (dtype != DT_BF16 || (hd != 64 && hd != 128) || max_seq % KB != 0 || !scratch) return hipErrorInvalidValue;
+  if (dtype != DT_BF16 || (hd != 64 && hd != 128) || max_seq % KB != 0 || max_seq > 512 * KB || !scratch)
+    return hipErrorInvalidValue;
   const MfmaShape sh = mfma_shape(RS, Hq / Hkv);
   const int KW = 4 / sh.QW;
   const int nsplit = ((max_kv_len + KB - 1) / KB + KW - 1) / KW;

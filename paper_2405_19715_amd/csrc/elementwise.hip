@@ -74,6 +74,68 @@ __global__ __launch_bounds__(EW_THREADS) void norm_k(const float* __restrict__ x
   }
 }
 
+// Residual add + RMSNorm of one row by one 1024-thread workgroup: every thread owns up
+// to 4 float4 column groups, issues all of its partial-sum loads at once, keeps the
+// sums in registers across the row-wide reduction, and writes x and xn.  Used when
+// d <= 16384 and d % 4 == 0; one launch instead of two.
+constexpr int ROW_THREADS = 1024;
+constexpr int ROW_MAXU = 4;
+
+template <typename T> struct Pack4;
+template <> struct Pack4<float> {
+  static __device__ __forceinline__ float4 ld(const float* p) { return *reinterpret_cast<const float4*>(p); }
+  static __device__ __forceinline__ void st(float* p, float4 v) { *reinterpret_cast<float4*>(p) = v; }
+};
+template <> struct Pack4<bf16_t> {
+  static __device__ __forceinline__ float4 ld(const bf16_t* p) {
+    const uint2 u = *reinterpret_cast<const uint2*>(p);
+    return float4{__uint_as_float(u.x << 16), __uint_as_float(u.x & 0xffff0000u), __uint_as_float(u.y << 16),
+                  __uint_as_float(u.y & 0xffff0000u)};
+  }
+  static __device__ __forceinline__ void st(bf16_t* p, float4 v) {
+    uint2 u;
+    u.x = (uint32_t)f2bf(v.x) | ((uint32_t)f2bf(v.y) << 16);
+    u.y = (uint32_t)f2bf(v.z) | ((uint32_t)f2bf(v.w) << 16);
+    *reinterpret_cast<uint2*>(p) = u;
+  }
+};
+
+template <typename T>
+__global__ __launch_bounds__(ROW_THREADS) void add_norm_row_k(const float* __restrict__ part, int S,
+                                                              const T* __restrict__ g, float eps,
+                                                              float* __restrict__ x, T* __restrict__ xn, int M, int d) {
+  __shared__ float red[ROW_THREADS / 64];
+  const int m = blockIdx.x;
+  float4 v[ROW_MAXU];
+  float ss = 0.f;
+#pragma unroll
+  for (int u = 0; u < ROW_MAXU; ++u) {
+    const int i = (u * ROW_THREADS + threadIdx.x) * 4;
+    if (i < d) {
+      float4 a = *reinterpret_cast<const float4*>(x + (size_t)m * d + i);
+#pragma unroll 4
+      for (int s = 0; s < S; ++s) {
+        const float4 p = *reinterpret_cast<const float4*>(part + ((size_t)s * M + m) * d + i);
+        a.x += p.x; a.y += p.y; a.z += p.z; a.w += p.w;
+      }
+      *reinterpret_cast<float4*>(x + (size_t)m * d + i) = a;
+      v[u] = a;
+      ss += a.x * a.x + a.y * a.y + a.z * a.z + a.w * a.w;
+    }
+  }
+  ss = block_sum(ss, red);
+  const float inv = 1.0f / sqrtf(ss / (float)d + eps);
+#pragma unroll
+  for (int u = 0; u < ROW_MAXU; ++u) {
+    const int i = (u * ROW_THREADS + threadIdx.x) * 4;
+    if (i < d) {
+      const float4 gg = Pack4<T>::ld(g + i);
+      Pack4<T>::st(xn + (size_t)m * d + i,
+                   float4{v[u].x * inv * gg.x, v[u].y * inv * gg.y, v[u].z * inv * gg.z, v[u].w * inv * gg.w});
+    }
+  }
+}
+
 // One block per (row, head slot): slots [0, Hq) are query heads, [Hq, Hq+Hkv) key
 // heads, [Hq+Hkv, Hq+2Hkv) value heads.
 template <typename T>
@@ -190,6 +252,14 @@ hipError_t launch_add_norm(hipStream_t st, int dtype, const float* part, int S, 
   if (bad_rows(M) || d < 1 || S < 1 || !part || !g || !x || !xn || !ssq) return hipErrorInvalidValue;
   const dim3 grid((d + NORM_COLS - 1) / NORM_COLS, M);
   if (grid.x > NORM_MAX_BLOCKS) return hipErrorInvalidValue;
+  if (d % 4 == 0 && d <= ROW_THREADS * 4 * ROW_MAXU) {
+    SD_DISPATCH_T(dtype,
+                  hipLaunchKernelGGL(add_norm_row_k<float>, dim3(M), dim3(ROW_THREADS), 0, st, part, S,
+                                     (const float*)g, eps, x, (float*)xn, M, d),
+                  hipLaunchKernelGGL(add_norm_row_k<bf16_t>, dim3(M), dim3(ROW_THREADS), 0, st, part, S,
+                                     (const bf16_t*)g, eps, x, (bf16_t*)xn, M, d));
+    return hipGetLastError();
+  }
   hipLaunchKernelGGL(add_partials_k, grid, dim3(EW_THREADS), 0, st, part, S, x, ssq, M, d);
   SD_DISPATCH_T(dtype,
                 hipLaunchKernelGGL(norm_k<float>, grid, dim3(EW_THREADS), 0, st, x, ssq, (const float*)g, eps,
