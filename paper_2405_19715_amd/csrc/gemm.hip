@@ -7,18 +7,18 @@
 // is laid over workgroups, wavefronts and time.
 //
 // bf16 layout of the work
-//   grid       = G row groups x S K-slices.  A workgroup (4 wavefronts) belongs to one
+//   grid       = G row groups x S K-slices.  A workgroup (8 wavefronts) belongs to one
 //                K-slice for its whole life: it stages that slice of X into LDS once
 //                (already in the order the multiply needs) and never synchronises again.
-//   wavefront  = walks its own list of 16-row weight tiles (tile = slot, slot + 4G, ...)
-//                with ONE continuous software pipeline of 16-byte loads that runs across
+//   wavefront  = walks its own list of 16-row weight tiles (tile = slot, slot + NW, ...)
+//                (NW = 8 G) with ONE continuous software pipeline of 16-byte loads that runs across
 //                tile boundaries; lane (r = lane % 16, g = lane / 16) loads, per 128-k
 //                step, 4 x 16 B of row r (instruction j covers the 64 contiguous bytes
 //                k0 + 32 j .. of every row, lane group g the 16 B at + 8 g).
 //   rotation   = each wavefront starts its slice at a different k-step (and wraps), so
 //                that the thousands of concurrent row streams, whose row stride is a
 //                large power of two, do not all hit the same HBM channels at once.
-//   few, long-lived workgroups (about two per CU) measured faster than many short ones:
+//   few, long-lived workgroups (about one per CU) measured faster than many short ones:
 //                fewer concurrent DRAM streams and no repeated X staging.
 //   M >= 5     : v_mfma_f32_16x16x32_bf16, weights as the A operand (16 rows x 32 k),
 //                X^T as the B operand (32 k x 16 activation rows), one MFMA per 16-row
@@ -37,11 +37,12 @@ namespace sd {
 
 namespace {
 
-constexpr int GEMM_THREADS = 256;
+constexpr int GEMM_WAVES = 8;            // wavefronts per workgroup, all sharing one staged X slice
+constexpr int GEMM_THREADS = 64 * GEMM_WAVES;
 constexpr int KSTEP = 128;
 constexpr int LDS_MAX = 72 * 1024;       // X slice per workgroup: two workgroups fit a CU's 160 KB
 constexpr int PREFETCH = 4;              // steps of weight loads in flight per wave
-constexpr int TARGET_WGS = 512;          // about two resident workgroups per CU
+constexpr int TARGET_WGS = 256;          // one long-lived workgroup per CU
 
 struct Split { int S, steps_per, G; };
 
@@ -54,7 +55,7 @@ Split plan_bf16(int M, int N, int K) {
   int max_steps = LDS_MAX / (M * KSTEP * 2);
   if (max_steps < 1) max_steps = 1;
   if (max_steps > total) max_steps = total;
-  const int g_max = (ntiles + 3) / 4;
+  const int g_max = (ntiles + GEMM_WAVES - 1) / GEMM_WAVES;
   Split best{1, total, 1};
   double best_score = -1.0;
   for (int sp = max_steps; sp >= 1; --sp) {
@@ -66,8 +67,8 @@ Split plan_bf16(int M, int N, int K) {
     if (g_lo > g_max) g_lo = g_max;
     if (g_hi > g_max) g_hi = g_max;
     for (int G = g_lo; G <= g_hi; ++G) {
-      const int per = (ntiles + 4 * G - 1) / (4 * G);
-      const double eff_rows = (double)ntiles / ((double)per * 4 * G);
+      const int per = (ntiles + GEMM_WAVES * G - 1) / (GEMM_WAVES * G);
+      const double eff_rows = (double)ntiles / ((double)per * GEMM_WAVES * G);
       double fill = (double)(G * S) / TARGET_WGS;
       if (fill > 1.0) fill = 1.0 / fill;                       // too many workgroups costs as well
       const double work = (double)per * sp;                    // steps per wavefront
@@ -159,7 +160,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_stream(const bf16_t* _
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int r = lane & 15, g = lane >> 4;
   const int ntiles = N >> 4;
-  const int wslot = grp * 4 + wave, nslots = G * 4;
+  const int wslot = grp * GEMM_WAVES + wave, nslots = G * GEMM_WAVES;
   const int my_tiles = wslot < ntiles ? (ntiles - wslot + nslots - 1) / nslots : 0;
 
   WaveWalk ww;
