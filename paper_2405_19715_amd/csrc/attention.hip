@@ -46,30 +46,17 @@ template <int HD, int QTW>
 __global__ __launch_bounds__(256) void attn_mfma_k(const bf16_t* __restrict__ qbuf, const bf16_t* __restrict__ kcache,
                                                    const bf16_t* __restrict__ vcache,
                                                    const int32_t* __restrict__ row_seq,
-                                                   const int32_t* __restrict__ row_pos, float* __restrict__ scratch,
+                                                   const int32_t* __restrict__ row_pos,
+                                                   const int32_t* __restrict__ grp_seq,
+                                                   const int32_t* __restrict__ grp_end, float* __restrict__ scratch,
                                                    int RS, int Hq, int Hkv, int max_seq, int QW, int NQG, int NSP) {
   constexpr int DT = HD / 16;          // 16-wide tiles of the head dimension
   constexpr int KS = HD / 32;          // MFMA k-steps of the score product
   constexpr int STRIDE = HD + 4;       // floats per partial: O[HD], max, sum, pad
-  __shared__ int s_info[2];            // cache sequence id, kv_end of the group
-
   const int kh = blockIdx.x / NQG, qg = blockIdx.x % NQG;
   const int grp = blockIdx.y, c = blockIdx.z;
   const int G = Hq / Hkv;
-  if (threadIdx.x == 0) {
-    int seq = -1, kv_end = 0;
-    for (int rr = 0; rr < RS; ++rr) {
-      const int m = grp * RS + rr;
-      if (row_seq[m] >= 0) {
-        seq = row_seq[m];
-        kv_end = max(kv_end, row_pos[m] + 1);
-      }
-    }
-    s_info[0] = seq;
-    s_info[1] = kv_end;
-  }
-  __syncthreads();
-  const int seq = s_info[0], kv_end = s_info[1];
+  const int seq = grp_seq[grp], kv_end = grp_end[grp];
   if (seq < 0) return;
 
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -123,6 +110,14 @@ __global__ __launch_bounds__(256) void attn_mfma_k(const bf16_t* __restrict__ qb
   }
 
   for (int key0 = kbeg; key0 < kend; key0 += KB) {
+    // value rows are requested first: they are not needed before the softmax is done
+    uint4 vf[DT][2];
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt) {
+      const bf16_t* vp = vbase + (size_t)(dt * 16 + li) * max_seq + key0 + 16 * g;
+      vf[dt][0] = ld16(vp);
+      vf[dt][1] = ld16(vp + 8);
+    }
     // ---- scores: 4 key tiles x QTW query tiles
     floatx4 sacc[QTW][4];
 #pragma unroll
@@ -186,8 +181,7 @@ __global__ __launch_bounds__(256) void attn_mfma_k(const bf16_t* __restrict__ qb
     // ---- O^T += V^T P^T
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt) {
-      const bf16_t* vp = vbase + (size_t)(dt * 16 + li) * max_seq + key0 + 16 * g;
-      const uint4 v0 = ld16(vp), v1 = ld16(vp + 8);
+      const uint4 v0 = vf[dt][0], v1 = vf[dt][1];
 #pragma unroll
       for (int q = 0; q < QTW; ++q) {
         o[q][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(v0), as_bf16x8(pf[q][0]), o[q][dt], 0, 0, 0);
@@ -212,7 +206,7 @@ __global__ __launch_bounds__(256) void attn_mfma_k(const bf16_t* __restrict__ qb
 
 template <int HD>
 __global__ __launch_bounds__(HD) void attn_merge_k(const float* __restrict__ scratch, const int32_t* __restrict__ row_seq,
-                                                   const int32_t* __restrict__ row_pos, bf16_t* __restrict__ out, int RS,
+                                                   const int32_t* __restrict__ grp_end, bf16_t* __restrict__ out, int RS,
                                                    int Hq, int NSP) {
   constexpr int STRIDE = HD + 4;
   constexpr int MAXP = 512;            // key blocks whose weights fit the LDS table (32768 keys)
@@ -224,12 +218,7 @@ __global__ __launch_bounds__(HD) void attn_merge_k(const float* __restrict__ scr
     *dst = 0;
     return;
   }
-  const int grp = m / RS;
-  int kv_end = 0;
-  for (int rr = 0; rr < RS; ++rr) {
-    const int mm = grp * RS + rr;
-    if (row_seq[mm] >= 0) kv_end = max(kv_end, row_pos[mm] + 1);
-  }
+  const int kv_end = grp_end[m / RS];
   const float* src = scratch + ((size_t)m * Hq + h) * NSP * STRIDE;
   const int nsp = min(min(NSP, MAXP), (kv_end + KB - 1) / KB);
   // the partials' maxima and sums go through LDS once; every thread then owns one column
@@ -339,7 +328,7 @@ hipError_t launch_attention(hipStream_t st, int dtype, const void* qbuf, const v
                             const RowPlan& rows, void* out, float* scratch, int M, int RS, int Hq, int Hkv, int hd,
                             int max_seq, int max_kv_len) {
   if (M < 1 || M > MAX_ROWS || RS < 1 || M % RS != 0 || Hq < 1 || Hkv < 1 || Hq % Hkv != 0 || max_kv_len < 1 ||
-      max_kv_len > max_seq || !qbuf || !kcache || !vcache || !out || !rows.seq || !rows.pos)
+      max_kv_len > max_seq || !qbuf || !kcache || !vcache || !out || !rows.seq || !rows.pos || !rows.gseq || !rows.gend)
     return hipErrorInvalidValue;
   const int ngroups = M / RS;
   if (use_plain(dtype)) {
@@ -365,7 +354,8 @@ hipError_t launch_attention(hipStream_t st, int dtype, const void* qbuf, const v
   const dim3 grid(Hkv * sh.NQG, ngroups, nsplit);
   const bf16_t *q = (const bf16_t*)qbuf, *k = (const bf16_t*)kcache, *v = (const bf16_t*)vcache;
 #define SD_ATTN_LAUNCH(HD_, QTW_)                                                                              \
-  hipLaunchKernelGGL((attn_mfma_k<HD_, QTW_>), grid, dim3(256), 0, st, q, k, v, rows.seq, rows.pos, scratch, RS, \
+  hipLaunchKernelGGL((attn_mfma_k<HD_, QTW_>), grid, dim3(256), 0, st, q, k, v, rows.seq, rows.pos, rows.gseq,   \
+                     rows.gend, scratch, RS,                                                                  \
                      Hq, Hkv, max_seq, sh.QW, sh.NQG, NSP)
   if (hd == 128) {
     if (sh.QTW == 1) SD_ATTN_LAUNCH(128, 1); else SD_ATTN_LAUNCH(128, 2);
@@ -376,10 +366,10 @@ hipError_t launch_attention(hipStream_t st, int dtype, const void* qbuf, const v
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   if (hd == 128)
-    hipLaunchKernelGGL(attn_merge_k<128>, dim3(M, Hq), dim3(128), 0, st, scratch, rows.seq, rows.pos, (bf16_t*)out,
+    hipLaunchKernelGGL(attn_merge_k<128>, dim3(M, Hq), dim3(128), 0, st, scratch, rows.seq, rows.gend, (bf16_t*)out,
                        RS, Hq, NSP);
   else
-    hipLaunchKernelGGL(attn_merge_k<64>, dim3(M, Hq), dim3(64), 0, st, scratch, rows.seq, rows.pos, (bf16_t*)out, RS,
+    hipLaunchKernelGGL(attn_merge_k<64>, dim3(M, Hq), dim3(64), 0, st, scratch, rows.seq, rows.gend, (bf16_t*)out, RS,
                        Hq, NSP);
   return hipGetLastError();
 }

@@ -290,6 +290,10 @@ sd_status plan_host_rows(sd_ctx* c, int seq, int start, const int32_t* toks, int
   SD_HIP(hipMemcpyAsync(c->rows.seq, h, n * sizeof(int32_t), hipMemcpyHostToDevice, c->st));
   SD_HIP(hipMemcpyAsync(c->rows.pos, h + MAX_ROWS, n * sizeof(int32_t), hipMemcpyHostToDevice, c->st));
   SD_HIP(hipMemcpyAsync(c->rows.tok, h + 2 * MAX_ROWS, n * sizeof(int32_t), hipMemcpyHostToDevice, c->st));
+  h[3 * MAX_ROWS] = seq;                 // one row group: the whole chunk
+  h[3 * MAX_ROWS + 1] = start + n;
+  SD_HIP(hipMemcpyAsync(c->rows.gseq, h + 3 * MAX_ROWS, sizeof(int32_t), hipMemcpyHostToDevice, c->st));
+  SD_HIP(hipMemcpyAsync(c->rows.gend, h + 3 * MAX_ROWS + 1, sizeof(int32_t), hipMemcpyHostToDevice, c->st));
   return SD_OK;
 }
 
@@ -417,6 +421,8 @@ sd_status sd_create(sd_ctx** out, const sd_model* target, const sd_model* draft,
   SD_ALLOC(c->rows.seq, MAX_ROWS * 4, true);
   SD_ALLOC(c->rows.pos, MAX_ROWS * 4, true);
   SD_ALLOC(c->rows.tok, MAX_ROWS * 4, true);
+  SD_ALLOC(c->rows.gseq, MAX_ROWS * 4, true);
+  SD_ALLOC(c->rows.gend, MAX_ROWS * 4, true);
   SD_ALLOC(c->s.P, B * 4, true);
   SD_ALLOC(c->s.kv_t, B * 4, true);
   SD_ALLOC(c->s.kv_d, B * 4, true);
@@ -436,7 +442,7 @@ sd_status sd_create(sd_ctx** out, const sd_model* target, const sd_model* draft,
   SD_ALLOC(c->s.active, B * 4, true);
   SD_ALLOC(c->result, (size_t)B * RESULT_INTS * 4, true);
 #undef SD_ALLOC
-  c->pinned_ints = std::max<size_t>(3 * MAX_ROWS, (size_t)B * RESULT_INTS) + 64;
+  c->pinned_ints = std::max<size_t>(3 * MAX_ROWS + 2, (size_t)B * RESULT_INTS) + 64;
   if (hipHostMalloc((void**)&c->pinned, c->pinned_ints * 4, hipHostMallocDefault) != hipSuccess) return fail(SD_ENOMEM);
   for (auto& e : c->ev)
     if (hipEventCreate(&e) != hipSuccess) return fail(SD_EDEVICE);

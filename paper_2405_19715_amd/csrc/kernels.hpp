@@ -25,6 +25,8 @@ struct RowPlan {           // device arrays, one entry per activation row
   int32_t* seq;            // sequence of the row, -1 = padding row
   int32_t* pos;            // absolute position of the row's token
   int32_t* tok;            // token id
+  int32_t* gseq;           // per row group: the sequence its rows belong to, -1 = no live row
+  int32_t* gend;           // per row group: largest pos + 1 over its live rows (keys to attend)
 };
 
 // ---------------------------------------------------------------- elementwise

@@ -113,8 +113,12 @@ __global__ void plan_draft_k(SeqState s, RowPlan rows, int B, int step, int max_
   rows.pos[m0] = rows.pos[m0 + 1] = 0;
   rows.tok[m0] = rows.tok[m0 + 1] = 0;
   s.last_row[b] = m0;
+  rows.gseq[b] = -1;
+  rows.gend[b] = 0;
   if (s.stopped[b]) return;
   const int P = s.P[b];
+  rows.gseq[b] = b;
+  rows.gend[b] = step == 1 ? P : P + step - 1;
   if (step == 1) {
     const int kv = s.kv_d[b];
     const int cnt = min(max(P - kv, 1), 2);
@@ -142,6 +146,10 @@ __global__ void plan_verify_k(SeqState s, RowPlan rows, int B, int k_max, int ma
   if (b >= B || j > k_max) return;
   const int m = b * (k_max + 1) + j;
   const int P = s.P[b], K = s.K[b];
+  if (j == 0) {
+    rows.gseq[b] = s.active[b] ? b : -1;
+    rows.gend[b] = P + K;
+  }
   if (j <= K && s.active[b]) {
     rows.seq[m] = b;
     rows.pos[m] = P - 1 + j;
