@@ -42,13 +42,17 @@ constexpr int GEMM_THREADS = 64 * GEMM_WAVES;
 constexpr int KSTEP = 128;
 constexpr int LDS_MAX = 72 * 1024;       // X slice per workgroup: two workgroups fit a CU's 160 KB
 constexpr int PREFETCH = 4;              // steps of weight loads in flight per wave
-constexpr int TARGET_WGS = 256;          // one long-lived workgroup per CU
 
 struct Split { int S, steps_per, G; };
 
-// Pick the K-slice length and the number of row groups: slices as long as LDS allows
-// (fewer partial sums), about TARGET_WGS workgroups, and row tiles / slices that divide
-// evenly over wavefronts so that no wave is left with a longer list than the others.
+// Pick the K-slice length (steps_per) and the number of row groups G by a small cost
+// model of the stream, fitted to measurements on the MI355X:
+//   - every workgroup must be resident at once (it is a persistent design): at most two
+//     per CU, fewer when the X slice in LDS is large;
+//   - a wavefront with PREFETCH steps in flight sustains about 2.6 GB/s under load, and all
+//     of them together about 5.3 TB/s;
+//   - the slowest wavefront (most tiles x steps) ends the kernel;
+//   - partial sums are written once and read once by the consumer, slice after slice.
 Split plan_bf16(int M, int N, int K) {
   const int total = K / KSTEP;
   const int ntiles = N / 16;
@@ -56,26 +60,32 @@ Split plan_bf16(int M, int N, int K) {
   if (max_steps < 1) max_steps = 1;
   if (max_steps > total) max_steps = total;
   const int g_max = (ntiles + GEMM_WAVES - 1) / GEMM_WAVES;
+  const double bw = 5.3e12, wave_rate = 2.6e9, step_bytes = 16.0 * KSTEP * 2;
   Split best{1, total, 1};
-  double best_score = -1.0;
+  double best_cost = 1e30;
   for (int sp = max_steps; sp >= 1; --sp) {
     const int S = (total + sp - 1) / sp;
-    const double eff_k = (double)total / ((double)S * sp);
-    int g_lo = (TARGET_WGS * 3 / 4) / S, g_hi = (TARGET_WGS * 5 / 4) / S;
-    if (g_lo < 1) g_lo = 1;
-    if (g_hi < g_lo) g_hi = g_lo;
-    if (g_lo > g_max) g_lo = g_max;
+    const size_t lds = (size_t)M * sp * KSTEP * 2;
+    const int resident = lds > 16 * 1024 ? 1 : 2;   // sizeable X slices: one workgroup per CU measured best
+    int g_hi = (256 * resident) / S;
     if (g_hi > g_max) g_hi = g_max;
-    for (int G = g_lo; G <= g_hi; ++G) {
-      const int per = (ntiles + GEMM_WAVES * G - 1) / (GEMM_WAVES * G);
-      const double eff_rows = (double)ntiles / ((double)per * GEMM_WAVES * G);
-      double fill = (double)(G * S) / TARGET_WGS;
-      if (fill > 1.0) fill = 1.0 / fill;                       // too many workgroups costs as well
-      const double work = (double)per * sp;                    // steps per wavefront
-      const double ramp = work / (work + 6.0);                 // pipeline fill / drain per wavefront
-      const double partial = 1.0 / (1.0 + 0.55 * M / (16.0 * sp));   // partial-sum traffic vs weight bytes
-      const double score = eff_k * eff_rows * (0.5 + 0.5 * fill) * ramp * partial;
-      if (score > best_score) { best_score = score; best = {S, sp, G}; }
+    if (g_hi < 1) {
+      if (S > 256 * resident) continue;       // would not be resident all at once
+      g_hi = 1;
+    }
+    for (int G = 1; G <= g_hi; ++G) {
+      const int slots = G * GEMM_WAVES;
+      const int per = (ntiles + slots - 1) / slots;               // tiles of the busiest wavefront
+      const double waves = (double)(ntiles < slots ? ntiles : slots) * S;
+      // more than ~2048 concurrent row streams cost DRAM locality (measured: -8 % per doubling)
+      double bw_eff = bw;
+      for (double w = 2048.0; w < waves; w *= 2.0) bw_eff *= (waves >= 2.0 * w) ? 0.92 : 1.0 - 0.08 * (waves / w - 1.0);
+      const double rate = wave_rate < bw_eff / waves ? wave_rate : bw_eff / waves;
+      const double t_stream = (double)per * sp * step_bytes / rate;
+      const double t_stage = (double)lds / 60.0e9;                // X slice through one CU's L2 port
+      const double t_part = 2.0 * S * M * (double)N * 4.0 / bw;
+      const double cost = 3.0e-6 + t_stage + t_stream + t_part + 0.1e-6 * S;   // consumers walk S slices
+      if (cost < best_cost) { best_cost = cost; best = {S, sp, G}; }
     }
   }
   return best;
