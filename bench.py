@@ -42,6 +42,19 @@ def _algorithmic_bytes_verify(shape, P, K, esz=2):
     return shape.streamed_params() * esz + kv_token * P + kv_token * (K + 1) + (K + 1) * shape.vocab * 4
 
 
+def _measured_traffic():
+    """HBM bytes per launch of the dominant kernel from the committed rocprofv3 --pmc
+    summary (FETCH_SIZE + WRITE_SIZE, scaled by a copy of known size), or None."""
+    path = os.path.join(ROOT, "profiles", "gemm_traffic_paper_workload.txt")
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch:"):
+                return float(line.split(":")[1])
+    except OSError:
+        pass
+    return None
+
+
 def _cpu_baseline(tgt, drf, k_mean, n_mean, P, k_max):
     """The oracle, as it stands, timed on this machine's host cores on a bounded sample of
     the same workload: one target layer over K_max+1 rows and one draft layer over one
@@ -105,6 +118,9 @@ def main():
     ap.add_argument("--h", type=float, default=0.7)
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="first run four 1 GiB device-to-device copies (a kernel of known traffic, to scale "
+                         "rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
     ap.add_argument("--profile-every", type=int, default=8,
                     help="bracket the target GEMMs of every n-th layer with HIP events (0 = off)")
     args = ap.parse_args()
@@ -118,6 +134,13 @@ def main():
     wl = _workload(args.workload)
     dev = "cuda:0"
     torch.cuda.set_device(0)
+    if args.calibrate_copy:
+        a = torch.ones(1 << 30, dtype=torch.uint8, device=dev)
+        b = torch.empty_like(a)
+        for _ in range(4):
+            b.copy_(a)
+        torch.cuda.synchronize()
+        del a, b
     t_build = time.perf_counter()
     tgt = synth.make_model(wl["target"], args.seed, device=dev, dtype=torch.bfloat16)
     drf = synth.make_model(wl["draft"], args.seed + 1, device=dev, dtype=torch.bfloat16)
@@ -169,7 +192,9 @@ def main():
     verify_bytes = _algorithmic_bytes_verify(wl["target"], P_mid, wl["k_max"])
     roofline = dict(bound="hbm", kernel="gemm_bf16_mfma<2> (target pass, M = K_max+1 = 17 rows)",
                     achieved=achieved, peak=HBM_PEAK_GBS, unit="GB/s",
-                    frac=(achieved / HBM_PEAK_GBS) if achieved else None, traffic=None,
+                    frac=(achieved / HBM_PEAK_GBS) if achieved else None,
+                    traffic=_measured_traffic() if args.workload == "paper" else None,
+                    algorithmic_bytes_per_launch=(tot_b / tot_n) if tot_n else None,
                     sampled_launches=tot_n, avg_launch_us=est_avg_us,
                     per_matrix_GBs={k: (v["weight_bytes"] / v["seconds"] / 1e9 if v["seconds"] > 0 else None)
                                     for k, v in prof.items()},

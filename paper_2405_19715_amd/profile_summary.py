@@ -48,11 +48,49 @@ def table(segments, title, out):
         out.write(f"  {name:48s} calls {n:6d}  avg {t / n / 1e3:9.2f} us  total {t / 1e6:9.3f} ms  {100.0 * t / span:5.1f}%\n")
 
 
+def pmc_summary(path, skip_rounds, out):
+    """Per-launch HBM traffic of the target pass's GEMM kernel from a
+    `rocprofv3 --pmc FETCH_SIZE|WRITE_SIZE --output-format csv` run of
+    `bench.py --calibrate-copy`: the counter (KiB) is scaled by what it reads for the
+    1 GiB device-to-device copies bench.py issues first."""
+    rows = []
+    with open(path, newline="") as f:
+        for r in csv.DictReader(f):
+            rows.append((int(r["Dispatch_Id"]), short_name(r["Kernel_Name"]), r["Counter_Name"], float(r["Counter_Value"])))
+    rows.sort()
+    counter = rows[0][2]
+    copies = sorted(v for _, n, _, v in rows if "copyBuffer" in n)[-4:]
+    scale = (1 << 20) / (sum(copies) / len(copies))          # KiB moved per counter unit
+    out.write(f"counter {counter}: the 1 GiB copies read {sum(copies) / len(copies):.1f} per launch -> "
+              f"{scale:.4f} KiB per counter unit\n")
+    starts = [i for i, r in enumerate(rows) if "begin_round_k" in r[1]][skip_rounds:]
+    per_grid = collections.OrderedDict()
+    n_pass = 0
+    for a, b in zip(starts, starts[1:] + [len(rows)]):
+        rnd = rows[a:b]
+        cut = next((i for i, r in enumerate(rnd) if "plan_verify_k" in r[1]), None)
+        if cut is None:
+            continue
+        n_pass += 1
+        for _, n, _, v in rnd[cut:]:
+            if "gemm_bf16_stream<2>" in n:
+                a2 = per_grid.setdefault("gemm_bf16_stream<2>", [0, 0.0])
+                a2[0] += 1
+                a2[1] += v
+    for k, (n, tot) in per_grid.items():
+        out.write(f"{k}: {n} launches in {n_pass} target passes, {counter} per launch "
+                  f"{tot / n * scale * 1024 / 1e6:.2f} MB (scaled), per pass {tot / n_pass * scale * 1024 / 1e9:.3f} GB\n")
+
+
 def main(argv=None):
     ap = argparse.ArgumentParser()
     ap.add_argument("trace")
     ap.add_argument("--skip-rounds", type=int, default=2)
+    ap.add_argument("--pmc", action="store_true", help="the file is a counter_collection.csv of a --pmc run")
     args = ap.parse_args(argv)
+    if args.pmc:
+        pmc_summary(args.trace, args.skip_rounds, sys.stdout)
+        return
     rows = load(args.trace)
     starts = [i for i, r in enumerate(rows) if "begin_round_k" in r[0]]
     if len(starts) <= args.skip_rounds:
