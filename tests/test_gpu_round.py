@@ -257,3 +257,57 @@ def test_batch_of_sequences_matches_single_sequence_runs():
         assert seqs == want
     finally:
         ctx.close()
+
+
+def test_ragged_batch_of_eight_bf16_decision_replay():
+    """Eight sequences with different prompt lengths decoded together on a bf16 pair
+    (136 activation rows in the target pass, ragged K per sequence, per-sequence
+    rollback): every sequence's K, n and y' replayed by the oracle on the HIP path's own
+    rows, and the sequence state stays consistent."""
+    from paper_2405_19715_amd import binding as B
+    from oracle import philox
+    t, d, h = _bf16_pair()
+    Bn, k_max, hh, seed = 8, 16, 0.8, 9
+    g0 = torch.Generator().manual_seed(123)
+    lens = torch.randint(20, 90, (Bn,), generator=g0).tolist()
+    prompts = [synth.make_prompt(lens[b], 2048, 50 + b) for b in range(Bn)]
+    ctx = _context(t, d, h, k_max=k_max, max_seq=256, batch=Bn)
+    try:
+        for b in range(Bn):
+            ctx.sd_prefill(b, prompts[b])
+        P = list(lens)
+        exempt = 0
+        seen_K = set()
+        for rho in range(4):
+            res = ctx.specdec_round(B.make_params(h=hh, seed=seed))
+            for b in range(Bn):
+                g = res[b]
+                K = g["K"]
+                seen_K.add(K)
+                q, p, s = ctx.sd_last_round_rows(b, K)
+                q, p, s = q.numpy(), p.numpy(), s.numpy()
+                want_K = OH.candidate_length(list(s.astype(np.float64)) + [1.0] * 40, hh, k_max)
+                if want_K != K:
+                    ph = np.cumprod(np.concatenate([[1.0], s.astype(np.float64)]))
+                    assert np.min(np.abs(1 - ph - hh)) < 1e-5
+                    exempt += 1
+                for i in range(1, K + 1):
+                    qi = sampling.softmax(q[i - 1])
+                    u = philox.uniform(seed, i, rho, b, philox.STREAM_DRAFT)
+                    y = sampling.sample_inverse_cdf(qi, u)
+                    assert y == g["cand"][i - 1] or sampling.cdf_margin(qi, u, y) < 1e-5, (rho, b, i)
+                o = sampling.accept_resample(p, q, g["cand"], K, seed=seed, rnd=rho, seq=b)
+                if o["n"] != g["n"]:
+                    i = min(o["n"], g["n"]) + 1
+                    assert abs(o["r"][i - 1] - o["ratio"][i - 1]) < 1e-3
+                    o = sampling.accept_resample(p, q, g["cand"], K, seed=seed, rnd=rho, seq=b,
+                                                 forced={("accept", i): 1 if g["n"] >= i else 0})
+                    exempt += 1
+                assert o["n"] == g["n"]
+                assert o["token"] == g["tokens"][-1] or o["margin"] < 1e-5
+                P[b] += g["n"] + 1
+                st = ctx.sd_seq_state(b)
+                assert st["P"] == P[b] and st["kv_len_target"] == P[b] - 1
+        assert exempt <= 3 and len(seen_K) > 1
+    finally:
+        ctx.close()
