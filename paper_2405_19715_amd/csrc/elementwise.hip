@@ -197,15 +197,16 @@ __global__ __launch_bounds__(EW_THREADS) void silu_mul_k(const float* __restrict
   Elem<T>::st(act + (size_t)m * ffn + f, g / (1.0f + expf(-g)) * u);
 }
 
+// Row m = (group m / RS, slot m % RS) goes to out[group * ld_group + slot * ld_row + n].
 __global__ __launch_bounds__(EW_THREADS) void reduce_rows_k(const float* __restrict__ part, int S,
-                                                            float* __restrict__ out, int64_t ldo, int M,
-                                                            int N) {
+                                                            float* __restrict__ out, int RS, int64_t ld_group,
+                                                            int64_t ld_row, int M, int N) {
   const int m = blockIdx.y;
   const int n = blockIdx.x * EW_THREADS + threadIdx.x;
   if (n >= N) return;
   float v = 0.f;
   for (int s = 0; s < S; ++s) v += part[((size_t)s * M + m) * N + n];
-  out[(size_t)m * ldo + n] = v;
+  out[(size_t)(m / RS) * ld_group + (size_t)(m % RS) * ld_row + n] = v;
 }
 
 template <typename T>
@@ -295,10 +296,12 @@ hipError_t launch_silu_mul(hipStream_t st, int dtype, const float* part, int S, 
   return hipGetLastError();
 }
 
-hipError_t launch_reduce_rows(hipStream_t st, const float* part, int S, float* out, int64_t ldo, int M, int N) {
-  if (bad_rows(M) || S < 1 || N < 1 || ldo < N || !part || !out) return hipErrorInvalidValue;
+hipError_t launch_reduce_rows(hipStream_t st, const float* part, int S, float* out, int RS, int64_t ld_group,
+                              int64_t ld_row, int M, int N) {
+  if (bad_rows(M) || S < 1 || N < 1 || RS < 1 || M % RS != 0 || ld_row < N || !part || !out)
+    return hipErrorInvalidValue;
   const dim3 grid((N + EW_THREADS - 1) / EW_THREADS, M);
-  hipLaunchKernelGGL(reduce_rows_k, grid, dim3(EW_THREADS), 0, st, part, S, out, ldo, M, N);
+  hipLaunchKernelGGL(reduce_rows_k, grid, dim3(EW_THREADS), 0, st, part, S, out, RS, ld_group, ld_row, M, N);
   return hipGetLastError();
 }
 

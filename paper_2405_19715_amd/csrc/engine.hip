@@ -222,9 +222,10 @@ sd_status gemm(sd_ctx* c, const ModelRt& rt, const void* W, const void* X, int l
 
 // The decoder over the rows of c->rows (M rows in groups of RS).  Leaves the
 // final-RMSNorm rows in c->xn.  If logits_out != null, runs the LM head over n_lm rows
-// (gathered through lm_rows when non-null) into logits_out[row * ldo + v].
+// (gathered through lm_rows when non-null); LM row i = (group i / lm_rs, slot i % lm_rs) goes
+// to logits_out[group * ld_group + slot * ld_row + v].
 sd_status forward(sd_ctx* c, ModelRt& rt, int M, int RS, int max_kv_len, const int* lm_rows, int n_lm,
-                  float* logits_out, int64_t ldo, bool profile) {
+                  float* logits_out, int lm_rs, int64_t ld_group, int64_t ld_row, bool profile) {
   const sd_model& m = rt.m;
   const int dt = m.dtype, d = m.d_model, nq = rt.n_q(), nkv = rt.n_kv();
   hipStream_t st = c->st;
@@ -252,7 +253,8 @@ sd_status forward(sd_ctx* c, ModelRt& rt, int M, int RS, int max_kv_len, const i
     if ((s = gemm(c, rt, m.lm_head, c->xn, d, lm_rows, n_lm, m.vocab, d, profile && c->prof_every > 0 ? 4 : -1)) !=
         SD_OK)
       return s;
-    SD_HIP(launch_reduce_rows(st, c->part, gemm_splits(dt, n_lm, m.vocab, d), logits_out, ldo, n_lm, m.vocab));
+    SD_HIP(launch_reduce_rows(st, c->part, gemm_splits(dt, n_lm, m.vocab, d), logits_out, lm_rs, ld_group, ld_row, n_lm,
+                              m.vocab));
   }
   return SD_OK;
 }
@@ -468,7 +470,7 @@ sd_status sd_prefill(sd_ctx* c, int32_t seq, const int32_t* prompt, int32_t n) {
     for (int start = 0; start < n - 1; start += PREFILL_CHUNK) {
       const int m = std::min(PREFILL_CHUNK, n - 1 - start);
       if ((s = plan_host_rows(c, seq, start, prompt + start, m)) != SD_OK) return s;
-      if ((s = forward(c, *rt, m, m, start + m, nullptr, 0, nullptr, 0, false)) != SD_OK) return s;
+      if ((s = forward(c, *rt, m, m, start + m, nullptr, 0, nullptr, 1, 0, 0, false)) != SD_OK) return s;
       SD_HIP(hipStreamSynchronize(c->st));
     }
   }
@@ -503,11 +505,12 @@ static sd_status round_impl(sd_ctx* c, const sd_params* params, sd_round_out* ou
   SD_HIP(launch_begin_round(st, c->s, B, k_max, max_seq));
   SD_HIP(hipEventRecord(c->ev[0], st));
   // ---- adaptive draft loop (Algorithm 2's first block)
+  int k_round = k_max;                      // largest K of the round = draft steps taken
   for (int step = 1; step <= k_max; ++step) {
     SD_HIP(launch_plan_draft(st, c->s, c->rows, B, step, max_seq));
     const int kv_bound = std::min(max_seq, maxP + step);
-    if ((s = forward(c, c->draft, 2 * B, 2, kv_bound, c->s.last_row, B,
-                     c->q_logits + (size_t)(step - 1) * V, (int64_t)k_max * V, false)) != SD_OK)
+    if ((s = forward(c, c->draft, 2 * B, 2, kv_bound, c->s.last_row, B, c->q_logits + (size_t)(step - 1) * V, 1,
+                     (int64_t)k_max * V, V, false)) != SD_OK)
       return s;
     const void* z = nullptr;
     const int* z_rows = nullptr;
@@ -523,15 +526,18 @@ static sd_status round_impl(sd_ctx* c, const sd_params* params, sd_round_out* ou
       SD_HIP(hipStreamSynchronize(st));
       bool all = true;
       for (int b = 0; b < B; ++b) all = all && c->pinned[b] != 0;
-      if (all) break;
+      if (all) {
+        k_round = step;
+        break;
+      }
     }
   }
   SD_HIP(hipEventRecord(c->ev[1], st));
-  // ---- target pass over the K+1 positions
-  SD_HIP(launch_plan_verify(st, c->s, c->rows, B, k_max, max_seq));
-  const int Mv = B * (k_max + 1);
-  if ((s = forward(c, c->target, Mv, k_max + 1, std::min(max_seq, maxP + k_max), nullptr, Mv, c->p_logits, V,
-                   true)) != SD_OK)
+  // ---- target pass over the K+1 positions (row slots sized by this round's largest K)
+  const int rs = k_round + 1, Mv = B * rs;
+  SD_HIP(launch_plan_verify(st, c->s, c->rows, B, rs, max_seq));
+  if ((s = forward(c, c->target, Mv, rs, std::min(max_seq, maxP + k_round), nullptr, Mv, c->p_logits, rs,
+                   (int64_t)(k_max + 1) * V, V, true)) != SD_OK)
     return s;
   SD_HIP(hipEventRecord(c->ev[2], st));
   // ---- accept / residual resample, commit, rollback
@@ -675,7 +681,7 @@ sd_status sd_forward(sd_ctx* c, int32_t which, int32_t seq, int32_t start, const
   SD_HIP(hipStreamSynchronize(c->st));
   if ((s = plan_host_rows(c, seq, start, tokens, n)) != SD_OK) return s;
   const int V = rt.m.vocab, d = rt.m.d_model;
-  if ((s = forward(c, rt, n, n, start + n, nullptr, n, logits_host ? c->fw_logits : nullptr, V, false)) != SD_OK)
+  if ((s = forward(c, rt, n, n, start + n, nullptr, n, logits_host ? c->fw_logits : nullptr, n, 0, V, false)) != SD_OK)
     return s;
   SD_HIP(hipStreamSynchronize(c->st));
   if (logits_host) SD_HIP(hipMemcpy(logits_host, c->fw_logits, (size_t)n * V * 4, hipMemcpyDeviceToHost));
@@ -747,7 +753,7 @@ sd_status sd_gemm_skinny(int32_t dtype, const void* W, const void* X, int32_t M,
   if (!W || !X || !Y || !ws || (dtype != SD_F32 && dtype != SD_BF16)) return SD_EINVAL;
   hipStream_t st = (hipStream_t)hip_stream;
   SD_HIP(launch_gemm(st, dtype, W, X, K, nullptr, (float*)ws, M, N, K));
-  SD_HIP(launch_reduce_rows(st, (const float*)ws, gemm_splits(dtype, M, N, K), Y, N, M, N));
+  SD_HIP(launch_reduce_rows(st, (const float*)ws, gemm_splits(dtype, M, N, K), Y, M, 0, N, M, N));
   return SD_OK;
 }
 

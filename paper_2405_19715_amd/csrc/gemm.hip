@@ -66,7 +66,7 @@ Split plan_bf16(int M, int N, int K) {
   for (int sp = max_steps; sp >= 1; --sp) {
     const int S = (total + sp - 1) / sp;
     const size_t lds = (size_t)M * sp * KSTEP * 2;
-    const int resident = lds > 16 * 1024 ? 1 : 2;   // sizeable X slices: one workgroup per CU measured best
+    const int resident = M >= 5 ? 1 : 2;   // MFMA path: one workgroup per CU measured best
     int g_hi = (256 * resident) / S;
     if (g_hi > g_max) g_hi = g_max;
     if (g_hi < 1) {

@@ -45,8 +45,9 @@ hipError_t launch_rope_kv(hipStream_t st, int dtype, const float* part, int S, c
                           int Hkv, int hd, int max_seq);
 // act[m,f] = silu(sum_s part[s,m,f]) * (sum_s part[s,m,ffn+f])
 hipError_t launch_silu_mul(hipStream_t st, int dtype, const float* part, int S, void* act, int M, int ffn);
-// out[m*ldo + n] = sum_s part[s,m,n]     (fp32 logits rows)
-hipError_t launch_reduce_rows(hipStream_t st, const float* part, int S, float* out, int64_t ldo, int M, int N);
+// out[(m / RS) * ld_group + (m % RS) * ld_row + n] = sum_s part[s,m,n]     (fp32 logits rows)
+hipError_t launch_reduce_rows(hipStream_t st, const float* part, int S, float* out, int RS, int64_t ld_group,
+                              int64_t ld_row, int M, int N);
 // z_out[m,:] = silu(sum_s part + b) (+ z_in when residual)       (acceptance head hidden layer)
 hipError_t launch_head_act(hipStream_t st, int dtype, const float* part, int S, const void* bias,
                            const void* z_in, const int* z_in_rows, void* z_out, int residual, int M, int n);
@@ -87,7 +88,8 @@ struct DecodeParams { float h, temperature; int greedy, eos_id; uint64_t seed; }
 hipError_t launch_begin_round(hipStream_t st, const SeqState& s, int B, int k_max, int max_seq);
 hipError_t launch_plan_draft(hipStream_t st, const SeqState& s, const RowPlan& rows, int B, int step,
                              int max_seq);
-hipError_t launch_plan_verify(hipStream_t st, const SeqState& s, const RowPlan& rows, int B, int k_max,
+// rs = row slots per sequence (>= largest K of the round + 1)
+hipError_t launch_plan_verify(hipStream_t st, const SeqState& s, const RowPlan& rows, int B, int rs,
                               int max_seq);
 // draw y_i from the draft logits row, update p_hat with the head's logit, apply the stop rule
 hipError_t launch_sample_stop(hipStream_t st, int dtype, const SeqState& s, const float* q_logits,

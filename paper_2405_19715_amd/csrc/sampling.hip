@@ -139,12 +139,12 @@ __global__ void plan_draft_k(SeqState s, RowPlan rows, int B, int step, int max_
   }
 }
 
-// Target pass: k_max + 1 row slots per sequence holding x_last, y_1 .. y_K.
-__global__ void plan_verify_k(SeqState s, RowPlan rows, int B, int k_max, int max_seq) {
+// Target pass: rs row slots per sequence (rs > every K of the round) holding x_last, y_1 .. y_K.
+__global__ void plan_verify_k(SeqState s, RowPlan rows, int B, int rs, int max_seq) {
   const int b = blockIdx.x;
   const int j = threadIdx.x;
-  if (b >= B || j > k_max) return;
-  const int m = b * (k_max + 1) + j;
+  if (b >= B || j >= rs) return;
+  const int m = b * rs + j;
   const int P = s.P[b], K = s.K[b];
   if (j == 0) {
     rows.gseq[b] = s.active[b] ? b : -1;
@@ -378,9 +378,9 @@ hipError_t launch_plan_draft(hipStream_t st, const SeqState& s, const RowPlan& r
   return hipGetLastError();
 }
 
-hipError_t launch_plan_verify(hipStream_t st, const SeqState& s, const RowPlan& rows, int B, int k_max, int max_seq) {
-  if (B < 1 || k_max < 1 || k_max > CAND_LD || B * (k_max + 1) > MAX_ROWS) return hipErrorInvalidValue;
-  hipLaunchKernelGGL(plan_verify_k, dim3(B), dim3(64), 0, st, s, rows, B, k_max, max_seq);
+hipError_t launch_plan_verify(hipStream_t st, const SeqState& s, const RowPlan& rows, int B, int rs, int max_seq) {
+  if (B < 1 || rs < 2 || rs > CAND_LD + 1 || B * rs > MAX_ROWS) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(plan_verify_k, dim3(B), dim3(64), 0, st, s, rows, B, rs, max_seq);
   return hipGetLastError();
 }
 
