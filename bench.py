@@ -190,7 +190,7 @@ def main():
         est_avg_us = sum(counts[k] * prof[k]["seconds"] / prof[k]["launches"] for k in counts) / sum(counts.values()) * 1e6
     achieved = tot_b / tot_s / 1e9 if tot_s > 0 else None
     verify_bytes = _algorithmic_bytes_verify(wl["target"], P_mid, wl["k_max"])
-    roofline = dict(bound="hbm", kernel="gemm_bf16_mfma<2> (target pass, M = K_max+1 = 17 rows)",
+    roofline = dict(bound="hbm", kernel="gemm_bf16_stream<MODE> (target pass, M = K+1 rows: MFMA instance <1> for 5..16 rows, <2> for 17, dot-product instances below 5)",
                     achieved=achieved, peak=HBM_PEAK_GBS, unit="GB/s",
                     frac=(achieved / HBM_PEAK_GBS) if achieved else None,
                     traffic=_measured_traffic() if args.workload == "paper" else None,

@@ -156,6 +156,7 @@ __global__ __launch_bounds__(64) void rope_kv_k(const float* __restrict__ part, 
   if (slot < Hq + Hkv) {
     for (int i = threadIdx.x; i < half; i += 64) {
       float a = 0.f, b = 0.f;
+#pragma unroll 4
       for (int s = 0; s < S; ++s) {
         a += p0[s * sstride + i];
         b += p0[s * sstride + i + half];
@@ -176,6 +177,7 @@ __global__ __launch_bounds__(64) void rope_kv_k(const float* __restrict__ part, 
     T* v = vcache + ((size_t)seq * Hkv + (slot - Hq - Hkv)) * hd * (size_t)max_seq + pos;
     for (int i = threadIdx.x; i < hd; i += 64) {
       float a = 0.f;
+#pragma unroll 4
       for (int s = 0; s < S; ++s) a += p0[s * sstride + i];
       Elem<T>::st(v + (size_t)i * max_seq, a);            // value cache is stored transposed: [hd, max_seq]
     }
@@ -189,6 +191,7 @@ __global__ __launch_bounds__(EW_THREADS) void silu_mul_k(const float* __restrict
   const int f = blockIdx.x * EW_THREADS + threadIdx.x;
   if (f >= ffn) return;
   float g = 0.f, u = 0.f;
+#pragma unroll 4
   for (int s = 0; s < S; ++s) {
     const float* p = part + ((size_t)s * M + m) * (2 * (size_t)ffn);
     g += p[f];
@@ -205,6 +208,7 @@ __global__ __launch_bounds__(EW_THREADS) void reduce_rows_k(const float* __restr
   const int n = blockIdx.x * EW_THREADS + threadIdx.x;
   if (n >= N) return;
   float v = 0.f;
+#pragma unroll 4
   for (int s = 0; s < S; ++s) v += part[((size_t)s * M + m) * N + n];
   out[(size_t)(m / RS) * ld_group + (size_t)(m % RS) * ld_row + n] = v;
 }

@@ -84,7 +84,7 @@ Split plan_bf16(int M, int N, int K) {
       const double t_stream = (double)per * sp * step_bytes / rate;
       const double t_stage = (double)lds / 60.0e9;                // X slice through one CU's L2 port
       const double t_part = 2.0 * S * M * (double)N * 4.0 / bw;
-      const double cost = 3.0e-6 + t_stage + t_stream + t_part + 0.1e-6 * S;   // consumers walk S slices
+      const double cost = 3.0e-6 + t_stage + t_stream + t_part + 0.25e-6 * S;   // consumers walk S slices
       if (cost < best_cost) { best_cost = cost; best = {S, sp, G}; }
     }
   }

@@ -73,8 +73,8 @@ def pmc_summary(path, skip_rounds, out):
             continue
         n_pass += 1
         for _, n, _, v in rnd[cut:]:
-            if "gemm_bf16_stream<2>" in n:
-                a2 = per_grid.setdefault("gemm_bf16_stream<2>", [0, 0.0])
+            if "gemm_bf16_stream<" in n:
+                a2 = per_grid.setdefault("gemm_bf16_stream<*> (target pass)", [0, 0.0])
                 a2[0] += 1
                 a2[1] += v
     for k, (n, tot) in per_grid.items():
