@@ -311,3 +311,63 @@ def test_ragged_batch_of_eight_bf16_decision_replay():
         assert exempt <= 3 and len(seen_K) > 1
     finally:
         ctx.close()
+
+
+@pytest.mark.parametrize("n_prompt", [1, 2, 3])
+def test_very_short_prompts(n_prompt):
+    """P = 1 means nothing to prefill (the first round ingests the only token); P = 2, 3
+    exercise the first catch-up steps.  Greedy output must equal target-only greedy."""
+    from paper_2405_19715_amd import binding as B
+    t, d, h = tiny_pair(seed=11)
+    prompt = synth.make_prompt(n_prompt, 1024, 40 + n_prompt)
+    want = R.target_greedy_generate(oracle_model(t), prompt, 20)
+    ctx = _context(t, d, h, k_max=4, max_seq=64)
+    try:
+        ctx.sd_prefill(0, prompt)
+        seqs, st = ctx.specdec_generate(B.make_params(h=0.9, greedy=True), 20)
+        assert seqs[0] == want
+    finally:
+        ctx.close()
+
+
+def test_non_finite_logits_are_reported_and_cleared_by_prefill():
+    from paper_2405_19715_amd import binding as B
+    t, d, h = tiny_pair(seed=12)
+    bad = dict(t)
+    bad["lm_head"] = t["lm_head"].clone()
+    bad["lm_head"][7, :] = float("inf")
+    d2 = dict(d)
+    d2["lm_head"] = bad["lm_head"]
+    d2["tok_emb"] = bad["tok_emb"]
+    d2["final_norm"] = bad["final_norm"]
+    prompt = synth.make_prompt(8, 1024, 3)
+    ctx = _context(bad, d2, h, k_max=4, max_seq=64)
+    try:
+        ctx.sd_prefill(0, prompt)
+        with pytest.raises(B.SpecDecError) as e:
+            ctx.specdec_round(B.make_params(h=0.7, seed=0))
+        assert e.value.status == B.SD_ENONFINITE
+        ctx.sd_prefill(0, prompt)              # clears the sticky flag; the weights are still bad
+        with pytest.raises(B.SpecDecError) as e:
+            ctx.specdec_round(B.make_params(h=0.7, seed=0))
+        assert e.value.status == B.SD_ENONFINITE
+    finally:
+        ctx.close()
+
+
+def test_eos_stops_generation_like_the_oracle():
+    from paper_2405_19715_amd import binding as B
+    t, d, h = tiny_pair(seed=13)
+    prompt = synth.make_prompt(10, 1024, 6)
+    tw, dw, hw = oracle_model(t), oracle_model(d), oracle_head(h)
+    base, _, _ = R.oracle_generate(tw, dw, hw, prompt, R.Params(h=0.7, seed=2), 30, 6, 128, cached=True)
+    eos = base[12]
+    want, ost, _ = R.oracle_generate(tw, dw, hw, prompt, R.Params(h=0.7, seed=2, eos_id=eos), 30, 6, 128, cached=True)
+    ctx = _context(t, d, h, k_max=6, max_seq=128)
+    try:
+        ctx.sd_prefill(0, prompt)
+        seqs, st = ctx.specdec_generate(B.make_params(h=0.7, seed=2, eos_id=eos), 30)
+        assert seqs[0] == want and want[-1] == eos and len(want) <= 13
+        assert (st["N"], st["N_draft"], st["N_target"]) == (ost.N, ost.N_draft, ost.N_target)
+    finally:
+        ctx.close()
