@@ -39,7 +39,7 @@ from . import philox
 from .head import HeadWeights, accept_prob, should_stop
 from .model import CachedForward, ModelWeights, forward_full
 from .sampling import (accept_resample, argmax_lowest, cdf_margin, sample_inverse_cdf, softmax,
-                       top2_gap)
+                       top2_gap, warp_top_k)
 
 
 @dataclass
@@ -49,6 +49,7 @@ class Params:
     greedy: bool = False
     eos_id: int = -1          # < 0: none
     seed: int = 0
+    top_k: int = 0            # 0: full vocabulary; k > 0: top-k warping of both models (Appendix D.1)
 
 
 @dataclass
@@ -121,7 +122,7 @@ def oracle_round(target, draft, head: Optional[HeadWeights], x: List[int], rho: 
             y = argmax_lowest(logits[0])
             trace.append(("draft", i, y, top2_gap(logits[0])))
         else:
-            qi = softmax(logits[0], params.temperature)
+            qi = softmax(warp_top_k(logits[0], params.top_k), params.temperature)
             u = philox.uniform(params.seed, i, rho, seq, philox.STREAM_DRAFT)
             y = sample_inverse_cdf(qi, u)
             trace.append(("draft", i, y, cdf_margin(qi, u, y)))
@@ -141,7 +142,8 @@ def oracle_round(target, draft, head: Optional[HeadWeights], x: List[int], rho: 
     K = len(cand)
     p_logits, _ = target.tail(x + cand, K + 1)
     res = accept_resample(p_logits, np.stack(q_rows), cand, K, temperature=params.temperature,
-                          greedy=params.greedy, seed=params.seed, rnd=rho, seq=seq, forced=forced)
+                          greedy=params.greedy, seed=params.seed, rnd=rho, seq=seq, forced=forced,
+                          top_k=params.top_k)
     for i in range(1, K + 1):
         trace.append(("accept", i, int(res["flags"][i - 1]),
                       res["ratio"][i - 1] if params.greedy else abs(res["r"][i - 1] - res["ratio"][i - 1])))

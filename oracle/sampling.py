@@ -10,7 +10,8 @@ Readings where the paper is silent:
   * the accept test for r in [0,1) is  r < p(y)/q(y), evaluated without the
     division as r*q(y) < p(y);
   * a residual whose mass is numerically zero falls back to p_{n+1};
-  * greedy mode compares y_i with argmax p_i (Sec. 4.1), ties to the lowest id.
+  * greedy mode compares y_i with argmax p_i (Sec. 4.1), ties to the lowest id;
+  * top-k warping (Appendix D.1) keeps every logit >= the k-th largest of its row.
 
 Pins: chi-square of the emitted token against p on tiny vocabularies, the
 acceptance frequency sum_v min(p_v, q_v), p == q accepts everything, and the
@@ -28,6 +29,19 @@ def softmax(logits: np.ndarray, temperature: float = 1.0) -> np.ndarray:
     z = z - np.max(z, axis=-1, keepdims=True)
     ez = np.exp(z)
     return ez / np.sum(ez, axis=-1, keepdims=True)
+
+
+def warp_top_k(logits: np.ndarray, top_k: int) -> np.ndarray:
+    """Top-k warping of the paper's inference setting (Appendix D.1, k = 50): logits
+    below the k-th largest value of their row become -inf, so the softmax that follows
+    gives them probability 0.  Entries equal to the k-th largest value are all kept.
+    top_k <= 0 or >= V leaves the row unchanged."""
+    z = np.asarray(logits, dtype=np.float64)
+    v = z.shape[-1]
+    if top_k <= 0 or top_k >= v:
+        return z
+    kth = np.partition(z, v - top_k, axis=-1)[..., v - top_k]
+    return np.where(z >= kth[..., None], z, -np.inf)
 
 
 def argmax_lowest(x: np.ndarray) -> int:
@@ -70,7 +84,7 @@ def top2_gap(x: np.ndarray) -> float:
 
 def accept_resample(p_logits, q_logits, cand, K: int, *, temperature: float = 1.0,
                     greedy: bool = False, seed: int = 0, rnd: int = 0, seq: int = 0,
-                    forced: dict | None = None) -> dict:
+                    forced: dict | None = None, top_k: int = 0) -> dict:
     """Verify K candidates and produce the correction / bonus token.
 
     p_logits: [>=K+1, V] target logits for positions 1..K+1; q_logits: [>=K, V]
@@ -104,8 +118,9 @@ def accept_resample(p_logits, q_logits, cand, K: int, *, temperature: float = 1.
         return dict(n=n, token=int(token), flags=flags, ratio=ratio, r=rs, u=None,
                     margin=top2_gap(p_logits[n]))
 
-    p = softmax(p_logits[:K + 1], temperature)
-    q = softmax(q_logits[:K], temperature) if K > 0 else np.zeros((0, p.shape[1]))
+    # both models are warped the same way before the softmax (Appendix D.1)
+    p = softmax(warp_top_k(p_logits[:K + 1], top_k), temperature)
+    q = softmax(warp_top_k(q_logits[:K], top_k), temperature) if K > 0 else np.zeros((0, p.shape[1]))
     for i in range(1, K + 1):
         y = cand[i - 1]
         r = philox.uniform(seed, i, rnd, seq, philox.STREAM_ACCEPT)

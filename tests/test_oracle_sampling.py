@@ -159,3 +159,43 @@ def test_accept_uses_ratio_p_over_q_orientation():
         assert sampling.accept_resample(p_logits, q_logits, [0], 1, seed=2, rnd=t)["n"] == 1
         res = sampling.accept_resample(p_logits, q_logits, [2], 1, seed=2, rnd=t)
         assert res["n"] == 0 and res["token"] == 0       # residual mass sits on token 0 only
+
+
+def test_top_k_warp_matches_torch_topk_and_keeps_ties():
+    import torch
+    rng = np.random.default_rng(7)
+    x = rng.normal(size=(5, 40))
+    for k in (1, 3, 10, 39):
+        got = sampling.warp_top_k(x, k)
+        idx = torch.topk(torch.from_numpy(x), k, dim=-1).indices.numpy()
+        want = np.full_like(x, -np.inf)
+        np.put_along_axis(want, idx, np.take_along_axis(x, idx, -1), -1)
+        np.testing.assert_array_equal(got, want)
+    assert sampling.warp_top_k(x, 0) is not None and np.array_equal(sampling.warp_top_k(x, 0), x)
+    assert np.array_equal(sampling.warp_top_k(x, 40), x) and np.array_equal(sampling.warp_top_k(x, 99), x)
+    tied = np.array([[3.0, 1.0, 3.0, 2.0, 3.0]])
+    assert np.isfinite(sampling.warp_top_k(tied, 2)).sum() == 3       # all three maxima survive
+
+
+def test_top_k_rounds_are_unbiased_for_the_warped_target():
+    """With top-k warping on both models the emitted token follows the WARPED target
+    distribution, and never leaves the target's top-k set."""
+    rng = np.random.default_rng(8)
+    V, K, k, trials = 12, 2, 4, 30000
+    p_logits = _rand_dist(rng, (K + 1) * V).reshape(K + 1, V)
+    q_logits = p_logits[:K] + rng.normal(0, 1.0, size=(K, V))
+    pw = sampling.softmax(sampling.warp_top_k(p_logits, k))
+    qw = sampling.softmax(sampling.warp_top_k(q_logits, k))
+    counts = np.zeros((K + 1, V))
+    for t in range(trials):
+        cand = [sampling.sample_inverse_cdf(qw[i], philox.uniform(13, i + 1, t, 0, philox.STREAM_DRAFT)) for i in range(K)]
+        res = sampling.accept_resample(p_logits, q_logits, cand, K, seed=13, rnd=t, top_k=k)
+        for j, tok in enumerate(cand[: res["n"]] + [res["token"]]):
+            counts[j, tok] += 1
+    for j in range(K + 1):
+        tot = counts[j].sum()
+        assert (counts[j][pw[j] == 0] == 0).all()
+        if tot < 2000:
+            continue
+        keep = pw[j] > 0
+        assert stats.chisquare(counts[j][keep], pw[j][keep] * tot).pvalue > 1e-3, j
