@@ -84,8 +84,10 @@ typedef struct {
 
 /* Per-call decoding parameters: threshold h of the stop rule (stop when
  * 1 - prod p_hat > h, Sec. 4.3), softmax temperature (Appendix D.1 uses 1),
- * greedy mode (Sec. 4.1), optional EOS (manual stop, Sec. 4.2 footnote), and the
- * Philox seed.  Uniforms are Philox4x32-10 with key = seed and counter
+ * greedy mode (Sec. 4.1), optional EOS (manual stop, Sec. 4.2 footnote), top-k warping
+ * of both models' distributions before the softmax (the paper's inference setting is
+ * top-k = 50, Appendix D.1; every logit >= the k-th largest of its row is kept; 0 = full
+ * vocabulary), and the Philox seed.  Uniforms are Philox4x32-10 with key = seed and counter
  * (slot i, round index, sequence id, stream), stream 0 = draft sample,
  * 1 = accept test r_i, 2 = residual / bonus sample;
  * u = (word0 >> 8) * 2^-24. */
@@ -95,6 +97,8 @@ typedef struct {
   int32_t greedy;
   int32_t eos_id;                  /* < 0: none                                        */
   uint64_t seed;
+  int32_t top_k;                   /* 0: off                                           */
+  int32_t reserved;                /* must be 0                                        */
 } sd_params;
 
 /* Result of one round for one sequence (Algorithm 2's return): K candidates were

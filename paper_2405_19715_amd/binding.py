@@ -45,7 +45,7 @@ class sd_config(C.Structure):
 
 class sd_params(C.Structure):
     _fields_ = [("h", C.c_float), ("temperature", C.c_float), ("greedy", C.c_int32), ("eos_id", C.c_int32),
-                ("seed", C.c_uint64)]
+                ("seed", C.c_uint64), ("top_k", C.c_int32), ("reserved", C.c_int32)]
 
 
 class sd_round_out(C.Structure):
@@ -118,8 +118,8 @@ def _stream_ptr() -> int:
 
 
 def make_params(h: float = 0.7, temperature: float = 1.0, greedy: bool = False, eos_id: int = -1,
-                seed: int = 0) -> sd_params:
-    return sd_params(float(h), float(temperature), int(bool(greedy)), int(eos_id), int(seed))
+                seed: int = 0, top_k: int = 0) -> sd_params:
+    return sd_params(float(h), float(temperature), int(bool(greedy)), int(eos_id), int(seed), int(top_k), 0)
 
 
 def _model_struct(m: Dict, keep: list) -> sd_model:

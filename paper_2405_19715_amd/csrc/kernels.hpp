@@ -83,7 +83,7 @@ struct SeqState {          // device arrays, one entry per sequence unless noted
   int32_t* active;         // 0: the sequence sits this round out (finished)
 };
 
-struct DecodeParams { float h, temperature; int greedy, eos_id; uint64_t seed; };
+struct DecodeParams { float h, temperature; int greedy, eos_id; uint64_t seed; int top_k; };
 
 hipError_t launch_begin_round(hipStream_t st, const SeqState& s, int B, int k_max, int max_seq);
 hipError_t launch_plan_draft(hipStream_t st, const SeqState& s, const RowPlan& rows, int B, int step,
@@ -98,8 +98,10 @@ hipError_t launch_sample_stop(hipStream_t st, int dtype, const SeqState& s, cons
                               int step);
 // softmax statistics of the live rows of a [B, rows_per_seq, V] logits array (row j of
 // sequence b is live when j < K[b] + extra): stats[row] = {max, sum exp((l-max)/T), argmax, 0}
+// With top_k > 0 only logits >= the row's k-th largest enter the sum, and stats[row][3] holds
+// that threshold (else -inf).
 hipError_t launch_row_stats(hipStream_t st, const float* logits, int rows_per_seq, int extra, const int32_t* K,
-                            int B, int V, float temperature, float* stats, int32_t* err);
+                            int B, int V, float temperature, int top_k, float* stats, int32_t* err);
 // accept tests, n, and the residual / bonus sample y' for every sequence
 hipError_t launch_accept(hipStream_t st, const float* p_logits, const float* q_logits, const float* p_stats,
                          const float* q_stats, const int32_t* cand, int cand_ld, const int32_t* K,

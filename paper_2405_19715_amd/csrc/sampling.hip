@@ -41,6 +41,37 @@ __device__ ArgMax block_argmax(ArgMax a, float* shv, int* shi) {
   return r;
 }
 
+// Monotone map float -> uint32 (larger float, larger key).
+__device__ __forceinline__ uint32_t order_key(float x) {
+  const uint32_t u = __float_as_uint(x);
+  return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+__device__ __forceinline__ float key_to_float(uint32_t k) {
+  return __uint_as_float((k & 0x80000000u) ? (k & 0x7fffffffu) : ~k);
+}
+
+// The k-th largest of l[0..V) (1 <= k <= V), found bit by bit on the order keys: 32 passes
+// over the row (it stays in L2), each a block-wide count.  Top-k warping keeps l[v] >= it.
+// sh: SB/64 ints.
+__device__ float block_kth_largest(const float* __restrict__ l, int V, int k, int* sh) {
+  uint32_t t = 0;
+  const int w = threadIdx.x >> 6, nw = blockDim.x >> 6;
+  for (int bit = 31; bit >= 0; --bit) {
+    const uint32_t cand = t | (1u << bit);
+    int c = 0;
+    for (int v = threadIdx.x; v < V; v += blockDim.x) c += order_key(l[v]) >= cand ? 1 : 0;
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) c += __shfl_xor(c, o, WAVE);
+    if ((threadIdx.x & 63) == 0) sh[w] = c;
+    __syncthreads();
+    int tot = 0;
+    for (int i = 0; i < nw; ++i) tot += sh[i];
+    __syncthreads();
+    if (tot >= k) t = cand;
+  }
+  return key_to_float(t);
+}
+
 // Inverse-CDF draw over v in [0, V) with weight f(v) >= 0; returns -1 when the total
 // mass is not positive.  sh_incl: SB floats, sh_w: SB/64 floats, sh_res: 1 int.
 template <typename F>
@@ -191,8 +222,10 @@ __global__ __launch_bounds__(SB) void sample_stop_k(SeqState s, const float* __r
     y = am.i;
   } else {
     const float mx = am.v, inv_t = 1.0f / p.temperature;
+    const float thr = (p.top_k > 0 && p.top_k < V) ? block_kth_largest(l, V, p.top_k, sh_i) : -INFINITY;
     const float u = philox_uniform(p.seed, (uint32_t)step, (uint32_t)s.round[b], (uint32_t)b, STREAM_DRAFT);
-    y = block_sample([&](int v) { return expf((l[v] - mx) * inv_t); }, V, u, sh_incl, sh_w, &sh_res);
+    y = block_sample([&](int v) { return l[v] >= thr ? expf((l[v] - mx) * inv_t) : 0.f; }, V, u, sh_incl, sh_w,
+                     &sh_res);
     if (y < 0) y = am.i;                // only reachable with non-finite logits
   }
 
@@ -223,7 +256,7 @@ __global__ __launch_bounds__(SB) void sample_stop_k(SeqState s, const float* __r
 // stats[row] = {max, sum_v exp((l_v - max)/T), argmax (int bits), 0}.  Row (b, j) of a
 // [B, rows_per_seq, V] array is live when j < K[b] + extra.
 __global__ __launch_bounds__(SB) void row_stats_k(const float* __restrict__ logits, int rows_per_seq, int extra,
-                                                  const int32_t* __restrict__ K, int V, float inv_t,
+                                                  const int32_t* __restrict__ K, int V, float inv_t, int top_k,
                                                   float* __restrict__ stats, int32_t* __restrict__ err) {
   __shared__ float sh_w[SB / 64];
   __shared__ int sh_i[SB / 64];
@@ -240,17 +273,18 @@ __global__ __launch_bounds__(SB) void row_stats_k(const float* __restrict__ logi
   }
   am = block_argmax(am, sh_w, sh_i);
   if (bad && err) atomicOr(err, 1);
+  const float thr = (top_k > 0 && top_k < V) ? block_kth_largest(l, V, top_k, sh_i) : -INFINITY;
   // contiguous chunk per thread, then a fixed-order block reduction
   const int C = (V + SB - 1) / SB;
   const int v0 = min((int)threadIdx.x * C, V), v1 = min(v0 + C, V);
   float local = 0.f;
-  for (int v = v0; v < v1; ++v) local += expf((l[v] - am.v) * inv_t);
+  for (int v = v0; v < v1; ++v) local += l[v] >= thr ? expf((l[v] - am.v) * inv_t) : 0.f;
   const float total = block_sum(local, sh_w);
   if (threadIdx.x == 0) {
     stats[row * 4 + 0] = am.v;
     stats[row * 4 + 1] = total;
     stats[row * 4 + 2] = __int_as_float(am.i);
-    stats[row * 4 + 3] = 0.f;
+    stats[row * 4 + 3] = thr;
   }
 }
 
@@ -284,8 +318,9 @@ __global__ __launch_bounds__(SB) void accept_k(const float* __restrict__ p_logit
       if (p.greedy) {
         ok = (y == __float_as_int(ps[(i - 1) * 4 + 2])) ? 1 : 0;
       } else {
-        const float py = expf((pl[(size_t)(i - 1) * V + y] - ps[(i - 1) * 4]) * inv_t) / ps[(i - 1) * 4 + 1];
-        const float qy = expf((ql[(size_t)(i - 1) * V + y] - qs[(i - 1) * 4]) * inv_t) / qs[(i - 1) * 4 + 1];
+        const float lp = pl[(size_t)(i - 1) * V + y], lq = ql[(size_t)(i - 1) * V + y];
+        const float py = lp >= ps[(i - 1) * 4 + 3] ? expf((lp - ps[(i - 1) * 4]) * inv_t) / ps[(i - 1) * 4 + 1] : 0.f;
+        const float qy = lq >= qs[(i - 1) * 4 + 3] ? expf((lq - qs[(i - 1) * 4]) * inv_t) / qs[(i - 1) * 4 + 1] : 0.f;
         const float r = philox_uniform(p.seed, (uint32_t)i, (uint32_t)rnd, (uint32_t)b, STREAM_ACCEPT);
         ok = (r * qy < py) ? 1 : 0;                      // accept iff r < p(y)/q(y)
       }
@@ -307,21 +342,24 @@ __global__ __launch_bounds__(SB) void accept_k(const float* __restrict__ p_logit
     y = __float_as_int(ps[n * 4 + 2]);
   } else {
     const float* prow = pl + (size_t)n * V;
-    const float pmx = ps[n * 4], pinv = 1.0f / ps[n * 4 + 1];
+    const float pmx = ps[n * 4], pinv = 1.0f / ps[n * 4 + 1], pthr = ps[n * 4 + 3];
     const float u = philox_uniform(p.seed, (uint32_t)(n + 1), (uint32_t)rnd, (uint32_t)b, STREAM_RESAMPLE);
     y = -1;
     if (n < K) {                                         // residual Norm[(p_{n+1} - q_{n+1})_+]
       const float* qrow = ql + (size_t)n * V;
-      const float qmx = qs[n * 4], qinv = 1.0f / qs[n * 4 + 1];
+      const float qmx = qs[n * 4], qinv = 1.0f / qs[n * 4 + 1], qthr = qs[n * 4 + 3];
       y = block_sample(
           [&](int v) {
-            return fmaxf(expf((prow[v] - pmx) * inv_t) * pinv - expf((qrow[v] - qmx) * inv_t) * qinv, 0.f);
+            const float pv = prow[v] >= pthr ? expf((prow[v] - pmx) * inv_t) * pinv : 0.f;
+            const float qv = qrow[v] >= qthr ? expf((qrow[v] - qmx) * inv_t) * qinv : 0.f;
+            return fmaxf(pv - qv, 0.f);
           },
           V, u, sh_incl, sh_w, &sh_res);
       __syncthreads();
     }
     if (y < 0)                                           // bonus token from p_{K+1}, or a residual with no mass
-      y = block_sample([&](int v) { return expf((prow[v] - pmx) * inv_t) * pinv; }, V, u, sh_incl, sh_w, &sh_res);
+      y = block_sample([&](int v) { return prow[v] >= pthr ? expf((prow[v] - pmx) * inv_t) * pinv : 0.f; }, V, u,
+                       sh_incl, sh_w, &sh_res);
     if (y < 0) y = __float_as_int(ps[n * 4 + 2]);
   }
   if (threadIdx.x == 0) {
@@ -401,11 +439,11 @@ hipError_t launch_sample_stop(hipStream_t st, int dtype, const SeqState& s, cons
 }
 
 hipError_t launch_row_stats(hipStream_t st, const float* logits, int rows_per_seq, int extra, const int32_t* K, int B,
-                            int V, float temperature, float* stats, int32_t* err) {
-  if (B < 1 || rows_per_seq < 1 || V < 1 || !logits || !K || !stats || !(temperature > 0.f))
+                            int V, float temperature, int top_k, float* stats, int32_t* err) {
+  if (B < 1 || rows_per_seq < 1 || V < 1 || top_k < 0 || !logits || !K || !stats || !(temperature > 0.f))
     return hipErrorInvalidValue;
   hipLaunchKernelGGL(row_stats_k, dim3(rows_per_seq, B), dim3(SB), 0, st, logits, rows_per_seq, extra, K, V,
-                     1.0f / temperature, stats, err);
+                     1.0f / temperature, top_k, stats, err);
   return hipGetLastError();
 }
 

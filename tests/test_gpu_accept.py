@@ -15,14 +15,14 @@ ACCEPT_TOL = 1e-3      # |r - p/q| below which an accept decision may differ
 CDF_TOL = 1e-5         # distance to a bucket edge (fraction of the mass) below which y' may differ
 
 
-def _candidates(q_logits, K, seed, rnd, b):
+def _candidates(q_logits, K, seed, rnd, b, top_k=0):
     """Candidates drawn from q by the oracle's sampler (stream 0), as the round does."""
-    q = sampling.softmax(q_logits[:K].double().numpy())
+    q = sampling.softmax(sampling.warp_top_k(q_logits[:K].double().numpy(), top_k))
     return [sampling.sample_inverse_cdf(q[i], philox.uniform(seed, i + 1, rnd, b, philox.STREAM_DRAFT))
             for i in range(K)]
 
 
-def _run_case(B, Kmax, V, seed, rounds, greedy=False, ragged=False):
+def _run_case(B, Kmax, V, seed, rounds, greedy=False, ragged=False, top_k=0):
     from paper_2405_19715_amd import binding as Bd
     p, q = synth.make_accept_logits(B, Kmax, V, seed)
     rng = np.random.default_rng(seed)
@@ -36,15 +36,15 @@ def _run_case(B, Kmax, V, seed, rounds, greedy=False, ragged=False):
             if greedy:
                 cand[b, : Ks[b]] = q[b, : Ks[b]].argmax(-1).numpy()
             else:
-                cand[b, : Ks[b]] = _candidates(q[b], Ks[b], seed, rnd, b)
-        params = Bd.make_params(seed=seed, greedy=greedy)
+                cand[b, : Ks[b]] = _candidates(q[b], Ks[b], seed, rnd, b, top_k)
+        params = Bd.make_params(seed=seed, greedy=greedy, top_k=top_k)
         n, tok, flags = Bd.sd_accept_resample(pc, qc, torch.from_numpy(cand).cuda(),
                                               torch.from_numpy(Ks.astype(np.int32)).cuda(), params, rnd)
         n, tok, flags = n.cpu().numpy(), tok.cpu().numpy(), flags.cpu().numpy()
         for b in range(B):
             K = int(Ks[b])
             o = sampling.accept_resample(p[b].numpy(), q[b].numpy(), cand[b], K, greedy=greedy, seed=seed,
-                                         rnd=rnd, seq=b)
+                                         rnd=rnd, seq=b, top_k=top_k)
             forced = {}
             for i in range(1, K + 1):
                 if flags[b, i - 1] != o["flags"][i - 1]:
@@ -54,7 +54,7 @@ def _run_case(B, Kmax, V, seed, rounds, greedy=False, ragged=False):
             assert (flags[b, K:] == 0).all()
             if forced:
                 o = sampling.accept_resample(p[b].numpy(), q[b].numpy(), cand[b], K, greedy=greedy, seed=seed,
-                                             rnd=rnd, seq=b, forced=forced)
+                                             rnd=rnd, seq=b, forced=forced, top_k=top_k)
             assert n[b] == o["n"], (b, rnd)
             if tok[b] != o["token"]:
                 assert not greedy and o["margin"] < CDF_TOL, (b, rnd, tok[b], o["token"], o["margin"])
@@ -69,6 +69,43 @@ def test_accept_parity_full_vocab(B, K):
     rounds = max(1, 64 // (B * K) + 1)
     _, exempt, tests = _run_case(B, K, 32000, seed=B * 100 + K, rounds=rounds)
     assert exempt <= max(2, tests // 200)
+
+
+@pytest.mark.parametrize("top_k", [1, 2, 50, 31999, 32000, 40000])
+def test_accept_parity_top_k(top_k):
+    """Top-k warping of both models (Appendix D.1; the paper runs k = 50), including the
+    degenerate k = 1 (point masses: accept iff the two argmaxes agree) and k >= V (off)."""
+    rate, exempt, tests = _run_case(16, 8, 32000, seed=700 + top_k % 97, rounds=2, top_k=top_k)
+    assert exempt <= 2
+    if top_k >= 32000:
+        rate0, _, _ = _run_case(16, 8, 32000, seed=700 + top_k % 97, rounds=2, top_k=0)
+        assert rate == rate0
+
+
+def test_top_k_keeps_ties_at_the_threshold():
+    """Rows quantised to a few distinct values put many logits exactly on the k-th
+    largest value; all of them stay in the support on both sides."""
+    from paper_2405_19715_amd import binding as Bd
+    B, K, V, top_k, seed = 4, 4, 4096, 50, 11
+    g = torch.Generator().manual_seed(seed)
+    p = torch.round(torch.randn(B, K + 1, V, generator=g) * 2.0) * 0.5
+    q = torch.round(p[:, :K] * 2.0 + torch.randn(B, K, V, generator=g) * 0.6) * 0.5
+    Ks = np.full(B, K, dtype=np.int32)
+    for rnd in range(3):
+        cand = np.stack([_candidates(q[b], K, seed, rnd, b, top_k) for b in range(B)]).astype(np.int32)
+        n, tok, flags = Bd.sd_accept_resample(p.cuda(), q.cuda(), torch.from_numpy(cand).cuda(),
+                                              torch.from_numpy(Ks).cuda(),
+                                              Bd.make_params(seed=seed, top_k=top_k), rnd)
+        for b in range(B):
+            o = sampling.accept_resample(p[b].numpy(), q[b].numpy(), cand[b], K, seed=seed, rnd=rnd, seq=b,
+                                         top_k=top_k)
+            kept = int((sampling.warp_top_k(p[b, 0].double().numpy(), top_k) > -np.inf).sum())
+            assert kept > top_k                       # the case really has ties at the threshold
+            assert (flags[b].cpu().numpy()[:K] == o["flags"]).all() or \
+                np.min(np.abs(o["r"] - o["ratio"])) < ACCEPT_TOL
+            if (flags[b].cpu().numpy()[:K] == o["flags"]).all():
+                assert int(n[b]) == o["n"]
+                assert int(tok[b]) == o["token"] or o["margin"] < CDF_TOL
 
 
 def test_ragged_k_and_greedy():

@@ -69,6 +69,24 @@ def test_tiny_pair_free_running_parity(greedy):
         ctx.close()
 
 
+@pytest.mark.parametrize("top_k", [1, 8, 50])
+def test_tiny_pair_free_running_parity_top_k(top_k):
+    """Sampled rounds with top-k warping of both models (Appendix D.1)."""
+    from paper_2405_19715_amd import binding as B
+    t, d, h = tiny_pair()
+    prompt = synth.make_prompt(48, 1024, 4)
+    ctx = _context(t, d, h, k_max=8, max_seq=256)
+    try:
+        ctx.sd_prefill(0, prompt)
+        op = R.Params(h=0.7, temperature=0.8, seed=9, top_k=top_k)
+        gp = B.make_params(h=0.7, temperature=0.8, seed=9, top_k=top_k)
+        toks, exempt, hist = run_free_running(ctx, oracle_model(t), oracle_model(d), oracle_head(h), prompt, op, gp,
+                                              96, 8, 256)
+        assert len(toks) == 96 and exempt <= 2
+    finally:
+        ctx.close()
+
+
 def test_greedy_generate_equals_target_only_greedy_and_counters():
     from paper_2405_19715_amd import binding as B
     t, d, h = tiny_pair(seed=3)
@@ -130,6 +148,10 @@ def test_cache_capacity_and_bad_arguments():
         assert e.value.status == B.SD_ERANGE
         prompt = synth.make_prompt(58, 1024, 2)
         ctx.sd_prefill(0, prompt)
+        for bad in (B.make_params(top_k=-1), B.make_params(temperature=0.0)):
+            with pytest.raises(B.SpecDecError) as e:
+                ctx.specdec_round(bad)
+            assert e.value.status == B.SD_EINVAL and ctx.sd_seq_state(0)["P"] == 58
         r = ctx.specdec_round(B.make_params(h=1.0, seed=1))[0]
         assert r["K"] == 64 - 58 - 1                        # cap = max_seq - P - 1
         # rounds go on until the cache is full, then the call reports it and changes nothing
