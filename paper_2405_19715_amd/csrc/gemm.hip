@@ -20,11 +20,13 @@
 //                large power of two, do not all hit the same HBM channels at once.
 //   few, long-lived workgroups (about one per CU) measured faster than many short ones:
 //                fewer concurrent DRAM streams and no repeated X staging.
-//   M >= 5     : v_mfma_f32_16x16x32_bf16, weights as the A operand (16 rows x 32 k),
-//                X^T as the B operand (32 k x 16 activation rows), one MFMA per 16-row
-//                tile of X; the last tile keeps only its live rows in LDS.
-//   M <= 4     : no MFMA; per-lane fp32 dot products over the same loads, then a
-//                reduction over the 4 lane groups with two wavefront shuffles.
+//   multiply   = v_mfma_f32_16x16x32_bf16 for every M, weights as the A operand (16 rows
+//                x 32 k), X^T as the B operand (32 k x 16 activation rows), one MFMA per
+//                16-row tile of X; the last tile keeps only its live rows in LDS.  Per-lane
+//                fp32 dot products with a shuffle reduction were measured for M <= 4 and
+//                were slower (M = 1, 12288 x 4096: 29 us against 23 us): the matrix core
+//                costs the wavefront one issue slot per 64 B of weights where the dot
+//                product costs sixteen.
 // Per-slice partial sums go to part[s] and are added by the consumer in slice order,
 // so results do not depend on scheduling.
 // fp32 weights (tiny configuration) take a plain wave-per-output-row kernel.
@@ -47,8 +49,7 @@ struct Split { int S, steps_per, G; };
 
 // Pick the K-slice length (steps_per) and the number of row groups G by a small cost
 // model of the stream, fitted to measurements on the MI355X:
-//   - every workgroup must be resident at once (it is a persistent design): at most two
-//     per CU, fewer when the X slice in LDS is large;
+//   - every workgroup must be resident at once (it is a persistent design): one per CU;
 //   - a wavefront with PREFETCH steps in flight sustains about 2.6 GB/s under load, and all
 //     of them together about 5.3 TB/s;
 //   - the slowest wavefront (most tiles x steps) ends the kernel;
@@ -66,7 +67,7 @@ Split plan_bf16(int M, int N, int K) {
   for (int sp = max_steps; sp >= 1; --sp) {
     const int S = (total + sp - 1) / sp;
     const size_t lds = (size_t)M * sp * KSTEP * 2;
-    const int resident = M >= 5 ? 1 : 2;   // MFMA path: one workgroup per CU measured best
+    const int resident = 1;                // one workgroup per CU measured best   // MFMA path: one workgroup per CU measured best
     int g_hi = (256 * resident) / S;
     if (g_hi > g_max) g_hi = g_max;
     if (g_hi < 1) {
@@ -99,25 +100,11 @@ __device__ __forceinline__ bf16x8 as_bf16x8(const uint4& v) {
   return c.b;
 }
 
-// fp32 dot of 8 bf16 pairs packed in two uint4
-__device__ __forceinline__ float dot8(const uint4& a, const uint4& b, float acc) {
-  const uint32_t* pa = reinterpret_cast<const uint32_t*>(&a);
-  const uint32_t* pb = reinterpret_cast<const uint32_t*>(&b);
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    acc = fmaf(__uint_as_float(pa[i] << 16), __uint_as_float(pb[i] << 16), acc);
-    acc = fmaf(__uint_as_float(pa[i] & 0xffff0000u), __uint_as_float(pb[i] & 0xffff0000u), acc);
-  }
-  return acc;
-}
-
 // Stage X[0..M, kbeg .. kbeg + 128*steps) into LDS as 16-byte groups.  Group o of a row
 // covers k = kbeg + 8 o ..; within a 128-k step it is (j = (o / 4) % 4, g = o % 4).
 //   MFMA order: group (m, step s, j, g) lands at
 //     tile_base(m / 16) + (((s*4 + j)*4 + g) * rows_in_tile + m % 16)
 //   so that lane (r, g) of MFMA j reads one 16-byte word at a lane-linear address.
-//   Row-major order (dot path): [m][o].
-template <bool MFMA_ORDER>
 __device__ __forceinline__ void stage_x(uint4* lds, const bf16_t* X, int ldx, const int* xrow, int M, int kbeg,
                                         int steps) {
   const int groups_per_row = steps * 16;
@@ -127,14 +114,10 @@ __device__ __forceinline__ void stage_x(uint4* lds, const bf16_t* X, int ldx, co
     const int m = idx / groups_per_row, o = idx - m * groups_per_row;
     const int src_row = xrow ? xrow[m] : m;
     const uint4 v = ldg128(X + (size_t)src_row * ldx + kbeg + o * 8);
-    if (MFMA_ORDER) {
-      const int s = o >> 4, j = (o >> 2) & 3, g = o & 3;
-      const int tile = m >> 4, r = m & 15;
-      const int rows_in_tile = (tile == last_tile) ? rows_last : 16;
-      lds[tile * groups_per_row * 16 + (((s * 4 + j) * 4 + g) * rows_in_tile + r)] = v;
-    } else {
-      lds[idx] = v;
-    }
+    const int s = o >> 4, j = (o >> 2) & 3, g = o & 3;
+    const int tile = m >> 4, r = m & 15;
+    const int rows_in_tile = (tile == last_tile) ? rows_last : 16;
+    lds[tile * groups_per_row * 16 + (((s * 4 + j) * 4 + g) * rows_in_tile + r)] = v;
   }
 }
 
@@ -151,16 +134,13 @@ struct WaveWalk {
   }
 };
 
-// MODE > 0: MFMA with NT = MODE activation tiles.  MODE < 0: dot products over -MODE rows.
-template <int MODE>
+// NT = number of 16-row activation tiles, ceil(M / 16).
+template <int NT>
 __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_stream(const bf16_t* __restrict__ W,
                                                                  const bf16_t* __restrict__ X, int ldx,
                                                                  const int* __restrict__ xrow,
                                                                  float* __restrict__ part, int M, int N, int K,
                                                                  int steps_per, int G) {
-  constexpr bool MFMA = MODE > 0;
-  constexpr int NT = MFMA ? MODE : 1;
-  constexpr int MV = MFMA ? 1 : -MODE;
   extern __shared__ uint4 lds[];
   const int total_steps = K / KSTEP;
   const int ks = blockIdx.y, grp = blockIdx.x;
@@ -190,17 +170,14 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_stream(const bf16_t* _
       for (int j = 0; j < 4; ++j) a[p][j] = ldg128(q + j * 32);
     }
 
-  stage_x<MFMA>(lds, X, ldx, xrow, M, kbeg, steps);
+  stage_x(lds, X, ldx, xrow, M, kbeg, steps);
   __syncthreads();
 
   const int groups_per_row = steps * 16;
   const int rows_last = M - ((NT - 1) << 4);
   floatx4 acc[NT];
-  float dacc[MV];
 #pragma unroll
   for (int t = 0; t < NT; ++t) acc[t] = floatx4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-  for (int m = 0; m < MV; ++m) dacc[m] = 0.f;
   float* pout = part + (size_t)ks * M * N;
   int sl = 0, tile = 0;
 
@@ -219,53 +196,30 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_stream(const bf16_t* _
         }
         int s = sl + ww.rot;
         if (s >= steps) s -= steps;
-        if (MFMA) {
 #pragma unroll
-          for (int j = 0; j < 4; ++j) {
-            const bf16x8 av = as_bf16x8(cur[j]);
+        for (int j = 0; j < 4; ++j) {
+          const bf16x8 av = as_bf16x8(cur[j]);
 #pragma unroll
-            for (int t = 0; t < NT; ++t) {
-              uint4 bv;
-              if (t < NT - 1) {
-                bv = lds[t * groups_per_row * 16 + (((s * 4 + j) * 4 + g) * 16 + r)];
-              } else {
-                bv = (r < rows_last)
-                         ? lds[t * groups_per_row * 16 + (((s * 4 + j) * 4 + g) * rows_last + r)]
-                         : uint4{0u, 0u, 0u, 0u};
-              }
-              acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, as_bf16x8(bv), acc[t], 0, 0, 0);
+          for (int t = 0; t < NT; ++t) {
+            uint4 bv;
+            if (t < NT - 1) {
+              bv = lds[t * groups_per_row * 16 + (((s * 4 + j) * 4 + g) * 16 + r)];
+            } else {
+              bv = (r < rows_last) ? lds[t * groups_per_row * 16 + (((s * 4 + j) * 4 + g) * rows_last + r)]
+                                   : uint4{0u, 0u, 0u, 0u};
             }
-          }
-        } else {
-#pragma unroll
-          for (int j = 0; j < 4; ++j) {
-#pragma unroll
-            for (int m = 0; m < MV; ++m) {
-              const uint4 xv = lds[m * groups_per_row + s * 16 + j * 4 + g];   // one address per lane group
-              dacc[m] = dot8(cur[j], xv, dacc[m]);
-            }
+            acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, as_bf16x8(bv), acc[t], 0, 0, 0);
           }
         }
         if (++sl == steps) {                  // tile finished: write its partial sums, start the next
           const int row0 = (wslot + tile * nslots) * 16;
-          if (MFMA) {
-            // D[i, n]: lane (n = lane % 16, i = 4 * (lane / 16) + 0..3): four consecutive weight
-            // rows for activation row n -> one 16-byte store.
+          // D[i, n]: lane (n = lane % 16, i = 4 * (lane / 16) + 0..3): four consecutive weight
+          // rows for activation row n -> one 16-byte store.
 #pragma unroll
-            for (int t = 0; t < NT; ++t) {
-              const int m = t * 16 + r;
-              if (m < M) *reinterpret_cast<floatx4*>(pout + (size_t)m * N + row0 + 4 * g) = acc[t];
-              acc[t] = floatx4{0.f, 0.f, 0.f, 0.f};
-            }
-          } else {
-#pragma unroll
-            for (int m = 0; m < MV; ++m) {
-              float v = dacc[m];
-              v += __shfl_xor(v, 16, WAVE);
-              v += __shfl_xor(v, 32, WAVE);
-              if (g == 0) pout[(size_t)m * N + row0 + r] = v;
-              dacc[m] = 0.f;
-            }
+          for (int t = 0; t < NT; ++t) {
+            const int m = t * 16 + r;
+            if (m < M) *reinterpret_cast<floatx4*>(pout + (size_t)m * N + row0 + 4 * g) = acc[t];
+            acc[t] = floatx4{0.f, 0.f, 0.f, 0.f};
           }
           sl = 0;
           ++tile;
@@ -307,19 +261,19 @@ __global__ __launch_bounds__(256) void gemm_f32(const float* __restrict__ W, con
   }
 }
 
-template <int MODE>
+template <int NT>
 hipError_t launch_stream(hipStream_t st, const bf16_t* W, const bf16_t* X, int ldx, const int* xrow, float* part, int M,
                          int N, int K, Split sp) {
   const dim3 grid(sp.G, sp.S);
   const size_t lds = (size_t)M * sp.steps_per * KSTEP * 2;
   static bool attr_set = false;          // dynamic LDS above 64 KB has to be allowed once per kernel
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_bf16_stream<MODE>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_bf16_stream<NT>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, LDS_MAX + 8 * 1024);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  hipLaunchKernelGGL(gemm_bf16_stream<MODE>, grid, dim3(GEMM_THREADS), lds, st, W, X, ldx, xrow, part, M, N, K,
+  hipLaunchKernelGGL(gemm_bf16_stream<NT>, grid, dim3(GEMM_THREADS), lds, st, W, X, ldx, xrow, part, M, N, K,
                      sp.steps_per, sp.G);
   return hipGetLastError();
 }
@@ -347,14 +301,6 @@ hipError_t launch_gemm(hipStream_t st, int dtype, const void* W, const void* X, 
   const Split sp = plan_bf16(M, N, K);
   const bf16_t* w = (const bf16_t*)W;
   const bf16_t* x = (const bf16_t*)X;
-  if (M <= 4) {
-    switch (M) {
-      case 1: return launch_stream<-1>(st, w, x, ldx, xrow, part, M, N, K, sp);
-      case 2: return launch_stream<-2>(st, w, x, ldx, xrow, part, M, N, K, sp);
-      case 3: return launch_stream<-3>(st, w, x, ldx, xrow, part, M, N, K, sp);
-      default: return launch_stream<-4>(st, w, x, ldx, xrow, part, M, N, K, sp);
-    }
-  }
   const int nt = (M + 15) / 16;
   switch (nt) {
     case 1: return launch_stream<1>(st, w, x, ldx, xrow, part, M, N, K, sp);

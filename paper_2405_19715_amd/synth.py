@@ -116,6 +116,17 @@ def make_perturbed_draft(target: Dict, n_layers: int, seed: int, std: float = 0.
     return m
 
 
+def damp_tail(model: Dict, first: int, gain: float) -> None:
+    """Scale, in place, the two matrices that write into the residual stream (wo, w_down)
+    of layers first.. by `gain`.  With gain < 1 those layers move the final hidden state
+    only a little, so a draft made of the layers before them (make_perturbed_draft) stays
+    aligned with the full model: the recipe for a pair whose acceptance rate is tunable
+    without trained weights."""
+    for lay in model["layers"][first:]:
+        for name in ("wo", "w_down"):
+            lay[name].mul_(gain)
+
+
 def make_head(dims: List[int], seed: int, device="cpu", dtype=torch.float32, residual: bool = False,
               out_bias: float = 1.386, std: float = 0.02) -> Dict:
     """Acceptance-head weights: len(dims)-1 layers, dims[-1] == 1.  The output bias
