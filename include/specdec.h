@@ -202,6 +202,15 @@ sd_status sd_profile_read(sd_ctx *ctx, int64_t *launches, double *seconds, doubl
  * 16-byte aligned.  Enqueued on `hip_stream`; does not synchronise. */
 sd_status sd_gemm_skinny(int32_t dtype, const void *W_dev, const void *X_dev, int32_t M, int32_t N, int32_t K,
                          float *Y_dev, void *ws_dev, void *hip_stream);
+
+/* The large-M GEMM of the prompt pass (both models ingest the prefix before the first
+ * round of Algorithm 2; with hundreds of rows per weight this is bound by the matrix
+ * cores, not by the weight stream): Y[m, n] = sum_k X[m, k] * W[n, k], bf16 in, fp32 out.
+ * W: DEVICE bf16 [N, K]; X: DEVICE bf16 [M, K]; Y: DEVICE fp32 [M, N].  M >= 1,
+ * K % 32 == 0, N % 4 == 0, pointers 16-byte aligned; SD_EDEVICE otherwise.  Enqueued on
+ * `hip_stream`; does not synchronise; no workspace. */
+sd_status sd_gemm_tile(const void *W_dev, const void *X_dev, int32_t M, int32_t N, int32_t K, float *Y_dev,
+                       void *hip_stream);
 int64_t sd_gemm_workspace_bytes(int32_t dtype, int32_t M, int32_t N, int32_t K);
 
 const char *sd_strerror(sd_status s);

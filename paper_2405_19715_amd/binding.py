@@ -78,6 +78,7 @@ _PROTOS = {
     "sd_profile_read": (C.c_int32, [C.c_void_p, C.POINTER(C.c_int64), C.POINTER(C.c_double), C.POINTER(C.c_double)]),
     "sd_gemm_skinny": (C.c_int32, [C.c_int32, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p,
                                    C.c_void_p, C.c_void_p]),
+    "sd_gemm_tile": (C.c_int32, [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]),
     "sd_gemm_workspace_bytes": (C.c_int64, [C.c_int32, C.c_int32, C.c_int32, C.c_int32]),
     "sd_strerror": (C.c_char_p, [C.c_int32]),
     "sd_version": (C.c_char_p, []),
@@ -263,4 +264,15 @@ def sd_gemm_skinny(W: torch.Tensor, X: torch.Tensor, out=None) -> torch.Tensor:
     Y, ws = out
     _check(lib.sd_gemm_skinny(dt, W.data_ptr(), X.data_ptr(), M, N, K, Y.data_ptr(), ws.data_ptr(), _stream_ptr()),
            "sd_gemm_skinny")
+    return Y
+
+
+def sd_gemm_tile(W: torch.Tensor, X: torch.Tensor, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """Y = X W^T in fp32 through the large-M kernel.  W [N, K], X [M, K], bf16, CUDA, contiguous."""
+    assert W.is_cuda and X.is_cuda and W.is_contiguous() and X.is_contiguous()
+    assert W.dtype == torch.bfloat16 and X.dtype == torch.bfloat16
+    (N, K), (M, K2) = W.shape, X.shape
+    assert K == K2
+    Y = out if out is not None else torch.empty((M, N), dtype=torch.float32, device=W.device)
+    _check(lib.sd_gemm_tile(W.data_ptr(), X.data_ptr(), M, N, K, Y.data_ptr(), _stream_ptr()), "sd_gemm_tile")
     return Y

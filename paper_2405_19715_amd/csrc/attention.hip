@@ -21,6 +21,9 @@
 // the sequence's row group: up to 17 x 8 = 136 vectors share each streamed K/V tile.
 // Every wavefront takes one block of 64 keys (for its share of the query tiles) and
 // writes one (max, sum, O) partial; a second kernel merges the partials in block order.
+// The prompt pass (hundreds of rows, FULL = true) has enough query tiles to fill the chip
+// without splitting the keys: there a wavefront walks every key block its tiles can see,
+// carrying the online softmax, and writes the finished rows itself.
 #include "common.hpp"
 #include "kernels.hpp"
 
@@ -42,14 +45,15 @@ __device__ __forceinline__ bf16x8 as_bf16x8(const uint4& v) {
 __device__ __forceinline__ uint32_t pack2(float lo, float hi) { return (uint32_t)f2bf(lo) | ((uint32_t)f2bf(hi) << 16); }
 
 // ------------------------------------------------------------------ MFMA kernel (bf16)
-template <int HD, int QTW>
+template <int HD, int QTW, bool FULL>
 __global__ __launch_bounds__(256) void attn_mfma_k(const bf16_t* __restrict__ qbuf, const bf16_t* __restrict__ kcache,
                                                    const bf16_t* __restrict__ vcache,
                                                    const int32_t* __restrict__ row_seq,
                                                    const int32_t* __restrict__ row_pos,
                                                    const int32_t* __restrict__ grp_seq,
                                                    const int32_t* __restrict__ grp_end, float* __restrict__ scratch,
-                                                   int RS, int Hq, int Hkv, int max_seq, int QW, int NQG, int NSP) {
+                                                   bf16_t* __restrict__ out, int RS, int Hq, int Hkv, int max_seq,
+                                                   int QW, int NQG, int NSP) {
   constexpr int DT = HD / 16;          // 16-wide tiles of the head dimension
   constexpr int KS = HD / 32;          // MFMA k-steps of the score product
   constexpr int STRIDE = HD + 4;       // floats per partial: O[HD], max, sum, pad
@@ -64,9 +68,10 @@ __global__ __launch_bounds__(256) void attn_mfma_k(const bf16_t* __restrict__ qb
   const int KW = 4 / QW;
   const int qw = wave % QW, kw = wave / QW;
   const int sp = c * KW + kw;              // this wave's key block, also its partial's index
-  const int kbeg = sp * KB;
+  if (FULL && kw != 0) return;             // keys are not split: one wave per set of query tiles
+  const int kbeg = FULL ? 0 : sp * KB;
   if (kbeg >= kv_end) return;
-  const int kend = min(kbeg + KB, kv_end);
+  int kend = min(kbeg + KB, kv_end);
 
   const bf16_t* kbase = kcache + ((size_t)seq * Hkv + kh) * (size_t)max_seq * HD;
   const bf16_t* vbase = vcache + ((size_t)seq * Hkv + kh) * (size_t)HD * max_seq;
@@ -97,6 +102,15 @@ __global__ __launch_bounds__(256) void attn_mfma_k(const bf16_t* __restrict__ qb
         for (int j = 0; j < KS; ++j) qf[q][j] = ld16(qp + j * 8);
       }
     }
+  }
+
+  if (FULL) {                              // causal: nothing beyond the largest position of the wave's rows
+    int lim = -1;
+#pragma unroll
+    for (int q = 0; q < QTW; ++q) lim = max(lim, limit[q]);
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) lim = max(lim, __shfl_xor(lim, o, WAVE));
+    kend = min(lim + 1, kv_end);
   }
 
   floatx4 o[QTW][DT];
@@ -190,7 +204,21 @@ __global__ __launch_bounds__(256) void attn_mfma_k(const bf16_t* __restrict__ qb
     }
   }
 
-  // partials: lane (qv = li, d = 16 dt + 4 g + r)
+  // lane (qv = li, d = 16 dt + 4 g + r)
+  if (FULL) {
+#pragma unroll
+    for (int q = 0; q < QTW; ++q) {
+      if (orow[q] < 0) continue;
+      const float inv = lrun[q] > 0.f ? 1.0f / lrun[q] : 0.f;
+      bf16_t* dst = out + ((size_t)orow[q] * Hq + ohead[q]) * HD;
+#pragma unroll
+      for (int dt = 0; dt < DT; ++dt) {
+        const floatx4 v = o[q][dt];
+        *reinterpret_cast<uint2*>(dst + dt * 16 + 4 * g) = uint2{pack2(v[0] * inv, v[1] * inv), pack2(v[2] * inv, v[3] * inv)};
+      }
+    }
+    return;
+  }
 #pragma unroll
   for (int q = 0; q < QTW; ++q) {
     if (orow[q] < 0) continue;
@@ -326,8 +354,8 @@ size_t attn_scratch_floats(int M, int Hq, int hd, int max_seq) {
 
 hipError_t launch_attention(hipStream_t st, int dtype, const void* qbuf, const void* kcache, const void* vcache,
                             const RowPlan& rows, void* out, float* scratch, int M, int RS, int Hq, int Hkv, int hd,
-                            int max_seq, int max_kv_len) {
-  if (M < 1 || M > MAX_ROWS || RS < 1 || M % RS != 0 || Hq < 1 || Hkv < 1 || Hq % Hkv != 0 || max_kv_len < 1 ||
+                            int max_seq, int max_kv_len, bool full) {
+  if (M < 1 || M > (full ? MAX_PREFILL_ROWS : MAX_ROWS) || RS < 1 || M % RS != 0 || Hq < 1 || Hkv < 1 || Hq % Hkv != 0 || max_kv_len < 1 ||
       max_kv_len > max_seq || !qbuf || !kcache || !vcache || !out || !rows.seq || !rows.pos || !rows.gseq || !rows.gend)
     return hipErrorInvalidValue;
   const int ngroups = M / RS;
@@ -345,22 +373,30 @@ hipError_t launch_attention(hipStream_t st, int dtype, const void* qbuf, const v
                          hd, max_seq);
     return hipGetLastError();
   }
-  if (dtype != DT_BF16 || (hd != 64 && hd != 128) || max_seq % KB != 0 || max_seq > 512 * KB || !scratch)
+  if (full && use_plain(dtype)) return hipErrorInvalidValue;
+  if (dtype != DT_BF16 || (hd != 64 && hd != 128) || max_seq % KB != 0 || max_seq > 512 * KB || (!scratch && !full))
     return hipErrorInvalidValue;
   const MfmaShape sh = mfma_shape(RS, Hq / Hkv);
   const int KW = 4 / sh.QW;
   const int nsplit = ((max_kv_len + KB - 1) / KB + KW - 1) / KW;
   const int NSP = (max_seq + KB - 1) / KB;
-  const dim3 grid(Hkv * sh.NQG, ngroups, nsplit);
+  const dim3 grid(Hkv * sh.NQG, ngroups, full ? 1 : nsplit);
   const bf16_t *q = (const bf16_t*)qbuf, *k = (const bf16_t*)kcache, *v = (const bf16_t*)vcache;
-#define SD_ATTN_LAUNCH(HD_, QTW_)                                                                              \
-  hipLaunchKernelGGL((attn_mfma_k<HD_, QTW_>), grid, dim3(256), 0, st, q, k, v, rows.seq, rows.pos, rows.gseq,   \
-                     rows.gend, scratch, RS,                                                                  \
-                     Hq, Hkv, max_seq, sh.QW, sh.NQG, NSP)
+#define SD_ATTN_LAUNCH(HD_, QTW_, FULL_)                                                                       \
+  hipLaunchKernelGGL((attn_mfma_k<HD_, QTW_, FULL_>), grid, dim3(256), 0, st, q, k, v, rows.seq, rows.pos,       \
+                     rows.gseq, rows.gend, scratch, (bf16_t*)out, RS, Hq, Hkv, max_seq, sh.QW, sh.NQG, NSP)
+  if (full) {
+    if (hd == 128) {
+      if (sh.QTW == 1) SD_ATTN_LAUNCH(128, 1, true); else SD_ATTN_LAUNCH(128, 2, true);
+    } else {
+      if (sh.QTW == 1) SD_ATTN_LAUNCH(64, 1, true); else SD_ATTN_LAUNCH(64, 2, true);
+    }
+    return hipGetLastError();
+  }
   if (hd == 128) {
-    if (sh.QTW == 1) SD_ATTN_LAUNCH(128, 1); else SD_ATTN_LAUNCH(128, 2);
+    if (sh.QTW == 1) SD_ATTN_LAUNCH(128, 1, false); else SD_ATTN_LAUNCH(128, 2, false);
   } else {
-    if (sh.QTW == 1) SD_ATTN_LAUNCH(64, 1); else SD_ATTN_LAUNCH(64, 2);
+    if (sh.QTW == 1) SD_ATTN_LAUNCH(64, 1, false); else SD_ATTN_LAUNCH(64, 2, false);
   }
 #undef SD_ATTN_LAUNCH
   hipError_t e = hipGetLastError();

@@ -228,7 +228,7 @@ __global__ __launch_bounds__(EW_THREADS) void head_act_k(const float* __restrict
   Elem<T>::st(z_out + (size_t)m * n + i, a);
 }
 
-inline bool bad_rows(int M) { return M < 1 || M > MAX_ROWS; }
+inline bool bad_rows(int M) { return M < 1 || M > MAX_PREFILL_ROWS; }
 
 }  // namespace
 

@@ -61,6 +61,7 @@ struct sd_ctx {
   ModelRt target, draft;
   HeadRt head;
   int B = 1, max_rows = 0;
+  int prefill_rows = 0;          // rows of one prompt-pass chunk of a bf16 model (tiled GEMM path)
 
   // activations (sized for the wider model)
   float* x = nullptr;
@@ -162,7 +163,7 @@ sd_status alloc_model(sd_ctx* c, ModelRt& rt) {
 
 size_t part_floats_for(int dtype, int max_rows, int N, int K) {
   size_t best = 0;
-  for (int M = 1; M <= max_rows; ++M) {
+  for (int M = 1; M <= std::min(max_rows, (int)MAX_ROWS); ++M) {
     const size_t v = (size_t)gemm_splits(dtype, M, N, K) * M * N;
     if (v > best) best = v;
   }
@@ -177,6 +178,9 @@ size_t part_floats(const sd_ctx* c) {
                               {2 * m.d_ffn, m.d_model},               {m.d_model, m.d_ffn},
                               {m.vocab, m.d_model}};
     for (auto& sh : shapes) best = std::max(best, part_floats_for(m.dtype, c->max_rows, sh[0], sh[1]));
+    // the prompt pass of a bf16 model writes whole [rows, N] products (no K slices)
+    if (m.dtype == SD_BF16)
+      for (int i = 0; i < 4; ++i) best = std::max(best, (size_t)c->prefill_rows * shapes[i][0]);
   }
   if (c->head.present)
     for (int j = 0; j + 1 < c->head.n_layers; ++j)
@@ -224,29 +228,40 @@ sd_status gemm(sd_ctx* c, const ModelRt& rt, const void* W, const void* X, int l
 // final-RMSNorm rows in c->xn.  If logits_out != null, runs the LM head over n_lm rows
 // (gathered through lm_rows when non-null); LM row i = (group i / lm_rs, slot i % lm_rs) goes
 // to logits_out[group * ld_group + slot * ld_row + v].
+// tile = true (prompt pass of a bf16 model, one row group): the four layer GEMMs go through
+// the large-M tiled kernel, which writes whole products (one "slice"), and attention
+// through its unsplit variant; M may then reach c->prefill_rows.
 sd_status forward(sd_ctx* c, ModelRt& rt, int M, int RS, int max_kv_len, const int* lm_rows, int n_lm,
-                  float* logits_out, int lm_rs, int64_t ld_group, int64_t ld_row, bool profile) {
+                  float* logits_out, int lm_rs, int64_t ld_group, int64_t ld_row, bool profile, bool tile = false) {
   const sd_model& m = rt.m;
   const int dt = m.dtype, d = m.d_model, nq = rt.n_q(), nkv = rt.n_kv();
   hipStream_t st = c->st;
+  if (tile && (dt != SD_BF16 || RS != M || logits_out)) return SD_EINVAL;
+  if (!tile && M > MAX_ROWS) return SD_EINVAL;
+  auto mm = [&](const void* W, const void* X, int ldx, int N, int K, int prof_kind) -> sd_status {
+    if (!tile) return gemm(c, rt, W, X, ldx, nullptr, M, N, K, prof_kind);
+    SD_HIP(launch_gemm_tile(st, W, X, ldx, nullptr, c->part, M, N, K));
+    return SD_OK;
+  };
+  auto slices = [&](int N, int K) { return tile ? 1 : gemm_splits(dt, M, N, K); };
   SD_HIP(launch_embed_norm(st, dt, m.tok_emb, rt.na[0], m.rms_eps, c->rows.tok, c->x, c->xn, c->ssq, M, d, m.vocab));
   for (int l = 0; l < m.n_layers; ++l) {
     const bool pr = profile && c->prof_every > 0 && (l % c->prof_every) == 0;
     sd_status s;
-    if ((s = gemm(c, rt, rt.wqkv[l], c->xn, d, nullptr, M, nq + 2 * nkv, d, pr ? 0 : -1)) != SD_OK) return s;
+    if ((s = mm(rt.wqkv[l], c->xn, d, nq + 2 * nkv, d, pr ? 0 : -1)) != SD_OK) return s;
     void* kc = rt.kcache + (size_t)l * rt.layer_bytes;
     void* vc = rt.vcache + (size_t)l * rt.layer_bytes;
-    SD_HIP(launch_rope_kv(st, dt, c->part, gemm_splits(dt, M, nq + 2 * nkv, d), c->rows, rt.cos_sin, c->qbuf, kc, vc,
+    SD_HIP(launch_rope_kv(st, dt, c->part, slices(nq + 2 * nkv, d), c->rows, rt.cos_sin, c->qbuf, kc, vc,
                           M, m.n_heads, m.n_kv_heads, m.head_dim, c->cfg.max_seq));
     SD_HIP(launch_attention(st, dt, c->qbuf, kc, vc, c->rows, c->attn, c->attn_scratch, M, RS, m.n_heads,
-                            m.n_kv_heads, m.head_dim, c->cfg.max_seq, max_kv_len));
-    if ((s = gemm(c, rt, rt.wo[l], c->attn, nq, nullptr, M, d, nq, pr ? 1 : -1)) != SD_OK) return s;
-    SD_HIP(launch_add_norm(st, dt, c->part, gemm_splits(dt, M, d, nq), rt.nm[l], m.rms_eps, c->x, c->xn, c->ssq, M, d));
-    if ((s = gemm(c, rt, rt.wgu[l], c->xn, d, nullptr, M, 2 * m.d_ffn, d, pr ? 2 : -1)) != SD_OK) return s;
-    SD_HIP(launch_silu_mul(st, dt, c->part, gemm_splits(dt, M, 2 * m.d_ffn, d), c->act, M, m.d_ffn));
-    if ((s = gemm(c, rt, rt.wdown[l], c->act, m.d_ffn, nullptr, M, d, m.d_ffn, pr ? 3 : -1)) != SD_OK) return s;
+                            m.n_kv_heads, m.head_dim, c->cfg.max_seq, max_kv_len, tile));
+    if ((s = mm(rt.wo[l], c->attn, nq, d, nq, pr ? 1 : -1)) != SD_OK) return s;
+    SD_HIP(launch_add_norm(st, dt, c->part, slices(d, nq), rt.nm[l], m.rms_eps, c->x, c->xn, c->ssq, M, d));
+    if ((s = mm(rt.wgu[l], c->xn, d, 2 * m.d_ffn, d, pr ? 2 : -1)) != SD_OK) return s;
+    SD_HIP(launch_silu_mul(st, dt, c->part, slices(2 * m.d_ffn, d), c->act, M, m.d_ffn));
+    if ((s = mm(rt.wdown[l], c->act, m.d_ffn, d, m.d_ffn, pr ? 3 : -1)) != SD_OK) return s;
     const void* g_next = (l + 1 < m.n_layers) ? rt.na[l + 1] : m.final_norm;
-    SD_HIP(launch_add_norm(st, dt, c->part, gemm_splits(dt, M, d, m.d_ffn), g_next, m.rms_eps, c->x, c->xn, c->ssq, M, d));
+    SD_HIP(launch_add_norm(st, dt, c->part, slices(d, m.d_ffn), g_next, m.rms_eps, c->x, c->xn, c->ssq, M, d));
   }
   if (logits_out) {
     sd_status s;
@@ -286,16 +301,16 @@ sd_status plan_host_rows(sd_ctx* c, int seq, int start, const int32_t* toks, int
   int32_t* h = c->pinned;
   for (int i = 0; i < n; ++i) {
     h[i] = seq;
-    h[MAX_ROWS + i] = start + i;
-    h[2 * MAX_ROWS + i] = toks[i];
+    h[MAX_PREFILL_ROWS + i] = start + i;
+    h[2 * MAX_PREFILL_ROWS + i] = toks[i];
   }
   SD_HIP(hipMemcpyAsync(c->rows.seq, h, n * sizeof(int32_t), hipMemcpyHostToDevice, c->st));
-  SD_HIP(hipMemcpyAsync(c->rows.pos, h + MAX_ROWS, n * sizeof(int32_t), hipMemcpyHostToDevice, c->st));
-  SD_HIP(hipMemcpyAsync(c->rows.tok, h + 2 * MAX_ROWS, n * sizeof(int32_t), hipMemcpyHostToDevice, c->st));
-  h[3 * MAX_ROWS] = seq;                 // one row group: the whole chunk
-  h[3 * MAX_ROWS + 1] = start + n;
-  SD_HIP(hipMemcpyAsync(c->rows.gseq, h + 3 * MAX_ROWS, sizeof(int32_t), hipMemcpyHostToDevice, c->st));
-  SD_HIP(hipMemcpyAsync(c->rows.gend, h + 3 * MAX_ROWS + 1, sizeof(int32_t), hipMemcpyHostToDevice, c->st));
+  SD_HIP(hipMemcpyAsync(c->rows.pos, h + MAX_PREFILL_ROWS, n * sizeof(int32_t), hipMemcpyHostToDevice, c->st));
+  SD_HIP(hipMemcpyAsync(c->rows.tok, h + 2 * MAX_PREFILL_ROWS, n * sizeof(int32_t), hipMemcpyHostToDevice, c->st));
+  h[3 * MAX_PREFILL_ROWS] = seq;                 // one row group: the whole chunk
+  h[3 * MAX_PREFILL_ROWS + 1] = start + n;
+  SD_HIP(hipMemcpyAsync(c->rows.gseq, h + 3 * MAX_PREFILL_ROWS, sizeof(int32_t), hipMemcpyHostToDevice, c->st));
+  SD_HIP(hipMemcpyAsync(c->rows.gend, h + 3 * MAX_PREFILL_ROWS + 1, sizeof(int32_t), hipMemcpyHostToDevice, c->st));
   return SD_OK;
 }
 
@@ -380,7 +395,9 @@ sd_status sd_create(sd_ctx** out, const sd_model* target, const sd_model* draft,
   c->cfg = *cfg;
   c->st = (hipStream_t)cfg->hip_stream;
   c->B = cfg->batch;
-  c->max_rows = std::max(PREFILL_CHUNK, std::max(c->B * (cfg->k_max + 1), 2 * c->B));
+  const bool any_bf16 = target->dtype == SD_BF16 || draft->dtype == SD_BF16;
+  c->prefill_rows = any_bf16 ? std::min((int)MAX_PREFILL_ROWS, cfg->max_seq) : PREFILL_CHUNK;
+  c->max_rows = std::max(std::max(PREFILL_CHUNK, c->prefill_rows), std::max(c->B * (cfg->k_max + 1), 2 * c->B));
   copy_model(c->target, target);
   copy_model(c->draft, draft);
   if (head) {
@@ -407,7 +424,7 @@ sd_status sd_create(sd_ctx** out, const sd_model* target, const sd_model* draft,
   size_t attn_fl = 16;
   for (const ModelRt* rt : {&c->target, &c->draft})
     if (rt->m.dtype == SD_BF16)
-      attn_fl = std::max(attn_fl, attn_scratch_floats(R, rt->m.n_heads, rt->m.head_dim, cfg->max_seq));
+      attn_fl = std::max(attn_fl, attn_scratch_floats(std::min(R, (int)MAX_ROWS), rt->m.n_heads, rt->m.head_dim, cfg->max_seq));
 
 #define SD_ALLOC(ptr, bytes, zero)                                              \
   if ((s = dev_alloc(c, (void**)&(ptr), (bytes), (zero))) != SD_OK) return fail(s)
@@ -420,16 +437,16 @@ sd_status sd_create(sd_ctx** out, const sd_model* target, const sd_model* draft,
   SD_ALLOC(c->hz[1], (size_t)B * hzmax * 4, true);
   SD_ALLOC(c->part, part_floats(c) * 4, false);
   SD_ALLOC(c->attn_scratch, attn_fl * 4, false);
-  SD_ALLOC(c->ssq, (size_t)MAX_ROWS * NORM_MAX_BLOCKS * 4, true);
+  SD_ALLOC(c->ssq, (size_t)MAX_PREFILL_ROWS * NORM_MAX_BLOCKS * 4, true);
   SD_ALLOC(c->q_logits, (size_t)B * cfg->k_max * V * 4, true);
   SD_ALLOC(c->p_logits, (size_t)B * (cfg->k_max + 1) * V * 4, true);
   SD_ALLOC(c->fw_logits, (size_t)PREFILL_CHUNK * V * 4, true);
   SD_ALLOC(c->stats, (size_t)B * (2 * cfg->k_max + 1) * 4 * 4, true);
-  SD_ALLOC(c->rows.seq, MAX_ROWS * 4, true);
-  SD_ALLOC(c->rows.pos, MAX_ROWS * 4, true);
-  SD_ALLOC(c->rows.tok, MAX_ROWS * 4, true);
-  SD_ALLOC(c->rows.gseq, MAX_ROWS * 4, true);
-  SD_ALLOC(c->rows.gend, MAX_ROWS * 4, true);
+  SD_ALLOC(c->rows.seq, MAX_PREFILL_ROWS * 4, true);
+  SD_ALLOC(c->rows.pos, MAX_PREFILL_ROWS * 4, true);
+  SD_ALLOC(c->rows.tok, MAX_PREFILL_ROWS * 4, true);
+  SD_ALLOC(c->rows.gseq, MAX_PREFILL_ROWS * 4, true);
+  SD_ALLOC(c->rows.gend, MAX_PREFILL_ROWS * 4, true);
   SD_ALLOC(c->s.P, B * 4, true);
   SD_ALLOC(c->s.kv_t, B * 4, true);
   SD_ALLOC(c->s.kv_d, B * 4, true);
@@ -449,7 +466,7 @@ sd_status sd_create(sd_ctx** out, const sd_model* target, const sd_model* draft,
   SD_ALLOC(c->s.active, B * 4, true);
   SD_ALLOC(c->result, (size_t)B * RESULT_INTS * 4, true);
 #undef SD_ALLOC
-  c->pinned_ints = std::max<size_t>(3 * MAX_ROWS + 2, (size_t)B * RESULT_INTS) + 64;
+  c->pinned_ints = std::max<size_t>(3 * MAX_PREFILL_ROWS + 2, (size_t)B * RESULT_INTS) + 64;
   if (hipHostMalloc((void**)&c->pinned, c->pinned_ints * 4, hipHostMallocDefault) != hipSuccess) return fail(SD_ENOMEM);
   for (auto& e : c->ev)
     if (hipEventCreate(&e) != hipSuccess) return fail(SD_EDEVICE);
@@ -472,10 +489,14 @@ sd_status sd_prefill(sd_ctx* c, int32_t seq, const int32_t* prompt, int32_t n) {
   SD_HIP(hipMemcpy(c->s.tokens + (size_t)seq * c->cfg.max_seq, prompt, n * sizeof(int32_t), hipMemcpyHostToDevice));
   sd_status s;
   for (ModelRt* rt : {&c->target, &c->draft}) {
-    for (int start = 0; start < n - 1; start += PREFILL_CHUNK) {
-      const int m = std::min(PREFILL_CHUNK, n - 1 - start);
+    // bf16 models take the prompt in chunks of up to prefill_rows rows through the tiled
+    // GEMM (bound by the matrix cores); fp32 (tiny) models in 32-row chunks
+    const bool tile = rt->m.dtype == SD_BF16;
+    const int chunk = tile ? c->prefill_rows : PREFILL_CHUNK;
+    for (int start = 0; start < n - 1; start += chunk) {
+      const int m = std::min(chunk, n - 1 - start);
       if ((s = plan_host_rows(c, seq, start, prompt + start, m)) != SD_OK) return s;
-      if ((s = forward(c, *rt, m, m, start + m, nullptr, 0, nullptr, 1, 0, 0, false)) != SD_OK) return s;
+      if ((s = forward(c, *rt, m, m, start + m, nullptr, 0, nullptr, 1, 0, 0, false, tile)) != SD_OK) return s;
       SD_HIP(hipStreamSynchronize(c->st));
     }
   }
@@ -759,6 +780,12 @@ sd_status sd_gemm_skinny(int32_t dtype, const void* W, const void* X, int32_t M,
   hipStream_t st = (hipStream_t)hip_stream;
   SD_HIP(launch_gemm(st, dtype, W, X, K, nullptr, (float*)ws, M, N, K));
   SD_HIP(launch_reduce_rows(st, (const float*)ws, gemm_splits(dtype, M, N, K), Y, M, 0, N, M, N));
+  return SD_OK;
+}
+
+sd_status sd_gemm_tile(const void* W, const void* X, int32_t M, int32_t N, int32_t K, float* Y, void* hip_stream) {
+  if (!W || !X || !Y) return SD_EINVAL;
+  SD_HIP(launch_gemm_tile((hipStream_t)hip_stream, W, X, K, nullptr, Y, M, N, K));
   return SD_OK;
 }
 

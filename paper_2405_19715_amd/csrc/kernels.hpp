@@ -8,7 +8,8 @@
 namespace sd {
 
 enum { DT_F32 = 0, DT_BF16 = 1 };
-constexpr int MAX_ROWS = 160;          // most activation rows one forward call carries
+constexpr int MAX_ROWS = 160;          // most activation rows a round's forward call carries (streaming GEMM)
+constexpr int MAX_PREFILL_ROWS = 1024; // most rows of one prompt-pass chunk (tiled GEMM, elementwise kernels)
 
 // ---------------------------------------------------------------- skinny GEMM
 // part[s, m, n] = sum over the s-th K-slice of X[m, :] * W[n, :]   (fp32)
@@ -20,6 +21,12 @@ int gemm_splits(int dtype, int M, int N, int K);
 hipError_t launch_gemm(hipStream_t st, int dtype, const void* W, const void* X, int ldx, const int* xrow,
                        float* part, int M, int N, int K);
 
+// ---------------------------------------------------------------- large-M GEMM (prompt pass)
+// C[m, n] = sum_k X[m, k] * W[n, k], bf16 in, fp32 out [M, N]; X rows optionally gathered
+// through xrow.  Any M >= 1; K % 32 == 0, N % 4 == 0, ldx % 8 == 0, 16-byte aligned pointers.
+hipError_t launch_gemm_tile(hipStream_t st, const void* W, const void* X, int ldx, const int* xrow, float* C,
+                            int M, int N, int K);
+
 // ---------------------------------------------------------------- row plans
 struct RowPlan {           // device arrays, one entry per activation row
   int32_t* seq;            // sequence of the row, -1 = padding row
@@ -30,7 +37,7 @@ struct RowPlan {           // device arrays, one entry per activation row
 };
 
 // ---------------------------------------------------------------- elementwise
-// `ssq` is scratch for per-block sums of squares: MAX_ROWS * NORM_MAX_BLOCKS floats.
+// `ssq` is scratch for per-block sums of squares: MAX_PREFILL_ROWS * NORM_MAX_BLOCKS floats.
 constexpr int NORM_MAX_BLOCKS = 64;    // d <= 65536
 // x[m,:] = E[tok[m],:]; xn[m,:] = rmsnorm(x[m,:]) * g
 hipError_t launch_embed_norm(hipStream_t st, int dtype, const void* emb, const void* g, float eps,
@@ -57,10 +64,13 @@ hipError_t launch_head_act(hipStream_t st, int dtype, const float* part, int S, 
 // Rows come in groups of RS consecutive rows that belong to one sequence (padding
 // rows have seq < 0).  `scratch` holds split partials: attn_scratch_floats(...) floats.
 // max_kv_len: upper bound on pos + 1 over all rows (sizes the grid).
+// full = true (prompt pass, bf16 only): every wavefront walks all the key blocks its query
+// tiles may see and writes finished outputs; no partials, `scratch` unused, M up to
+// MAX_PREFILL_ROWS.  Otherwise M <= MAX_ROWS.
 size_t attn_scratch_floats(int M, int Hq, int hd, int max_seq);
 hipError_t launch_attention(hipStream_t st, int dtype, const void* qbuf, const void* kcache,
                             const void* vcache, const RowPlan& rows, void* out, float* scratch, int M,
-                            int RS, int Hq, int Hkv, int hd, int max_seq, int max_kv_len);
+                            int RS, int Hq, int Hkv, int hd, int max_seq, int max_kv_len, bool full = false);
 
 // ---------------------------------------------------------------- sampling / accept
 struct SeqState {          // device arrays, one entry per sequence unless noted

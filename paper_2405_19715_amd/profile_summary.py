@@ -95,6 +95,7 @@ def main(argv=None):
     starts = [i for i, r in enumerate(rows) if "begin_round_k" in r[0]]
     if len(starts) <= args.skip_rounds:
         raise SystemExit("trace holds too few rounds")
+    first_round = starts[0]
     starts = starts[args.skip_rounds:]
     draft, verify = [], []
     n_rounds = 0
@@ -114,6 +115,9 @@ def main(argv=None):
     v_span = sum(v[-1][2] - v[0][1] for v in verify)
     out.write(f"draft steps: {d_steps}, mean draft-step span {d_span / max(d_steps, 1) / 1e6:.3f} ms; "
               f"mean target pass + accept span {v_span / n_rounds / 1e6:.3f} ms\n")
+    prompt = [r for r in rows[:first_round] if r[0].startswith("sd::")]
+    if prompt:
+        table([prompt], "prompt pass of both models (before the first round, warm-up call included)", out)
     table(draft, "draft loops (all summarised rounds)", out)
     table(verify, "target pass + accept + commit (all summarised rounds)", out)
 

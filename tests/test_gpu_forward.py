@@ -88,3 +88,30 @@ def test_bf16_long_context_many_key_splits():
         assert _row_err(got, want) < TOL[torch.bfloat16]
     finally:
         ctx.close()
+
+
+@pytest.mark.parametrize("shape,n,max_seq", [
+    (synth.ModelShape(2, 512, 8, 1, 64, 640, 2048), 2, 256),        # one prompt row
+    (synth.ModelShape(2, 512, 8, 1, 64, 640, 2048), 38, 256),       # less than one tile
+    (synth.ModelShape(2, 256, 2, 2, 128, 384, 2048), 201, 256),     # MHA, head_dim 128, ragged tiles
+    (synth.ModelShape(2, 1024, 8, 1, 128, 1280, 2048), 230, 256),   # 8:1 grouped queries, head_dim 128
+    (synth.ModelShape(1, 256, 4, 2, 64, 256, 512), 1101, 1152),     # two prompt chunks (1024 + 76 rows)
+])
+def test_bf16_prompt_pass_matches_oracle(shape, n, max_seq):
+    """The prompt pass (tiled large-M GEMM + unsplit causal attention) fills the KV cache
+    with what the oracle's forward computes: the rows that follow, teacher-forced against
+    that cache, must give the oracle's logits and final hidden states."""
+    from paper_2405_19715_amd import binding as B
+    m = synth.make_model(shape, 5, dtype=torch.bfloat16, std=0.04)
+    tail = 6
+    toks = synth.make_prompt(n + tail, shape.vocab, 6)
+    want_logits, want_hid = forward_full(oracle_model(m), toks)
+    mc = _cuda(m)
+    ctx = B.Context(mc, mc, None, batch=1, max_seq=max_seq, k_max=8)
+    try:
+        ctx.sd_prefill(0, toks[:n])                 # caches now hold positions 0 .. n-2
+        l, h = ctx.sd_forward(0, 0, n - 1, toks[n - 1:], want_hidden=True)
+        assert _row_err(l.numpy(), want_logits[n - 1:]) < TOL[torch.bfloat16]
+        assert _row_err(h.numpy(), want_hid[n - 1:]) < TOL[torch.bfloat16]
+    finally:
+        ctx.close()

@@ -45,3 +45,33 @@ def test_rejects_shapes_the_kernel_cannot_take():
     ws = torch.zeros(1 << 16, dtype=torch.uint8, device="cuda")
     with pytest.raises(B.SpecDecError):
         B.sd_gemm_skinny(W, X, out=(Y, ws))
+
+
+def _check_tile(M, N, K, seed, tol=3e-5):
+    from paper_2405_19715_amd import binding as B
+    g = torch.Generator().manual_seed(seed)
+    W = (torch.randn((N, K), generator=g) * 0.05).to(torch.bfloat16)
+    X = torch.randn((M, K), generator=g).to(torch.bfloat16)
+    want = X.double().numpy() @ W.double().numpy().T            # the definition, in fp64
+    Y = torch.full((M, N), float("nan"), dtype=torch.float32, device="cuda")
+    got = B.sd_gemm_tile(W.cuda(), X.cuda(), out=Y).cpu().double().numpy()
+    assert np.isfinite(got).all(), (M, N, K)                    # every element of Y was written
+    err = np.abs(got - want).max() / np.abs(want).max()
+    assert err < tol, (M, N, K, err)
+
+
+@pytest.mark.parametrize("shape", [
+    (1, 64, 32), (64, 128, 32), (128, 256, 64), (130, 640, 512), (257, 1284, 96), (63, 36, 160),
+    (512, 2048, 1024), (1024, 1280, 512), (300, 4096, 4096), (1023, 2560, 2048)])
+def test_tile_gemm_matches_fp64_matmul(shape):
+    """The prompt-pass GEMM: all three tile shapes, ragged M and N tails, one and many
+    k steps, grids that do not fill the last group of 8 weight tiles."""
+    _check_tile(*shape, seed=sum(shape))
+
+
+def test_tile_gemm_rejects_bad_shapes():
+    from paper_2405_19715_amd import binding as B
+    W = torch.zeros((16, 48), dtype=torch.bfloat16, device="cuda")       # K not a multiple of 32
+    X = torch.zeros((4, 48), dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(B.SpecDecError):
+        B.sd_gemm_tile(W, X)
