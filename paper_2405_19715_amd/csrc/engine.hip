@@ -491,10 +491,11 @@ sd_status sd_prefill(sd_ctx* c, int32_t seq, const int32_t* prompt, int32_t n) {
   for (ModelRt* rt : {&c->target, &c->draft}) {
     // bf16 models take the prompt in chunks of up to prefill_rows rows through the tiled
     // GEMM (bound by the matrix cores); fp32 (tiny) models in 32-row chunks
-    const bool tile = rt->m.dtype == SD_BF16;
-    const int chunk = tile ? c->prefill_rows : PREFILL_CHUNK;
+    const bool bf16 = rt->m.dtype == SD_BF16;
+    const int chunk = bf16 ? c->prefill_rows : PREFILL_CHUNK;
     for (int start = 0; start < n - 1; start += chunk) {
       const int m = std::min(chunk, n - 1 - start);
+      const bool tile = bf16 && m > PREFILL_CHUNK;     // a short chunk is weight-bound: streaming kernel
       if ((s = plan_host_rows(c, seq, start, prompt + start, m)) != SD_OK) return s;
       if ((s = forward(c, *rt, m, m, start + m, nullptr, 0, nullptr, 1, 0, 0, false, tile)) != SD_OK) return s;
       SD_HIP(hipStreamSynchronize(c->st));

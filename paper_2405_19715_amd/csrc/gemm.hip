@@ -42,7 +42,7 @@ namespace {
 constexpr int GEMM_WAVES = 8;            // wavefronts per workgroup, all sharing one staged X slice
 constexpr int GEMM_THREADS = 64 * GEMM_WAVES;
 constexpr int KSTEP = 128;
-constexpr int LDS_MAX = 72 * 1024;       // X slice per workgroup: two workgroups fit a CU's 160 KB
+constexpr int LDS_MAX = 144 * 1024;      // largest X slice per workgroup (one workgroup per CU, 160 KB of LDS)
 constexpr int PREFETCH = 4;              // steps of weight loads in flight per wave
 
 struct Split { int S, steps_per, G; };
@@ -67,7 +67,7 @@ Split plan_bf16(int M, int N, int K) {
   for (int sp = max_steps; sp >= 1; --sp) {
     const int S = (total + sp - 1) / sp;
     const size_t lds = (size_t)M * sp * KSTEP * 2;
-    const int resident = 1;                // one workgroup per CU measured best   // MFMA path: one workgroup per CU measured best
+    const int resident = 1;                // one workgroup per CU measured best
     int g_hi = (256 * resident) / S;
     if (g_hi > g_max) g_hi = g_max;
     if (g_hi < 1) {
