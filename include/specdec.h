@@ -203,6 +203,49 @@ sd_status sd_profile_read(sd_ctx *ctx, int64_t *launches, double *seconds, doubl
 sd_status sd_gemm_skinny(int32_t dtype, const void *W_dev, const void *X_dev, int32_t M, int32_t N, int32_t K,
                          float *Y_dev, void *ws_dev, void *hip_stream);
 
+/* ---- Training of the acceptance-prediction head (Sec. 4.4) ---------------------------
+ *
+ * sd_head_examples builds the training examples of one (prompt, response) pair with the
+ * context's two models: `tokens` (HOST) holds n_prompt prompt tokens followed by the N
+ * tokens X_1..X_N of a target response (e.g. the output of specdec_generate, which is
+ * distributed as the target's own samples).  Teacher-forced on X it computes, for every i,
+ * Y_i ~ q_i (uniform of (slot i, example, sequence 0, stream 3)) and the target
+ * P_i = min(1, p_i(Y_i)/q_i(Y_i)) under `temperature` / `top_k`; mixes tokens
+ * (Z_i = X_i when the uniform of (slot i, example, 0, stream 4) < r, else Y_i; mask_i = 1
+ * where Z_i = Y_i: the tokens that carry a loss); and runs the draft over (prompt, Z) to get
+ * E_i, its final (post-RMSNorm) embedding of Z_i.
+ * E_dev: DEVICE fp32 [N, d_draft]; P_dev: DEVICE fp32 [N]; mask_dev: DEVICE int32 [N];
+ * Y_host, Z_host: HOST int32 [N], may be null.  Needs n_prompt + N + 2 <= max_seq.
+ * Uses sequence slot `seq` and leaves it inactive: sd_prefill it again before decoding.
+ * Synchronises the stream. */
+sd_status sd_head_examples(sd_ctx *ctx, int32_t seq, const int32_t *tokens_host, int32_t n_prompt, int32_t N, float r,
+                           uint64_t seed, int32_t example, float temperature, int32_t top_k, float *E_dev,
+                           float *P_dev, int32_t *mask_dev, int32_t *Y_host, int32_t *Z_host);
+
+/* A trainer owns fp32 copies of a head's weights (initialised from `init`, whose arrays are
+ * DEVICE memory in init->dtype), their gradients and Adam moments, and activation buffers
+ * for batches of up to n_max <= 4096 rows.  Work is enqueued on `hip_stream`. */
+typedef struct sd_trainer sd_trainer;
+sd_status sd_trainer_create(sd_trainer **out, const sd_head *init, int32_t n_max, void *hip_stream);
+sd_status sd_trainer_destroy(sd_trainer *tr);
+
+/* One step on a batch of n examples (E: DEVICE fp32 [n, dims[0]], P: DEVICE fp32 [n], mask:
+ * DEVICE int32 [n]): forward, the weighted BCE of Sec. 4.4 averaged over the n_m masked rows
+ *   (1/n_m) sum_{mask} -w_acc P log P_hat - w_rej (1 - P) log(1 - P_hat),   P_hat = sigmoid(f(E)),
+ * its gradient for every W_j, b_j, and, when apply != 0, one Adam update (bias-corrected, no
+ * weight decay) with the given lr / beta1 / beta2 / eps.  loss_host (HOST, may be null)
+ * receives the loss before the update; passing it synchronises the stream. */
+sd_status sd_trainer_step(sd_trainer *tr, const float *E_dev, const float *P_dev, const int32_t *mask_dev, int32_t n,
+                          float w_acc, float w_rej, float lr, float beta1, float beta2, float eps, int32_t apply,
+                          float *loss_host);
+/* logits_dev[i] = f_theta(E_i) with the current weights (DEVICE fp32 [n]). */
+sd_status sd_trainer_predict(sd_trainer *tr, const float *E_dev, int32_t n, float *logits_dev);
+/* Copy layer `layer`'s W (what = 0), b (1), last gradient of W (2) or of b (3) to HOST fp32. */
+sd_status sd_trainer_read(sd_trainer *tr, int32_t layer, int32_t what, float *host);
+/* Write the current weights, converted to `dtype`, into caller-owned DEVICE arrays laid out
+ * like sd_head.W / sd_head.b (so that a head for sd_create can be built from them). */
+sd_status sd_trainer_export(sd_trainer *tr, int32_t dtype, void *const *W_out_dev, void *const *b_out_dev);
+
 /* The large-M GEMM of the prompt pass (both models ingest the prefix before the first
  * round of Algorithm 2; with hundreds of rows per weight this is bound by the matrix
  * cores, not by the weight stream): Y[m, n] = sum_k X[m, k] * W[n, k], bf16 in, fp32 out.

@@ -78,6 +78,15 @@ _PROTOS = {
     "sd_profile_read": (C.c_int32, [C.c_void_p, C.POINTER(C.c_int64), C.POINTER(C.c_double), C.POINTER(C.c_double)]),
     "sd_gemm_skinny": (C.c_int32, [C.c_int32, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p,
                                    C.c_void_p, C.c_void_p]),
+    "sd_head_examples": (C.c_int32, [C.c_void_p, C.c_int32, _i32p, C.c_int32, C.c_int32, C.c_float, C.c_uint64, C.c_int32,
+                                     C.c_float, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, _i32p, _i32p]),
+    "sd_trainer_create": (C.c_int32, [C.POINTER(C.c_void_p), C.POINTER(sd_head), C.c_int32, C.c_void_p]),
+    "sd_trainer_destroy": (C.c_int32, [C.c_void_p]),
+    "sd_trainer_step": (C.c_int32, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_float, C.c_float,
+                                    C.c_float, C.c_float, C.c_float, C.c_float, C.c_int32, _f32p]),
+    "sd_trainer_predict": (C.c_int32, [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p]),
+    "sd_trainer_read": (C.c_int32, [C.c_void_p, C.c_int32, C.c_int32, _f32p]),
+    "sd_trainer_export": (C.c_int32, [C.c_void_p, C.c_int32, _vpp, _vpp]),
     "sd_gemm_tile": (C.c_int32, [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]),
     "sd_gemm_workspace_bytes": (C.c_int64, [C.c_int32, C.c_int32, C.c_int32, C.c_int32]),
     "sd_strerror": (C.c_char_p, [C.c_int32]),
@@ -214,6 +223,21 @@ class Context:
                                       C.cast(s.data_ptr(), _f32p)), "sd_last_round_rows")
         return q, p, s[: K - 1]
 
+    def sd_head_examples(self, seq: int, prompt: Sequence[int], response: Sequence[int], r: float, seed: int,
+                         example: int, temperature: float = 1.0, top_k: int = 0):
+        """(E [N, d] fp32, P [N] fp32, mask [N] int32) on the device, and Y, Z as lists."""
+        toks = list(prompt) + list(response)
+        N = len(response)
+        arr = (C.c_int32 * len(toks))(*toks)
+        dev = torch.device("cuda", torch.cuda.current_device())
+        E = torch.empty((N, self.d_model[1]), dtype=torch.float32, device=dev)
+        P = torch.empty((N,), dtype=torch.float32, device=dev)
+        mask = torch.empty((N,), dtype=torch.int32, device=dev)
+        Y, Z = (C.c_int32 * N)(), (C.c_int32 * N)()
+        _check(lib.sd_head_examples(self.handle, seq, arr, len(prompt), N, r, seed, example, temperature, top_k,
+                                    E.data_ptr(), P.data_ptr(), mask.data_ptr(), Y, Z), "sd_head_examples")
+        return E, P, mask, list(Y), list(Z)
+
     def sd_profile_enable(self, every: int) -> None:
         _check(lib.sd_profile_enable(self.handle, every), "sd_profile_enable")
 
@@ -276,3 +300,60 @@ def sd_gemm_tile(W: torch.Tensor, X: torch.Tensor, out: Optional[torch.Tensor] =
     Y = out if out is not None else torch.empty((M, N), dtype=torch.float32, device=W.device)
     _check(lib.sd_gemm_tile(W.data_ptr(), X.data_ptr(), M, N, K, Y.data_ptr(), _stream_ptr()), "sd_gemm_tile")
     return Y
+
+
+def _head_struct(head: Dict, keep: list) -> sd_head:
+    dims = (C.c_int32 * len(head["dims"]))(*head["dims"])
+    W, b = _ptr_array(head["W"]), _ptr_array(head["b"])
+    keep += [dims, W, b]
+    return sd_head(len(head["W"]), C.cast(dims, _i32p), int(head["residual"]), _dtype_code(head["dtype"]),
+                   C.cast(W, _vpp), C.cast(b, _vpp))
+
+
+class Trainer:
+    """Owns an sd_trainer initialised from a head dict of `synth.make_head` (CUDA tensors)."""
+
+    def __init__(self, head: Dict, n_max: int):
+        self._keep = [head]
+        hs = _head_struct(head, self._keep)
+        self.handle = C.c_void_p()
+        self.dims, self.residual = list(head["dims"]), bool(head["residual"])
+        _check(lib.sd_trainer_create(C.byref(self.handle), C.byref(hs), n_max, _stream_ptr()), "sd_trainer_create")
+
+    def close(self):
+        if self.handle:
+            lib.sd_trainer_destroy(self.handle)
+            self.handle = C.c_void_p()
+
+    def sd_trainer_step(self, E: torch.Tensor, P: torch.Tensor, mask: torch.Tensor, w_acc=1.0, w_rej=1.0, lr=5e-5,
+                        beta1=0.9, beta2=0.999, eps=1e-8, apply=True, want_loss=True) -> Optional[float]:
+        assert E.is_cuda and E.dtype == torch.float32 and E.is_contiguous() and E.shape[1] == self.dims[0]
+        assert P.is_cuda and P.dtype == torch.float32 and mask.is_cuda and mask.dtype == torch.int32
+        n = E.shape[0]
+        assert P.numel() == n and mask.numel() == n
+        loss = C.c_float()
+        _check(lib.sd_trainer_step(self.handle, E.data_ptr(), P.data_ptr(), mask.data_ptr(), n, w_acc, w_rej, lr, beta1,
+                                   beta2, eps, int(bool(apply)), C.byref(loss) if want_loss else None),
+               "sd_trainer_step")
+        return loss.value if want_loss else None
+
+    def sd_trainer_predict(self, E: torch.Tensor) -> torch.Tensor:
+        out = torch.empty(E.shape[0], dtype=torch.float32, device=E.device)
+        _check(lib.sd_trainer_predict(self.handle, E.data_ptr(), E.shape[0], out.data_ptr()), "sd_trainer_predict")
+        return out
+
+    def sd_trainer_read(self, layer: int, what: int) -> torch.Tensor:
+        shape = (self.dims[layer + 1], self.dims[layer]) if what in (0, 2) else (self.dims[layer + 1],)
+        out = torch.empty(shape, dtype=torch.float32)
+        _check(lib.sd_trainer_read(self.handle, layer, what, C.cast(out.data_ptr(), _f32p)), "sd_trainer_read")
+        return out
+
+    def sd_trainer_export(self, dtype: torch.dtype, device="cuda") -> Dict:
+        """A head dict (like synth.make_head's) holding the current weights in `dtype`."""
+        L = len(self.dims) - 1
+        W = [torch.empty((self.dims[j + 1], self.dims[j]), dtype=dtype, device=device) for j in range(L)]
+        b = [torch.empty((self.dims[j + 1],), dtype=dtype, device=device) for j in range(L)]
+        Wp, bp = _ptr_array(W), _ptr_array(b)
+        _check(lib.sd_trainer_export(self.handle, _dtype_code(dtype), C.cast(Wp, _vpp), C.cast(bp, _vpp)),
+               "sd_trainer_export")
+        return dict(dims=list(self.dims), W=W, b=b, residual=self.residual, dtype=dtype)

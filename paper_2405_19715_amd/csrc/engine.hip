@@ -68,6 +68,8 @@ struct sd_ctx {
   void *xn = nullptr, *qbuf = nullptr, *attn = nullptr, *act = nullptr, *hz[2] = {nullptr, nullptr};
   float *part = nullptr, *attn_scratch = nullptr, *ssq = nullptr;
   float *q_logits = nullptr, *p_logits = nullptr, *fw_logits = nullptr, *stats = nullptr;
+  float* fw_logits2 = nullptr;     // second [32, V] logits buffer, allocated by the first sd_head_examples call
+  int32_t* ex_ints = nullptr;      // X, Y, Z, mask staging of sd_head_examples: 4 * max_seq ints
   RowPlan rows{};
   SeqState s{};
   int32_t* result = nullptr;       // device, [B, RESULT_INTS]
@@ -723,6 +725,61 @@ sd_status sd_forward(sd_ctx* c, int32_t which, int32_t seq, int32_t start, const
   }
   kv[seq] = start + n;
   return set_dev_int(c, which == 0 ? c->s.kv_t : c->s.kv_d, seq, start + n);
+}
+
+// Training examples of the acceptance head for one (prompt, response) pair (Sec. 4.4).
+sd_status sd_head_examples(sd_ctx* c, int32_t seq, const int32_t* tokens, int32_t n_prompt, int32_t N, float r,
+                           uint64_t seed, int32_t example, float temperature, int32_t top_k, float* E_dev,
+                           float* P_dev, int32_t* mask_dev, int32_t* Y_host, int32_t* Z_host) {
+  if (!c || !tokens || !E_dev || !P_dev || !mask_dev || seq < 0 || seq >= c->B || n_prompt < 1 || N < 1 ||
+      !(r >= 0.f && r <= 1.f) || !(temperature > 0.f) || top_k < 0)
+    return SD_EINVAL;
+  if (n_prompt + N + 2 > c->cfg.max_seq) return SD_ERANGE;
+  const int V = c->target.m.vocab, d = c->draft.m.d_model, ms = c->cfg.max_seq;
+  if (c->draft.m.vocab != V) return SD_EINVAL;
+  for (int i = 0; i < n_prompt + N; ++i)
+    if (tokens[i] < 0 || tokens[i] >= V) return SD_ERANGE;
+  sd_status s;
+  if (!c->fw_logits2 && (s = dev_alloc(c, (void**)&c->fw_logits2, (size_t)PREFILL_CHUNK * V * 4, true)) != SD_OK) return s;
+  if (!c->ex_ints && (s = dev_alloc(c, (void**)&c->ex_ints, (size_t)4 * ms * 4, true)) != SD_OK) return s;
+  int32_t *Xd = c->ex_ints, *Yd = Xd + ms, *Zd = Yd + ms;
+  hipStream_t st = c->st;
+  // both caches take the prompt (positions 0 .. n_prompt - 2)
+  if ((s = sd_prefill(c, seq, tokens, n_prompt)) != SD_OK) return s;
+  SD_HIP(hipMemcpyAsync(Xd, tokens + n_prompt, (size_t)N * 4, hipMemcpyHostToDevice, st));
+  // pass 1, teacher-forced on the response X: row of position n_prompt - 1 + j predicts X_{j+1}
+  for (int j0 = 0; j0 < N; j0 += PREFILL_CHUNK) {
+    const int m = std::min(PREFILL_CHUNK, N - j0), start = n_prompt - 1 + j0;
+    SD_HIP(hipStreamSynchronize(st));                  // the pinned row plan is reused
+    if ((s = plan_host_rows(c, seq, start, tokens + start, m)) != SD_OK) return s;
+    if ((s = forward(c, c->target, m, m, start + m, nullptr, m, c->fw_logits, m, 0, V, false)) != SD_OK) return s;
+    if ((s = forward(c, c->draft, m, m, start + m, nullptr, m, c->fw_logits2, m, 0, V, false)) != SD_OK) return s;
+    SD_HIP(launch_labels(st, c->fw_logits, c->fw_logits2, m, V, temperature, top_k, seed, j0 + 1, example, Yd + j0,
+                         P_dev + j0));
+  }
+  SD_HIP(launch_mix(st, Xd, Yd, N, r, seed, example, Zd, mask_dev));
+  std::vector<int32_t> z(N + 1);
+  z[0] = tokens[n_prompt - 1];
+  SD_HIP(hipStreamSynchronize(st));
+  SD_HIP(hipMemcpy(z.data() + 1, Zd, (size_t)N * 4, hipMemcpyDeviceToHost));
+  if (Y_host) SD_HIP(hipMemcpy(Y_host, Yd, (size_t)N * 4, hipMemcpyDeviceToHost));
+  if (Z_host) memcpy(Z_host, z.data() + 1, (size_t)N * 4);
+  // pass 2, draft only, on the mixed sequence: the row whose input token is Z_i gives E_i
+  for (int j0 = 0; j0 < N + 1; j0 += PREFILL_CHUNK) {
+    const int m = std::min(PREFILL_CHUNK, N + 1 - j0), start = n_prompt - 1 + j0;
+    SD_HIP(hipStreamSynchronize(st));
+    if ((s = plan_host_rows(c, seq, start, z.data() + j0, m)) != SD_OK) return s;
+    if ((s = forward(c, c->draft, m, m, start + m, nullptr, 0, nullptr, 1, 0, 0, false)) != SD_OK) return s;
+    // rows of this chunk are Z_{j0} .. (row 0 of the first chunk is the last prompt token: skipped)
+    const int skip = j0 == 0 ? 1 : 0;
+    if (m - skip > 0)
+      SD_HIP(launch_to_f32(st, c->draft.m.dtype, (const char*)c->xn + (size_t)skip * d * c->draft.esz,
+                           E_dev + (size_t)(j0 - 1 + skip) * d, (size_t)(m - skip) * d));
+  }
+  SD_HIP(hipStreamSynchronize(st));
+  // the caches now hold a training sequence: the slot must be prefilled again before it decodes
+  c->active[seq] = 0;
+  return set_dev_int(c, c->s.active, seq, 0);
 }
 
 sd_status sd_seq_state(sd_ctx* c, int32_t seq, int32_t* P, int32_t* kv_t, int32_t* kv_d, int32_t* round_idx) {

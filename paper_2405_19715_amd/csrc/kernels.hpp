@@ -117,9 +117,19 @@ hipError_t launch_accept(hipStream_t st, const float* p_logits, const float* q_l
                          const float* q_stats, const int32_t* cand, int cand_ld, const int32_t* K,
                          const int32_t* round, int round_const, const DecodeParams& p, int B, int Kmax,
                          int V, int32_t* n_out, int32_t* tok_out, uint8_t* flags, int flags_ld);
+// training targets of the acceptance head (Sec. 4.4): for row i of p / q [n, V], Y_i ~ q_i with the
+// uniform of (slot0 + i, example, 0, stream 3) and P_i = min(1, p_i(Y_i) / q_i(Y_i))
+hipError_t launch_labels(hipStream_t st, const float* p_logits, const float* q_logits, int n, int V,
+                         float temperature, int top_k, uint64_t seed, int slot0, int example, int32_t* Y, float* P);
+// token mixing: Z_i = X_i when u(i + 1, example, 0, stream 4) < r, else Y_i (mask_i = 1)
+hipError_t launch_mix(hipStream_t st, const int32_t* X, const int32_t* Y, int n, float r, uint64_t seed,
+                      int example, int32_t* Z, int32_t* mask);
 // append y_1..y_n, y' to the token history and roll both cache lengths back
 // and pack {K, n, y', p_hat, cand[32], P, kv_t, kv_d, err} (40 ints per sequence) for the host
 hipError_t launch_commit(hipStream_t st, const SeqState& s, int32_t* result, int B, int max_seq);
 constexpr int RESULT_INTS = 40;
+
+// y[i] = (float) x[i] for n elements of `dtype`
+hipError_t launch_to_f32(hipStream_t st, int dtype, const void* x, float* y, size_t n);
 
 }  // namespace sd

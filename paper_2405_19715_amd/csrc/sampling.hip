@@ -288,6 +288,63 @@ __global__ __launch_bounds__(SB) void row_stats_k(const float* __restrict__ logi
   }
 }
 
+// ------------------------------------------------------------------ training targets (Sec. 4.4)
+// Row i (0-based) of p / q [n, V]: Y ~ q_row with the uniform of (slot0 + i, example,
+// sequence 0, stream 3); P = min(1, p_row(Y) / q_row(Y)).  Same warping as the round.
+__global__ __launch_bounds__(SB) void label_k(const float* __restrict__ p_logits, const float* __restrict__ q_logits,
+                                              int V, float inv_t, int top_k, uint64_t seed, int slot0, int example,
+                                              int32_t* __restrict__ Y, float* __restrict__ P) {
+  __shared__ float sh_incl[SB];
+  __shared__ float sh_w[SB / 64];
+  __shared__ int sh_i[SB / 64];
+  __shared__ int sh_res;
+  const int i = blockIdx.x;
+  const float* lq = q_logits + (size_t)i * V;
+  const float* lp = p_logits + (size_t)i * V;
+  const bool warp = top_k > 0 && top_k < V;
+  // draft row: max, threshold, sample
+  ArgMax am{-INFINITY, 0x7fffffff};
+  for (int v = threadIdx.x; v < V; v += SB) am = better(am, ArgMax{lq[v], v});
+  am = block_argmax(am, sh_w, sh_i);
+  const float qmx = am.v;
+  const float qthr = warp ? block_kth_largest(lq, V, top_k, sh_i) : -INFINITY;
+  const float u = philox_uniform(seed, (uint32_t)(slot0 + i), (uint32_t)example, 0u, 3u);
+  const int y = block_sample([&](int v) { return lq[v] >= qthr ? expf((lq[v] - qmx) * inv_t) : 0.f; }, V, u, sh_incl,
+                             sh_w, &sh_res);
+  __syncthreads();
+  const int C = (V + SB - 1) / SB;
+  const int v0 = min((int)threadIdx.x * C, V), v1 = min(v0 + C, V);
+  float local = 0.f;
+  for (int v = v0; v < v1; ++v) local += lq[v] >= qthr ? expf((lq[v] - qmx) * inv_t) : 0.f;
+  const float qsum = block_sum(local, sh_w);
+  // target row: max, threshold, sum
+  ArgMax pm{-INFINITY, 0x7fffffff};
+  for (int v = threadIdx.x; v < V; v += SB) pm = better(pm, ArgMax{lp[v], v});
+  pm = block_argmax(pm, sh_w, sh_i);
+  const float pthr = warp ? block_kth_largest(lp, V, top_k, sh_i) : -INFINITY;
+  local = 0.f;
+  for (int v = v0; v < v1; ++v) local += lp[v] >= pthr ? expf((lp[v] - pm.v) * inv_t) : 0.f;
+  const float psum = block_sum(local, sh_w);
+  if (threadIdx.x == 0) {
+    const int yy = y < 0 ? am.i : y;
+    const float qy = expf((lq[yy] - qmx) * inv_t) / qsum;
+    const float py = lp[yy] >= pthr ? expf((lp[yy] - pm.v) * inv_t) / psum : 0.f;
+    Y[i] = yy;
+    P[i] = fminf(1.0f, py / qy);
+  }
+}
+
+// Token mixing: Z_i = X_i when u(slot i + 1, example, 0, stream 4) < r, else Y_i; mask_i = 1 where Z_i = Y_i.
+__global__ void mix_k(const int32_t* __restrict__ X, const int32_t* __restrict__ Y, int n, float r, uint64_t seed,
+                      int example, int32_t* __restrict__ Z, int32_t* __restrict__ mask) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n) return;
+  const float u = philox_uniform(seed, (uint32_t)(i + 1), (uint32_t)example, 0u, 4u);
+  const bool keep = u < r;
+  Z[i] = keep ? X[i] : Y[i];
+  mask[i] = keep ? 0 : 1;
+}
+
 // ------------------------------------------------------------------ accept + resample
 __global__ __launch_bounds__(SB) void accept_k(const float* __restrict__ p_logits, const float* __restrict__ q_logits,
                                                const float* __restrict__ p_stats, const float* __restrict__ q_stats,
@@ -444,6 +501,22 @@ hipError_t launch_row_stats(hipStream_t st, const float* logits, int rows_per_se
     return hipErrorInvalidValue;
   hipLaunchKernelGGL(row_stats_k, dim3(rows_per_seq, B), dim3(SB), 0, st, logits, rows_per_seq, extra, K, V,
                      1.0f / temperature, top_k, stats, err);
+  return hipGetLastError();
+}
+
+hipError_t launch_labels(hipStream_t st, const float* p_logits, const float* q_logits, int n, int V, float temperature,
+                         int top_k, uint64_t seed, int slot0, int example, int32_t* Y, float* P) {
+  if (n < 1 || V < 1 || top_k < 0 || !(temperature > 0.f) || !p_logits || !q_logits || !Y || !P)
+    return hipErrorInvalidValue;
+  hipLaunchKernelGGL(label_k, dim3(n), dim3(SB), 0, st, p_logits, q_logits, V, 1.0f / temperature, top_k, seed, slot0,
+                     example, Y, P);
+  return hipGetLastError();
+}
+
+hipError_t launch_mix(hipStream_t st, const int32_t* X, const int32_t* Y, int n, float r, uint64_t seed, int example,
+                      int32_t* Z, int32_t* mask) {
+  if (n < 1 || !X || !Y || !Z || !mask || !(r >= 0.f && r <= 1.f)) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(mix_k, dim3((n + 255) / 256), dim3(256), 0, st, X, Y, n, r, seed, example, Z, mask);
   return hipGetLastError();
 }
 
