@@ -122,6 +122,77 @@ def _cpu_baseline(tgt, drf, k_mean, n_mean, P, k_max):
                 t_target_s=t_target, t_draft_s=t_draft)
 
 
+def _train_head(args, tgt, drf, head, shape, n_gen):
+    """Sec. 4.4 on synthetic prompts: responses come from the pair itself (the output of
+    speculative decoding is distributed as the target's own samples), examples from
+    sd_head_examples (token mixing r = 15 %), then Adam on the weighted BCE (w_rej from
+    --w-rej, batch of 512 tokens, cosine schedule from --lr), a held-out tenth for the
+    reported loss.  Returns (head dict in bf16, info)."""
+    import math
+    import torch
+    from paper_2405_19715_amd import binding as B
+    from paper_2405_19715_amd import synth
+    n_prompt, n_resp = 128, n_gen
+    ctx = B.Context(tgt, drf, head, batch=1, max_seq=n_prompt + n_resp + 64, k_max=8)
+    Es, Ps, Ms = [], [], []
+    t0 = time.perf_counter()
+    for ex in range(args.train_head):
+        prompt = synth.make_prompt(n_prompt, shape.vocab, 1000 + ex)
+        ctx.sd_prefill(0, prompt)
+        resp, _ = ctx.specdec_generate(B.make_params(h=1.0, seed=args.seed + ex, top_k=args.top_k), n_resp)
+        E, P, mask, _, _ = ctx.sd_head_examples(0, prompt, resp[0], r=0.15, seed=args.seed, example=ex,
+                                                top_k=args.top_k)
+        Es.append(E); Ps.append(P); Ms.append(mask)
+    ctx.close()
+    t_data = time.perf_counter() - t0
+    E, P, M = torch.cat(Es), torch.cat(Ps), torch.cat(Ms)
+    n_all = E.shape[0]
+    n_val = max(n_all // 10, 1)
+    Ev, Pv, Mv = E[-n_val:], P[-n_val:], M[-n_val:]
+    E, P, M = E[:-n_val], P[:-n_val], M[:-n_val]
+    bs, epochs = 512, args.train_epochs
+    tr = B.Trainer(head, n_max=bs)
+    steps = epochs * ((E.shape[0] + bs - 1) // bs)
+    g = torch.Generator(device="cpu").manual_seed(args.seed)
+
+    def val_loss():
+        tot, cnt = 0.0, 0
+        for i in range(0, n_val, bs):
+            l = tr.sd_trainer_step(Ev[i:i + bs].contiguous(), Pv[i:i + bs].contiguous(), Mv[i:i + bs].contiguous(),
+                                   w_acc=1.0, w_rej=args.w_rej, apply=False)
+            k = int(Mv[i:i + bs].sum())
+            tot, cnt = tot + l * k, cnt + k
+        return tot / max(cnt, 1)
+
+    v0 = val_loss()
+    t0 = time.perf_counter()
+    step, first, last = 0, None, None
+    for ep in range(epochs):
+        perm = torch.randperm(E.shape[0], generator=g).to(E.device)
+        for i in range(0, E.shape[0], bs):
+            idx = perm[i:i + bs]
+            lr = 0.5 * args.lr * (1.0 + math.cos(math.pi * step / steps))
+            last = tr.sd_trainer_step(E[idx].contiguous(), P[idx].contiguous(), M[idx].contiguous(), w_acc=1.0,
+                                      w_rej=args.w_rej, lr=lr, want_loss=(step % 20 == 0 or step == steps - 1)) or last
+            first = first if first is not None else last
+            step += 1
+    torch.cuda.synchronize()
+    t_train = time.perf_counter() - t0
+    v1 = val_loss()
+    # how well the prediction tracks the target on the held-out tokens
+    pred = torch.sigmoid(torch.cat([tr.sd_trainer_predict(Ev[i:i + bs].contiguous()) for i in range(0, n_val, bs)]))
+    sel = Mv.bool()
+    corr = float(torch.corrcoef(torch.stack([pred[sel], Pv[sel]]))[0, 1])
+    out = tr.sd_trainer_export(torch.bfloat16)
+    tr.close()
+    info = dict(prompts=args.train_head, tokens=int(n_all), masked_fraction=float(M.float().mean()),
+                mean_target=float(P[M.bool()].mean()), steps=steps, data_s=t_data, train_s=t_train,
+                ms_per_step=t_train / max(steps, 1) * 1e3, first_loss=first, last_loss=last, val_loss_before=v0,
+                val_loss_after=v1, val_corr_pred_target=corr, w_rej=args.w_rej, lr=args.lr)
+    print(f"head training: {info}", file=sys.stderr, flush=True)
+    return out, info
+
+
 def _sweep(args):
     """Sec. 5.2's trade-off report on one synthetic aligned pair: the fixed-K baseline
     (Algorithm 1 = Algorithm 2 with h >= 1 and K_max = K) for K in 2..14 and SpecDec++
@@ -148,6 +219,9 @@ def _sweep(args):
     drf = synth.make_perturbed_draft(tgt, n_draft, args.seed + 1, std=std)
     head = synth.make_head([shape.d_model] * 4 + [1], args.seed + 2, device=dev, dtype=torch.bfloat16, residual=True)
     prompt = synth.make_prompt(n_prompt, shape.vocab, args.seed + 3)
+    train_info = None
+    if args.train_head > 0:
+        head, train_info = _train_head(args, tgt, drf, head, shape, n_gen)
     settings = [("fixed", K, 1.0, K) for K in range(2, 15, 2)] + [("specdec++", None, h, 20) for h in (0.3, 0.5, 0.7, 0.9)]
     rows = []
     for mode, K, h, k_max in settings:
@@ -179,7 +253,8 @@ def _sweep(args):
         scaling="weak", vs_baseline=None, dtype="bf16", data="synthetic",
         config=dict(workload=f"aligned pair: llama2-7b-shaped target with layers {n_draft}.. damped x{gain}, draft = "
                              f"its first {n_draft} layers + N(0,{std}), random-init head, batch 1, prompt {n_prompt}, "
-                             f"{n_gen} tokens per setting, top_k {args.top_k}", best=dict(mode=best["mode"], K=best["K"], h=best["h"])),
+                             f"{n_gen} tokens per setting, top_k {args.top_k}", best=dict(mode=best["mode"], K=best["K"], h=best["h"]),
+                    head="trained" if train_info else "random-init", head_training=train_info),
         sweep=rows)))
 
 
@@ -199,6 +274,11 @@ def main():
     ap.add_argument("--sweep", action="store_true", help="fixed-K / threshold sweep on an aligned synthetic pair")
     ap.add_argument("--sweep-tokens", type=int, default=256)
     ap.add_argument("--align-std", type=float, default=0.001)
+    ap.add_argument("--train-head", type=int, default=0, metavar="PROMPTS",
+                    help="with --sweep: first train the acceptance head on this many synthetic prompts")
+    ap.add_argument("--train-epochs", type=int, default=3)
+    ap.add_argument("--w-rej", type=float, default=3.0)
+    ap.add_argument("--lr", type=float, default=5e-5)
     ap.add_argument("--profile-every", type=int, default=8,
                     help="bracket the target GEMMs of every n-th layer with HIP events (0 = off)")
     args = ap.parse_args()

@@ -161,3 +161,30 @@ def test_trainer_rejects_bad_arguments():
             tr.sd_trainer_step(E.cuda(), P.cuda(), m.cuda(), beta1=1.0)
     finally:
         tr.close()
+
+
+def test_training_learns_a_learnable_target():
+    """Targets that are a logistic function of the embedding are recovered by a D = 1 head:
+    the held-out prediction correlates with the target (the synthetic model pairs give
+    targets that do not depend on the embedding, so this is the check that the trainer
+    learns when there is something to learn)."""
+    from paper_2405_19715_amd import binding as B
+    g = torch.Generator().manual_seed(0)
+    d = 64
+    w_true = torch.randn(d, generator=g)
+    h = synth.make_head([d, d, 1], 5, dtype=torch.float32, residual=True, std=0.05, out_bias=0.0)
+    tr = B.Trainer(_cuda_head(h), n_max=256)
+    try:
+        first = last = None
+        for step in range(400):
+            E = torch.randn((256, d), generator=g)
+            P = torch.sigmoid(E @ w_true / 4.0)
+            last = tr.sd_trainer_step(E.cuda(), P.cuda(), torch.ones(256, dtype=torch.int32).cuda(), lr=3e-3)
+            first = first if first is not None else last
+        E = torch.randn((256, d), generator=g)
+        P = torch.sigmoid(E @ w_true / 4.0)
+        pred = torch.sigmoid(tr.sd_trainer_predict(E.cuda()).cpu())
+        assert last < first - 0.02
+        assert float(torch.corrcoef(torch.stack([pred, P]))[0, 1]) > 0.97
+    finally:
+        tr.close()
