@@ -33,14 +33,21 @@ def _workload(name):
     if name == "mid":        # Llama-2-7B-shaped target, 1.1B-shaped draft
         return dict(target=synth.LLAMA_7B, draft=synth.LLAMA_1B, head=[2048, 2048, 2048, 2048, 1], prompt=512,
                     gen=256, k_max=16, label="llama2-7b/1.1b-shaped bf16 random-init, batch 1, prompt 512, K_max 16")
+    if name == "batch8":     # the paper-shaped pair, 8 sequences with ragged prompts, per-sequence adaptive K
+        import random
+        rng = random.Random(7)
+        return dict(target=synth.LLAMA_70B, draft=synth.LLAMA_7B, head=[4096, 4096, 4096, 4096, 1], batch=8,
+                    prompts=[rng.randint(256, 2048) for _ in range(8)], prompt=2048, gen=512, k_max=16,
+                    label="llama2-70b/7b-shaped bf16 random-init, batch 8, prompts uniform in [256, 2048], K_max 16")
     raise SystemExit(f"unknown workload {name}")
 
 
-def _algorithmic_bytes_verify(shape, P, K, esz=2):
+def _algorithmic_bytes_verify(shape, P, K, esz=2, batch=1):
     """Bytes one target pass must move: every weight once, the KV cache of the P
-    finalised positions, the K+1 new KV rows, and the K+1 fp32 logits rows."""
+    finalised positions (summed over the batch), the K+1 new KV rows and the K+1 fp32
+    logits rows of every sequence."""
     kv_token = 2 * shape.n_layers * shape.n_kv * esz
-    return shape.streamed_params() * esz + kv_token * P + kv_token * (K + 1) + (K + 1) * shape.vocab * 4
+    return shape.streamed_params() * esz + kv_token * P + batch * (kv_token * (K + 1) + (K + 1) * shape.vocab * 4)
 
 
 def _measured_traffic():
@@ -120,6 +127,57 @@ def _cpu_baseline(tgt, drf, k_mean, n_mean, P, k_max):
                         f"t_draft {t_draft:.2f}s; tokens/s = (n+1)/(K*t_draft + t_target) with the GPU run's "
                         f"mean K={k_mean:.2f}, n={n_mean:.2f}"),
                 t_target_s=t_target, t_draft_s=t_draft)
+
+
+def _accept_bench(args):
+    """The isolated softmax + accept + residual-resample step (Algorithm 1's tail) on its own
+    workload: vocab 32000, batch {1, 16, 64}, K in {1, 4, 8, 16}, target logits N(0, 2^2),
+    draft = target + N(0, 0.5^2).  Algorithmic bytes per call: every live logits row once,
+    B (2K + 1) V 4.  A step is one call; the JSON line reports B = 64, K = 16."""
+    import torch
+    from paper_2405_19715_amd import binding as B
+    from paper_2405_19715_amd import synth
+    torch.cuda.set_device(0)
+    V, rows = 32000, []
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    for nb in (1, 16, 64):
+        for K in (1, 4, 8, 16):
+            # several input sets in rotation so that the 256 MB memory-side cache does not serve the rows
+            n_sets = max(2, int(6e8 // (nb * (2 * K + 1) * V * 4)) + 1) if nb * K > 16 else 2
+            n_sets = min(n_sets, 8)
+            sets = [synth.make_accept_logits(nb, K, V, args.seed + i, device="cuda") for i in range(n_sets)]
+            cand = torch.stack([q.argmax(-1) for _, q in sets]).to(torch.int32)
+            Ks = torch.full((nb,), K, dtype=torch.int32, device="cuda")
+            params = B.make_params(seed=args.seed, top_k=args.top_k)
+            out = None
+            n, tok, flags = B.sd_accept_resample(sets[0][0], sets[0][1], cand[0].contiguous(), Ks, params, 0)
+            out = (n, tok, flags, torch.empty(B.lib.sd_accept_workspace_bytes(nb, K), dtype=torch.uint8, device="cuda"))
+            for i in range(n_sets):
+                B.sd_accept_resample(sets[i][0], sets[i][1], cand[i].contiguous(), Ks, params, i, out=out)
+            torch.cuda.synchronize()
+            reps = max(args.steps // n_sets, 2)
+            e0.record()
+            for rnd in range(reps):
+                for i in range(n_sets):
+                    B.sd_accept_resample(sets[i][0], sets[i][1], cand[i], Ks, params, rnd, out=out)
+            e1.record()
+            torch.cuda.synchronize()
+            t = e0.elapsed_time(e1) * 1e-3 / (reps * n_sets)
+            nbytes = nb * (2 * K + 1) * V * 4
+            rows.append(dict(batch=nb, K=K, us=t * 1e6, GBs=nbytes / t / 1e9, bytes=nbytes))
+            print(f"accept B={nb:3d} K={K:2d}: {t * 1e6:8.1f} us  {nbytes / t / 1e9:8.1f} GB/s", file=sys.stderr, flush=True)
+            del sets
+    last = rows[-1]
+    print(json.dumps(dict(
+        metric="isolated accept / resample calls per second (vocab 32000, batch 64, K 16)", value=1e6 / last["us"],
+        unit="calls/s", n_gpus=1, steps=args.steps, warmup=1, ms_per_step=last["us"] / 1e3, higher_is_better=True,
+        scaling="weak", vs_baseline=None, dtype="f32", data="synthetic",
+        config=dict(workload="isolated accept/resample: vocab 32000, target logits N(0,4), draft = target + N(0,0.25)",
+                    top_k=args.top_k),
+        roofline=dict(bound="hbm", kernel="row_stats_k x2 + accept_k", achieved=last["GBs"], peak=HBM_PEAK_GBS,
+                      unit="GB/s", frac=last["GBs"] / HBM_PEAK_GBS, traffic=None,
+                      algorithmic_bytes_per_launch=last["bytes"]),
+        cpu_baseline=None, cases=rows)))
 
 
 def _train_head(args, tgt, drf, head, shape, n_gen):
@@ -286,6 +344,8 @@ def main():
         raise SystemExit("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)")
     if args.sweep:
         return _sweep(args)
+    if args.workload == "accept":
+        return _accept_bench(args)
 
     import torch
     from paper_2405_19715_amd import binding as B
@@ -308,15 +368,18 @@ def main():
     torch.cuda.synchronize()
     t_build = time.perf_counter() - t_build
     max_seq = -(-(wl["prompt"] + wl["gen"] + (args.steps + args.warmup + 16) * (wl["k_max"] + 1) + 2) // 64) * 64
-    ctx = B.Context(tgt, drf, head, batch=1, max_seq=max_seq, k_max=wl["k_max"])
-    prompt = synth.make_prompt(wl["prompt"], wl["target"].vocab, args.seed + 3)
-    ctx.sd_prefill(0, prompt[:8])                       # warm-up of the prompt-pass kernels, overwritten below
+    nb = wl.get("batch", 1)
+    lens = wl.get("prompts", [wl["prompt"]])
+    ctx = B.Context(tgt, drf, head, batch=nb, max_seq=max_seq, k_max=wl["k_max"])
+    prompts = [synth.make_prompt(lens[b], wl["target"].vocab, args.seed + 3 + b) for b in range(nb)]
+    ctx.sd_prefill(0, prompts[0][:8])                   # warm-up of the prompt-pass kernels, overwritten below
     torch.cuda.synchronize()
     t_prefill = time.perf_counter()
-    ctx.sd_prefill(0, prompt)                           # untimed for the metric; reported on its own
+    for b in range(nb):
+        ctx.sd_prefill(b, prompts[b])                   # untimed for the metric; reported on its own
     torch.cuda.synchronize()
     t_prefill = time.perf_counter() - t_prefill
-    rows = wl["prompt"] - 1
+    rows = sum(lens) - nb
     prefill_flops = 2.0 * rows * sum(sh.n_layers * sh.layer_params() for sh in (wl["target"], wl["draft"]))
     params = B.make_params(h=args.h, temperature=1.0, greedy=False, seed=args.seed, top_k=args.top_k)
 
@@ -324,22 +387,22 @@ def main():
         ctx.specdec_round(params)
     ctx.sd_profile_enable(args.profile_every)
     ctx.sd_profile_read()
-    P0 = ctx.sd_seq_state(0)["P"]
+    P0 = sum(ctx.sd_seq_state(b)["P"] for b in range(nb))
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    # the timed region: exactly `steps` rounds
+    # the timed region: exactly `steps` rounds (each over the whole batch)
     Ks, ns = [], []
     for _ in range(args.steps):
-        r = ctx.specdec_round(params)[0]
-        Ks.append(r["K"])
-        ns.append(r["n"])
+        for r in ctx.specdec_round(params):
+            Ks.append(r["K"])
+            ns.append(r["n"])
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     prof = ctx.sd_profile_read()
     ctx.sd_profile_enable(0)
     n_tok = sum(n + 1 for n in ns)
     k_mean, n_mean = sum(Ks) / len(Ks), sum(ns) / len(ns)
-    P_mid = (P0 + ctx.sd_seq_state(0)["P"]) // 2
+    P_mid = (P0 + sum(ctx.sd_seq_state(b)["P"] for b in range(nb))) // 2      # summed over the batch
 
     # phase times of a few more rounds (events inside the library, same stream)
     _, st2 = ctx.specdec_generate(params, max(8, 4 * int(n_mean + 1)))
@@ -356,7 +419,7 @@ def main():
     if all(prof[k]["launches"] for k in counts):
         est_avg_us = sum(counts[k] * prof[k]["seconds"] / prof[k]["launches"] for k in counts) / sum(counts.values()) * 1e6
     achieved = tot_b / tot_s / 1e9 if tot_s > 0 else None
-    verify_bytes = _algorithmic_bytes_verify(wl["target"], P_mid, wl["k_max"])
+    verify_bytes = _algorithmic_bytes_verify(wl["target"], P_mid, wl["k_max"], batch=nb)
     roofline = dict(bound="hbm", kernel="gemm_bf16_stream<NT> (target pass, M = K+1 rows: instance <1> for up to 16 rows, <2> for 17)",
                     achieved=achieved, peak=HBM_PEAK_GBS, unit="GB/s",
                     frac=(achieved / HBM_PEAK_GBS) if achieved else None,
@@ -369,9 +432,11 @@ def main():
                                      achieved_GBs=verify_bytes / t_target / 1e9,
                                      frac=verify_bytes / t_target / 1e9 / HBM_PEAK_GBS))
     cpu = None
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and nb == 1:
         cpu = _cpu_baseline(tgt, drf, k_mean, n_mean, wl["prompt"], wl["k_max"])
-    out = dict(metric="generated tokens/s (batch 1, 70B/7B shape) + verify-pass HBM GB/s % of peak",
+    metric = ("generated tokens/s (batch 1, 70B/7B shape) + verify-pass HBM GB/s % of peak" if nb == 1 else
+              f"generated tokens/s (batch {nb}, ragged prompts, whole batch) + verify-pass HBM GB/s % of peak")
+    out = dict(metric=metric,
                value=n_tok / dt, unit="tokens/s", n_gpus=1, steps=args.steps, warmup=args.warmup,
                ms_per_step=dt / args.steps * 1e3, higher_is_better=True, scaling="weak", vs_baseline=None,
                dtype="bf16", data="synthetic",

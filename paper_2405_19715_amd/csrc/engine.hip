@@ -572,8 +572,8 @@ static sd_status round_impl(sd_ctx* c, const sd_params* params, sd_round_out* ou
   // ---- accept / residual resample, commit, rollback
   float* p_stats = c->stats;
   float* q_stats = c->stats + (size_t)B * (k_max + 1) * 4;
-  SD_HIP(launch_row_stats(st, c->p_logits, k_max + 1, 1, c->s.K, B, V, dp.temperature, dp.top_k, p_stats, c->s.err));
-  SD_HIP(launch_row_stats(st, c->q_logits, k_max, 0, c->s.K, B, V, dp.temperature, dp.top_k, q_stats, c->s.err));
+  SD_HIP(launch_row_stats(st, c->p_logits, c->q_logits, k_max, c->s.K, B, V, dp.temperature, dp.top_k, p_stats, q_stats,
+                          c->s.err));
   SD_HIP(launch_accept(st, c->p_logits, c->q_logits, p_stats, q_stats, c->s.cand, CAND_LD, c->s.K, c->s.round, 0, dp,
                        B, k_max, V, c->s.n_acc, c->s.y_new, c->s.flags, CAND_LD));
   SD_HIP(launch_commit(st, c->s, c->result, B, max_seq));
@@ -689,8 +689,7 @@ sd_status sd_accept_resample(const float* p_logits, const float* q_logits, const
   const DecodeParams dp = to_dp(params);
   float* p_stats = (float*)ws;
   float* q_stats = p_stats + (size_t)B * (Kmax + 1) * 4;
-  SD_HIP(launch_row_stats(st, p_logits, Kmax + 1, 1, K, B, V, dp.temperature, dp.top_k, p_stats, nullptr));
-  SD_HIP(launch_row_stats(st, q_logits, Kmax, 0, K, B, V, dp.temperature, dp.top_k, q_stats, nullptr));
+  SD_HIP(launch_row_stats(st, p_logits, q_logits, Kmax, K, B, V, dp.temperature, dp.top_k, p_stats, q_stats, nullptr));
   SD_HIP(launch_accept(st, p_logits, q_logits, p_stats, q_stats, cand, Kmax, K, nullptr, round_idx, dp, B, Kmax, V,
                        n_out, tok_out, flags, Kmax));
   return SD_OK;

@@ -106,12 +106,13 @@ hipError_t launch_sample_stop(hipStream_t st, int dtype, const SeqState& s, cons
                               int64_t ld_seq, const void* z, const int* z_rows, int z_dim, const void* w_last,
                               const void* b_last, int have_head, const DecodeParams& p, int B, int V,
                               int step);
-// softmax statistics of the live rows of a [B, rows_per_seq, V] logits array (row j of
-// sequence b is live when j < K[b] + extra): stats[row] = {max, sum exp((l-max)/T), argmax, 0}
-// With top_k > 0 only logits >= the row's k-th largest enter the sum, and stats[row][3] holds
-// that threshold (else -inf).
-hipError_t launch_row_stats(hipStream_t st, const float* logits, int rows_per_seq, int extra, const int32_t* K,
-                            int B, int V, float temperature, int top_k, float* stats, int32_t* err);
+// softmax statistics of the live rows of the target logits [B, Kmax + 1, V] (row j of sequence b
+// is live when j <= K[b]) and the draft logits [B, Kmax, V] (live when j < K[b]), in one launch:
+// stats[row] = {max, sum exp((l-max)/T), argmax, top-k threshold}.  With top_k > 0 only logits >=
+// the row's k-th largest enter the sum and the threshold is that value (else -inf).
+hipError_t launch_row_stats(hipStream_t st, const float* p_logits, const float* q_logits, int Kmax,
+                            const int32_t* K, int B, int V, float temperature, int top_k, float* p_stats,
+                            float* q_stats, int32_t* err);
 // accept tests, n, and the residual / bonus sample y' for every sequence
 hipError_t launch_accept(hipStream_t st, const float* p_logits, const float* q_logits, const float* p_stats,
                          const float* q_stats, const int32_t* cand, int cand_ld, const int32_t* K,

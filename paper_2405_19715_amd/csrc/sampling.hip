@@ -73,48 +73,82 @@ __device__ float block_kth_largest(const float* __restrict__ l, int V, int k, in
 }
 
 // Inverse-CDF draw over v in [0, V) with weight f(v) >= 0; returns -1 when the total
-// mass is not positive.  sh_incl: SB floats, sh_w: SB/64 floats, sh_res: 1 int.
+// mass is not positive.  sh_w: SB/64 floats, sh_res: 1 int (sh_incl is unused scratch).
+//
+// The cumulative sum runs in index order, but it is not formed left to right by one
+// thread: wavefront w owns the contiguous range [w CW, (w+1) CW), walks it in rows of 256
+// elements (lane l holds elements 4l .. 4l+3 of a row, so every load is coalesced), and
+// a row's total is the last lane of an inclusive lane scan.  Pass 1 gives every
+// wavefront its total; the wavefront whose range contains u * S repeats its walk with
+// exactly the same additions to find the row, the lane and the element.
 template <typename F>
 __device__ int block_sample(F f, int V, float u, float* sh_incl, float* sh_w, int* sh_res) {
+  (void)sh_incl;
   const int t = threadIdx.x, lane = t & 63, w = t >> 6;
-  const int C = (V + SB - 1) / SB;
-  const int v0 = min(t * C, V), v1 = min(v0 + C, V);
-  float local = 0.f;
-  for (int v = v0; v < v1; ++v) local += f(v);
-  float s = local;
+  constexpr int NW = SB / 64;
+  const int CW = (((V + NW - 1) / NW) + 255) & ~255;            // elements per wavefront, whole rows
+  const int beg = min(w * CW, V), end = min(beg + CW, V);
+  auto row_scan = [&](int r0, float* fv, float& incl, float& tot) {
+    float ls = 0.f;
 #pragma unroll
-  for (int o = 1; o < 64; o <<= 1) {
-    const float n = __shfl_up(s, o, WAVE);
-    if (lane >= o) s += n;
+    for (int e = 0; e < 4; ++e) {
+      const int v = r0 + 4 * lane + e;
+      fv[e] = v < end ? f(v) : 0.f;
+      ls += fv[e];
+    }
+    incl = ls;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+      const float n = __shfl_up(incl, o, WAVE);
+      if (lane >= o) incl += n;
+    }
+    tot = __shfl(incl, 63, WAVE);
+    return ls;
+  };
+  float cw = 0.f;
+  for (int r0 = beg; r0 < end; r0 += 256) {
+    float fv[4], incl, tot;
+    row_scan(r0, fv, incl, tot);
+    cw += tot;
   }
-  if (lane == 63) sh_w[w] = s;
+  if (lane == 0) sh_w[w] = cw;
   if (t == 0) *sh_res = -1;
   __syncthreads();
-  float off = 0.f;
-  for (int k = 0; k < w; ++k) off += sh_w[k];
-  const float incl = off + s;
-  sh_incl[t] = incl;
-  __syncthreads();
-  const float total = sh_incl[SB - 1];
-  if (!(total > 0.f)) return -1;
+  float off = 0.f, total = 0.f;
+  for (int k = 0; k < NW; ++k) {
+    if (k == w) off = total;
+    total += sh_w[k];
+  }
+  if (!(total > 0.f)) return -1;                                // uniform: every thread sees the same total
   const float target = u * total;
-  const float excl = t == 0 ? 0.f : sh_incl[t - 1];
-  if (excl <= target && target < incl) {
-    float run = excl;
-    int pick = -1, last_pos = -1;
-    for (int v = v0; v < v1; ++v) {
-      const float fv = f(v);
-      run += fv;
-      if (fv > 0.f) last_pos = v;
-      if (run > target) { pick = v; break; }
+  if (off <= target && target < off + cw) {                     // wave-uniform
+    float run = 0.f;
+    for (int r0 = beg; r0 < end; r0 += 256) {
+      float fv[4], incl, tot;
+      const float ls = row_scan(r0, fv, incl, tot);
+      if (off + (run + tot) > target) {
+        const unsigned long long m = __ballot(off + (run + incl) > target);
+        if (lane == __ffsll((long long)m) - 1) {
+          float r = run + (incl - ls);
+          int pick = -1, last_pos = -1;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            r += fv[e];
+            if (fv[e] > 0.f) last_pos = r0 + 4 * lane + e;
+            if (pick < 0 && off + r > target) pick = r0 + 4 * lane + e;
+          }
+          *sh_res = pick >= 0 ? pick : last_pos;
+        }
+        break;
+      }
+      run += tot;
     }
-    *sh_res = pick >= 0 ? pick : last_pos;
   }
   __syncthreads();
   int res = *sh_res;
   if (res < 0) {                      // rounding left no bucket: largest v with mass
     int best = -1;
-    for (int v = v0; v < v1; ++v)
+    for (int v = t; v < V; v += SB)
       if (f(v) > 0.f) best = v;
     __syncthreads();
     atomicMax(sh_res, best);
@@ -253,38 +287,64 @@ __global__ __launch_bounds__(SB) void sample_stop_k(SeqState s, const float* __r
 }
 
 // ------------------------------------------------------------------ softmax statistics per row
-// stats[row] = {max, sum_v exp((l_v - max)/T), argmax (int bits), 0}.  Row (b, j) of a
-// [B, rows_per_seq, V] array is live when j < K[b] + extra.
-__global__ __launch_bounds__(SB) void row_stats_k(const float* __restrict__ logits, int rows_per_seq, int extra,
-                                                  const int32_t* __restrict__ K, int V, float inv_t, int top_k,
-                                                  float* __restrict__ stats, int32_t* __restrict__ err) {
+// stats[row] = {max, sum_v exp((l_v - max)/T), argmax (int bits), top-k threshold or -inf}.
+// One launch covers two logits arrays: blocks x < rows_a serve array A ([B, rows_a, V], row j
+// live when j < K[b] + extra_a), the rest array B ([B, rows_b, V], live when j < K[b] + extra_b).
+// Without top-k a row is read once: every thread keeps a running (max, sum) pair over its
+// strided 16-byte pieces and the pairs are rescaled to the row maximum at the end.
+struct RowSet { const float* logits; float* stats; int rows, extra; };
+
+__global__ __launch_bounds__(SB) void row_stats_k(RowSet A, RowSet Bq, const int32_t* __restrict__ K, int V, float inv_t,
+                                                  int top_k, int32_t* __restrict__ err) {
   __shared__ float sh_w[SB / 64];
   __shared__ int sh_i[SB / 64];
-  const int j = blockIdx.x, b = blockIdx.y;
-  if (j >= K[b] + extra) return;
-  const size_t row = (size_t)b * rows_per_seq + j;
-  const float* l = logits + row * V;
+  const int b = blockIdx.y;
+  const bool first = (int)blockIdx.x < A.rows;
+  const RowSet& R = first ? A : Bq;
+  const int j = first ? blockIdx.x : blockIdx.x - A.rows;
+  if (j >= K[b] + R.extra) return;
+  const size_t row = (size_t)b * R.rows + j;
+  const float* l = R.logits + row * V;
+  const bool warp = top_k > 0 && top_k < V;
   ArgMax am{-INFINITY, 0x7fffffff};
+  float run = 0.f;                                   // sum of exp((x - am.v)/T) over this thread's elements
   bool bad = false;
-  for (int v = threadIdx.x; v < V; v += SB) {
-    const float x = l[v];
+  auto take = [&](float x, int v) {
     bad |= !isfinite(x);
-    am = better(am, ArgMax{x, v});
+    if (x > am.v) {                                  // strided indices grow, so ties keep the lowest id
+      run = run * expf((am.v - x) * inv_t) + 1.0f;
+      am = ArgMax{x, v};
+    } else {
+      run += expf((x - am.v) * inv_t);
+    }
+  };
+  if ((V & 3) == 0 && (reinterpret_cast<uintptr_t>(l) & 15) == 0) {
+    const float4* l4 = reinterpret_cast<const float4*>(l);
+    for (int q = threadIdx.x; q < V / 4; q += SB) {
+      const float4 x = l4[q];
+      take(x.x, 4 * q); take(x.y, 4 * q + 1); take(x.z, 4 * q + 2); take(x.w, 4 * q + 3);
+    }
+  } else {
+    for (int v = threadIdx.x; v < V; v += SB) take(l[v], v);
   }
+  const ArgMax mine = am;
   am = block_argmax(am, sh_w, sh_i);
   if (bad && err) atomicOr(err, 1);
-  const float thr = (top_k > 0 && top_k < V) ? block_kth_largest(l, V, top_k, sh_i) : -INFINITY;
-  // contiguous chunk per thread, then a fixed-order block reduction
-  const int C = (V + SB - 1) / SB;
-  const int v0 = min((int)threadIdx.x * C, V), v1 = min(v0 + C, V);
-  float local = 0.f;
-  for (int v = v0; v < v1; ++v) local += l[v] >= thr ? expf((l[v] - am.v) * inv_t) : 0.f;
-  const float total = block_sum(local, sh_w);
+  float thr = -INFINITY, total;
+  if (!warp) {
+    const float scaled = mine.i == 0x7fffffff ? 0.f : run * expf((mine.v - am.v) * inv_t);
+    total = block_sum(scaled, sh_w);
+  } else {
+    thr = block_kth_largest(l, V, top_k, sh_i);
+    float local = 0.f;
+    for (int v = threadIdx.x; v < V; v += SB) local += l[v] >= thr ? expf((l[v] - am.v) * inv_t) : 0.f;
+    total = block_sum(local, sh_w);
+  }
   if (threadIdx.x == 0) {
-    stats[row * 4 + 0] = am.v;
-    stats[row * 4 + 1] = total;
-    stats[row * 4 + 2] = __int_as_float(am.i);
-    stats[row * 4 + 3] = thr;
+    R.stats[row * 4 + 0] = am.v;
+    R.stats[row * 4 + 1] = total;
+    R.stats[row * 4 + 2] = __int_as_float(am.i);
+    R.stats[row * 4 + 3] = thr;
   }
 }
 
@@ -312,10 +372,8 @@ __global__ __launch_bounds__(SB) void label_k(const float* __restrict__ p_logits
   const int y = block_sample([&](int v) { return lq[v] >= qthr ? expf((lq[v] - qmx) * inv_t) : 0.f; }, V, u, sh_incl,
                              sh_w, &sh_res);
   __syncthreads();
-  const int C = (V + SB - 1) / SB;
-  const int v0 = min((int)threadIdx.x * C, V), v1 = min(v0 + C, V);
   float local = 0.f;
-  for (int v = v0; v < v1; ++v) local += lq[v] >= qthr ? expf((lq[v] - qmx) * inv_t) : 0.f;
+  for (int v = threadIdx.x; v < V; v += SB) local += lq[v] >= qthr ? expf((lq[v] - qmx) * inv_t) : 0.f;
   const float qsum = block_sum(local, sh_w);
   // target row: max, threshold, sum
   ArgMax pm{-INFINITY, 0x7fffffff};
@@ -323,7 +381,7 @@ __global__ __launch_bounds__(SB) void label_k(const float* __restrict__ p_logits
   pm = block_argmax(pm, sh_w, sh_i);
   const float pthr = warp ? block_kth_largest(lp, V, top_k, sh_i) : -INFINITY;
   local = 0.f;
-  for (int v = v0; v < v1; ++v) local += lp[v] >= pthr ? expf((lp[v] - pm.v) * inv_t) : 0.f;
+  for (int v = threadIdx.x; v < V; v += SB) local += lp[v] >= pthr ? expf((lp[v] - pm.v) * inv_t) : 0.f;
   const float psum = block_sum(local, sh_w);
   if (threadIdx.x == 0) {
     const int yy = y < 0 ? am.i : y;
@@ -495,12 +553,13 @@ hipError_t launch_sample_stop(hipStream_t st, int dtype, const SeqState& s, cons
   return hipGetLastError();
 }
 
-hipError_t launch_row_stats(hipStream_t st, const float* logits, int rows_per_seq, int extra, const int32_t* K, int B,
-                            int V, float temperature, int top_k, float* stats, int32_t* err) {
-  if (B < 1 || rows_per_seq < 1 || V < 1 || top_k < 0 || !logits || !K || !stats || !(temperature > 0.f))
+hipError_t launch_row_stats(hipStream_t st, const float* p_logits, const float* q_logits, int Kmax, const int32_t* K,
+                            int B, int V, float temperature, int top_k, float* p_stats, float* q_stats, int32_t* err) {
+  if (B < 1 || Kmax < 1 || V < 1 || top_k < 0 || !p_logits || !q_logits || !K || !p_stats || !q_stats ||
+      !(temperature > 0.f))
     return hipErrorInvalidValue;
-  hipLaunchKernelGGL(row_stats_k, dim3(rows_per_seq, B), dim3(SB), 0, st, logits, rows_per_seq, extra, K, V,
-                     1.0f / temperature, top_k, stats, err);
+  const RowSet A{p_logits, p_stats, Kmax + 1, 1}, Bq{q_logits, q_stats, Kmax, 0};
+  hipLaunchKernelGGL(row_stats_k, dim3(2 * Kmax + 1, B), dim3(SB), 0, st, A, Bq, K, V, 1.0f / temperature, top_k, err);
   return hipGetLastError();
 }
 
