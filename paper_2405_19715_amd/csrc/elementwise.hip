@@ -200,17 +200,21 @@ __global__ __launch_bounds__(EW_THREADS) void silu_mul_k(const float* __restrict
   Elem<T>::st(act + (size_t)m * ffn + f, g / (1.0f + expf(-g)) * u);
 }
 
-// Row m = (group m / RS, slot m % RS) goes to out[group * ld_group + slot * ld_row + n].
+// Row m = (group m / RS, slot m % RS) goes to out[group * ld_group + slot * ld_row + n]; with a
+// destination map, to out[dst[m] * ld_row + n] instead (rows with dst[m] < 0 are dropped).
 __global__ __launch_bounds__(EW_THREADS) void reduce_rows_k(const float* __restrict__ part, int S,
                                                             float* __restrict__ out, int RS, int64_t ld_group,
-                                                            int64_t ld_row, int M, int N) {
+                                                            int64_t ld_row, const int32_t* __restrict__ dst, int M,
+                                                            int N) {
   const int m = blockIdx.y;
   const int n = blockIdx.x * EW_THREADS + threadIdx.x;
   if (n >= N) return;
+  if (dst && dst[m] < 0) return;
   float v = 0.f;
 #pragma unroll 4
   for (int s = 0; s < S; ++s) v += part[((size_t)s * M + m) * N + n];
-  out[(size_t)(m / RS) * ld_group + (size_t)(m % RS) * ld_row + n] = v;
+  const size_t o = dst ? (size_t)dst[m] * ld_row : (size_t)(m / RS) * ld_group + (size_t)(m % RS) * ld_row;
+  out[o + n] = v;
 }
 
 template <typename T>
@@ -301,11 +305,11 @@ hipError_t launch_silu_mul(hipStream_t st, int dtype, const float* part, int S, 
 }
 
 hipError_t launch_reduce_rows(hipStream_t st, const float* part, int S, float* out, int RS, int64_t ld_group,
-                              int64_t ld_row, int M, int N) {
+                              int64_t ld_row, int M, int N, const int32_t* dst) {
   if (bad_rows(M) || S < 1 || N < 1 || RS < 1 || M % RS != 0 || ld_row < N || !part || !out)
     return hipErrorInvalidValue;
   const dim3 grid((N + EW_THREADS - 1) / EW_THREADS, M);
-  hipLaunchKernelGGL(reduce_rows_k, grid, dim3(EW_THREADS), 0, st, part, S, out, RS, ld_group, ld_row, M, N);
+  hipLaunchKernelGGL(reduce_rows_k, grid, dim3(EW_THREADS), 0, st, part, S, out, RS, ld_group, ld_row, dst, M, N);
   return hipGetLastError();
 }
 

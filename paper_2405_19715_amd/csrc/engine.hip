@@ -69,6 +69,7 @@ struct sd_ctx {
   float *part = nullptr, *attn_scratch = nullptr, *ssq = nullptr;
   float *q_logits = nullptr, *p_logits = nullptr, *fw_logits = nullptr, *stats = nullptr;
   float* fw_logits2 = nullptr;     // second [32, V] logits buffer, allocated by the first sd_head_examples call
+  int32_t* lm_dst = nullptr;       // [MAX_ROWS] logits row of every slot of a ragged target pass
   int32_t* ex_ints = nullptr;      // X, Y, Z, mask staging of sd_head_examples: 4 * max_seq ints
   RowPlan rows{};
   SeqState s{};
@@ -234,7 +235,8 @@ sd_status gemm(sd_ctx* c, const ModelRt& rt, const void* W, const void* X, int l
 // the large-M tiled kernel, which writes whole products (one "slice"), and attention
 // through its unsplit variant; M may then reach c->prefill_rows.
 sd_status forward(sd_ctx* c, ModelRt& rt, int M, int RS, int max_kv_len, const int* lm_rows, int n_lm,
-                  float* logits_out, int lm_rs, int64_t ld_group, int64_t ld_row, bool profile, bool tile = false) {
+                  float* logits_out, int lm_rs, int64_t ld_group, int64_t ld_row, bool profile, bool tile = false,
+                  const int32_t* lm_dst = nullptr) {
   const sd_model& m = rt.m;
   const int dt = m.dtype, d = m.d_model, nq = rt.n_q(), nkv = rt.n_kv();
   hipStream_t st = c->st;
@@ -271,7 +273,7 @@ sd_status forward(sd_ctx* c, ModelRt& rt, int M, int RS, int max_kv_len, const i
         SD_OK)
       return s;
     SD_HIP(launch_reduce_rows(st, c->part, gemm_splits(dt, n_lm, m.vocab, d), logits_out, lm_rs, ld_group, ld_row, n_lm,
-                              m.vocab));
+                              m.vocab, lm_dst));
   }
   return SD_OK;
 }
@@ -467,6 +469,7 @@ sd_status sd_create(sd_ctx** out, const sd_model* target, const sd_model* draft,
   SD_ALLOC(c->s.err, 16, true);
   SD_ALLOC(c->s.active, B * 4, true);
   SD_ALLOC(c->result, (size_t)B * RESULT_INTS * 4, true);
+  SD_ALLOC(c->lm_dst, MAX_ROWS * 4, true);
 #undef SD_ALLOC
   c->pinned_ints = std::max<size_t>(3 * MAX_PREFILL_ROWS + 2, (size_t)B * RESULT_INTS) + 64;
   if (hipHostMalloc((void**)&c->pinned, c->pinned_ints * 4, hipHostMallocDefault) != hipSuccess) return fail(SD_ENOMEM);
@@ -535,6 +538,7 @@ static sd_status round_impl(sd_ctx* c, const sd_params* params, sd_round_out* ou
   SD_HIP(hipEventRecord(c->ev[0], st));
   // ---- adaptive draft loop (Algorithm 2's first block)
   int k_round = k_max;                      // largest K of the round = draft steps taken
+  std::vector<int> k_seq(B, 0);             // per-sequence K as the stop flags reveal it (0: not yet stopped)
   for (int step = 1; step <= k_max; ++step) {
     SD_HIP(launch_plan_draft(st, c->s, c->rows, B, step, max_seq));
     const int kv_bound = std::min(max_seq, maxP + step);
@@ -554,7 +558,10 @@ static sd_status round_impl(sd_ctx* c, const sd_params* params, sd_round_out* ou
       SD_HIP(hipMemcpyAsync(c->pinned, c->s.stopped, B * sizeof(int32_t), hipMemcpyDeviceToHost, st));
       SD_HIP(hipStreamSynchronize(st));
       bool all = true;
-      for (int b = 0; b < B; ++b) all = all && c->pinned[b] != 0;
+      for (int b = 0; b < B; ++b) {
+        all = all && c->pinned[b] != 0;
+        if (c->pinned[b] != 0 && k_seq[b] == 0 && c->active[b]) k_seq[b] = step;
+      }
       if (all) {
         k_round = step;
         break;
@@ -563,11 +570,27 @@ static sd_status round_impl(sd_ctx* c, const sd_params* params, sd_round_out* ou
   }
   SD_HIP(hipEventRecord(c->ev[1], st));
   // ---- target pass over the K+1 positions (row slots sized by this round's largest K)
-  const int rs = k_round + 1, Mv = B * rs;
-  SD_HIP(launch_plan_verify(st, c->s, c->rows, B, rs, max_seq));
-  if ((s = forward(c, c->target, Mv, rs, std::min(max_seq, maxP + k_round), nullptr, Mv, c->p_logits, rs,
-                   (int64_t)(k_max + 1) * V, V, true)) != SD_OK)
-    return s;
+  // One sequence: its K+1 rows are one group.  Several: K differs between sequences, so each takes
+  // ceil((K_b+1)/4) groups of 4 row slots, packed, instead of max_b(K_b)+1 slots each; the GEMMs then
+  // carry sum_b (K_b+1) rows plus at most 3 padding rows per sequence.
+  const int rs = k_round + 1;
+  constexpr int RAGGED_RS = 4;
+  int n_groups = 0;
+  for (int b = 0; b < B; ++b)
+    if (c->active[b]) n_groups += ((k_seq[b] ? k_seq[b] : k_round) + RAGGED_RS) / RAGGED_RS;
+  if (B > 1 && n_groups * RAGGED_RS < B * rs && n_groups * RAGGED_RS <= MAX_ROWS) {
+    const int Mv = n_groups * RAGGED_RS;
+    SD_HIP(launch_plan_verify_ragged(st, c->s, c->rows, B, RAGGED_RS, n_groups, k_max, max_seq, c->lm_dst));
+    if ((s = forward(c, c->target, Mv, RAGGED_RS, std::min(max_seq, maxP + k_round), nullptr, Mv, c->p_logits,
+                     RAGGED_RS, 0, V, true, false, c->lm_dst)) != SD_OK)
+      return s;
+  } else {
+    const int Mv = B * rs;
+    SD_HIP(launch_plan_verify(st, c->s, c->rows, B, rs, max_seq));
+    if ((s = forward(c, c->target, Mv, rs, std::min(max_seq, maxP + k_round), nullptr, Mv, c->p_logits, rs,
+                     (int64_t)(k_max + 1) * V, V, true)) != SD_OK)
+      return s;
+  }
   SD_HIP(hipEventRecord(c->ev[2], st));
   // ---- accept / residual resample, commit, rollback
   float* p_stats = c->stats;

@@ -52,9 +52,10 @@ hipError_t launch_rope_kv(hipStream_t st, int dtype, const float* part, int S, c
                           int Hkv, int hd, int max_seq);
 // act[m,f] = silu(sum_s part[s,m,f]) * (sum_s part[s,m,ffn+f])
 hipError_t launch_silu_mul(hipStream_t st, int dtype, const float* part, int S, void* act, int M, int ffn);
-// out[(m / RS) * ld_group + (m % RS) * ld_row + n] = sum_s part[s,m,n]     (fp32 logits rows)
+// out[(m / RS) * ld_group + (m % RS) * ld_row + n] = sum_s part[s,m,n]     (fp32 logits rows);
+// with dst (device int32 [M]) row m goes to out[dst[m] * ld_row + n] instead, dst[m] < 0 drops it
 hipError_t launch_reduce_rows(hipStream_t st, const float* part, int S, float* out, int RS, int64_t ld_group,
-                              int64_t ld_row, int M, int N);
+                              int64_t ld_row, int M, int N, const int32_t* dst = nullptr);
 // z_out[m,:] = silu(sum_s part + b) (+ z_in when residual)       (acceptance head hidden layer)
 hipError_t launch_head_act(hipStream_t st, int dtype, const float* part, int S, const void* bias,
                            const void* z_in, const int* z_in_rows, void* z_out, int residual, int M, int n);
@@ -101,6 +102,11 @@ hipError_t launch_plan_draft(hipStream_t st, const SeqState& s, const RowPlan& r
 // rs = row slots per sequence (>= largest K of the round + 1)
 hipError_t launch_plan_verify(hipStream_t st, const SeqState& s, const RowPlan& rows, int B, int rs,
                               int max_seq);
+// Ragged target pass: sequence b takes ceil((K_b + 1) / RS) groups of RS row slots, packed one
+// sequence after another (n_groups in all, counted by the caller from the same K_b); dst[m] = row of
+// the [B, k_max + 1, V] logits array that slot m feeds, or -1 for a padding slot.
+hipError_t launch_plan_verify_ragged(hipStream_t st, const SeqState& s, const RowPlan& rows, int B, int RS,
+                                     int n_groups, int k_max, int max_seq, int32_t* dst);
 // draw y_i from the draft logits row, update p_hat with the head's logit, apply the stop rule
 hipError_t launch_sample_stop(hipStream_t st, int dtype, const SeqState& s, const float* q_logits,
                               int64_t ld_seq, const void* z, const int* z_rows, int z_dim, const void* w_last,

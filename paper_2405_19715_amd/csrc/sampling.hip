@@ -226,6 +226,37 @@ __global__ void plan_verify_k(SeqState s, RowPlan rows, int B, int rs, int max_s
   }
 }
 
+// Ragged target pass (several sequences, different K): groups of RS row slots, sequence after
+// sequence.  One thread per sequence; the group offset is a serial prefix count (B is small).
+__global__ void plan_verify_ragged_k(SeqState s, RowPlan rows, int B, int RS, int n_groups, int k_max, int max_seq,
+                                     int32_t* __restrict__ dst) {
+  const int b = threadIdx.x;
+  if (b >= B) return;
+  int g0 = 0;
+  for (int i = 0; i < b; ++i) g0 += s.active[i] ? (s.K[i] + RS) / RS : 0;       // ceil((K + 1) / RS)
+  if (!s.active[b]) return;
+  const int P = s.P[b], K = s.K[b];
+  const int ng = (K + RS) / RS;
+  for (int g = 0; g < ng && g0 + g < n_groups; ++g) {
+    rows.gseq[g0 + g] = b;
+    rows.gend[g0 + g] = P + min(K, g * RS + RS - 1);                           // largest position of the group + 1
+    for (int r = 0; r < RS; ++r) {
+      const int j = g * RS + r, m = (g0 + g) * RS + r;
+      if (j <= K) {
+        rows.seq[m] = b;
+        rows.pos[m] = P - 1 + j;
+        rows.tok[m] = j == 0 ? s.tokens[(size_t)b * max_seq + P - 1] : s.cand[b * CAND_LD + j - 1];
+        dst[m] = b * (k_max + 1) + j;
+      } else {
+        rows.seq[m] = -1;
+        rows.pos[m] = 0;
+        rows.tok[m] = 0;
+        dst[m] = -1;
+      }
+    }
+  }
+}
+
 // ------------------------------------------------------------------ draft sample + stop rule
 template <typename T>
 __global__ __launch_bounds__(SB) void sample_stop_k(SeqState s, const float* __restrict__ q_logits, int64_t ld_seq,
@@ -534,6 +565,14 @@ hipError_t launch_plan_draft(hipStream_t st, const SeqState& s, const RowPlan& r
 hipError_t launch_plan_verify(hipStream_t st, const SeqState& s, const RowPlan& rows, int B, int rs, int max_seq) {
   if (B < 1 || rs < 2 || rs > CAND_LD + 1 || B * rs > MAX_ROWS) return hipErrorInvalidValue;
   hipLaunchKernelGGL(plan_verify_k, dim3(B), dim3(64), 0, st, s, rows, B, rs, max_seq);
+  return hipGetLastError();
+}
+
+hipError_t launch_plan_verify_ragged(hipStream_t st, const SeqState& s, const RowPlan& rows, int B, int RS, int n_groups,
+                                     int k_max, int max_seq, int32_t* dst) {
+  if (B < 1 || B > 1024 || RS < 1 || n_groups < 1 || n_groups * RS > MAX_ROWS || !dst) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(plan_verify_ragged_k, dim3(1), dim3(((B + 63) / 64) * 64), 0, st, s, rows, B, RS, n_groups, k_max,
+                     max_seq, dst);
   return hipGetLastError();
 }
 
