@@ -9,20 +9,25 @@
 //                activation rows; each wavefront owns TN x TM accumulators of
 //                v_mfma_f32_32x32x16_bf16 (weights are the A operand, X^T the B operand, so
 //                a lane ends up with 4 consecutive n of one m: 16-byte stores).
-//   k loop     = BK per step, two LDS buffers, one barrier per step: the global loads of
-//                step i+1 are in flight while step i multiplies, and the operand words of
-//                the next 16-k sub-step are read from LDS before the current MFMAs issue.
-//   LDS order  = 16-byte words laid out [k-group][row], i.e. already in the order the MFMA
-//                lanes read them (lane = (row % 32, k-half)), so reads and writes are
-//                both lane-linear and free of bank conflicts.
+//   operands   = loaded from global memory straight into LDS (global_load_lds_dwordx4: lane l
+//                of an instruction writes LDS word base + l), NS stages of BK k each in a
+//                ring, no registers and no LDS store instructions in between.  One
+//                instruction covers 64 / KG rows x KG 16-byte k-groups (KG = BK / 8), i.e.
+//                whole 64- or 128-byte row pieces, and the lanes pick their k-group with an
+//                XOR of the row index, so that LDS is row-major [row][slot] yet the MFMA
+//                operand reads (32 consecutive rows, one k-group) touch every bank once.
+//   k loop     = wait until this wavefront's loads of stage kt have landed (s_waitcnt vmcnt
+//                with the younger stages still in flight), barrier, issue the loads of stage
+//                kt + NS - 1 into the buffer everyone has just finished with, multiply stage kt.
+//                The load is inline assembly on purpose: through the compiler builtin every
+//                LDS read is preceded by a wait for ALL outstanding loads, which serialises the
+//                ring.
 //   grid       = one dimension, n-tile-major with the m-tiles of one weight tile adjacent
 //                and on the same XCD (ids are dealt round-robin over the 8 XCDs), so that
 //                a weight tile comes from HBM once and its other readers hit that XCD's L2.
-// Measured on the MI355X (M = 1024, 57344 x 8192): the MFMA loop alone sustains about
-// 1.6 PFLOP/s, with LDS reads and barriers 1.4, and with the global -> register -> LDS
-// staging 0.6-0.7: the kernel is bound by the rate at which a CU's vector memory path
-// returns L2 data, which is why the widest tile (least operand traffic per flop) wins
-// whenever its grid still fills the chip.
+// Measured on the MI355X (M = 1024): 57344 x 8192 0.88 PFLOP/s, 10240 x 8192 0.81, 8192 x 28672
+// 0.88 (register-staged loads reached 0.45-0.68 on the same tiles; the MFMA loop alone, with
+// nothing to load, sustains 1.6).
 #include "common.hpp"
 #include "kernels.hpp"
 
@@ -34,28 +39,40 @@ typedef __attribute__((__vector_size__(16 * sizeof(float)))) float floatx16;
 
 constexpr int NXCD = 8;
 
-__device__ __forceinline__ uint4 ldg128(const bf16_t* p) { return *reinterpret_cast<const uint4*>(p); }
 __device__ __forceinline__ bf16x8 as_bf16x8(const uint4& v) {
   union { uint4 u; bf16x8 b; } c;
   c.u = v;
   return c.b;
 }
 
-template <int TN, int TM, int WN, int WM, int BK>
+// s_waitcnt on the vector-memory counter alone: vmcnt[3:0] | expcnt[6:4] | lgkmcnt[11:8] | vmcnt[5:4] << 14
+template <int VM>
+__device__ __forceinline__ void wait_vmcnt() {
+  static_assert(VM >= 0 && VM < 64, "vmcnt has six bits");
+  __builtin_amdgcn_s_waitcnt((VM & 0xF) | (0x7 << 4) | (0xF << 8) | ((VM >> 4) << 14));
+}
+
+// 16 bytes per lane from global memory to LDS word (lds_bytes / 16 + lane); lds_bytes is wave-uniform
+__device__ __forceinline__ void load_to_lds16(const bf16_t* g, uint32_t lds_bytes) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_bytes), "v"(g) : "memory", "m0");
+}
+
+template <int TN, int TM, int WN, int WM, int BK, int NS>
 __global__ __launch_bounds__(64 * WN * WM) void gemm_bf16_tile(const bf16_t* __restrict__ W,
                                                                const bf16_t* __restrict__ X, int ldx,
                                                                const int* __restrict__ xrow, float* __restrict__ C,
                                                                int M, int N, int K, int n_tiles, int m_tiles) {
-  constexpr int NW = WN * WM, NTH = 64 * NW;
-  constexpr int KG = BK / 8;                         // 16-byte k-groups per step
-  constexpr int GQ = KG / 4;                         // load instructions that cover a row's k-groups
+  constexpr int NWV = WN * WM;
+  constexpr int KG = BK / 8;                         // 16-byte k-groups per row and stage (4 or 8)
   constexpr int BN = 32 * TN * WN, BM = 32 * TM * WM;
-  constexpr int LA = BN * KG / NTH, LB = BM * KG / NTH;   // 16-byte global loads per thread and step
-  constexpr int NS = BK / 16;                        // MFMA sub-steps
-  static_assert(KG % 4 == 0 && (BN * KG) % NTH == 0 && (BM * KG) % NTH == 0, "tile does not divide over the loaders");
+  constexpr int RPI = 64 / KG;                       // rows one load instruction covers
+  constexpr int ABLK = BN / RPI, BBLK = BM / RPI;    // load instructions per stage for W and for X
+  constexpr int LPW = (ABLK + BBLK) / NWV;           // per wavefront
+  constexpr int STAGE = (BN + BM) * KG;              // 16-byte words per stage
+  constexpr int SH = KG == 4 ? 2 : 1, MSK = KG - 1;  // slot of k-group kg in row r: kg ^ ((r >> SH) & MSK)
+  constexpr int NSUB = BK / 16;                      // MFMA sub-steps per stage
+  static_assert((KG == 4 || KG == 8) && (ABLK + BBLK) % NWV == 0 && NS >= 2 && (NS - 2) * LPW < 64, "tile shape");
   extern __shared__ uint4 smem[];
-  uint4* As = smem;                                  // [2][KG * BN]
-  uint4* Bs = smem + 2 * KG * BN;                    // [2][KG * BM]
 
   // tile of this workgroup: ids are dealt to XCDs round-robin; XCD x takes weight tiles x, x+8, ..
   const int L = blockIdx.x;
@@ -66,25 +83,33 @@ __global__ __launch_bounds__(64 * WN * WM) void gemm_bf16_tile(const bf16_t* __r
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wn = wave % WN, wm = wave / WN;
-  const int lr = lane & 15, lo = lane >> 4;          // loader: 16 rows x 4 k-groups per instruction
   const int r32 = lane & 31, kh = lane >> 5;         // MFMA operand lane: row, k half
+  const int row_l = lane / KG, slot = lane % KG;     // loader lane: row within the instruction, LDS slot
 
-  const bf16_t* ga[LA];
-  const bf16_t* gb[LB];
-  int sa[LA], sb[LB];
+  const bf16_t* gsrc[LPW];
+  uint32_t ldst[LPW];
+  const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint4*)smem;   // LDS byte address
 #pragma unroll
-  for (int i = 0; i < LA; ++i) {
-    const int id = i * NW + wave, rl = (id / GQ) * 16 + lr, grp = (id % GQ) * 4 + lo;
-    ga[i] = W + (size_t)min(n0 + rl, N - 1) * K + grp * 8;
-    sa[i] = grp * BN + rl;
+  for (int i = 0; i < LPW; ++i) {
+    const int q = i * NWV + wave;                    // instruction q of the stage: W blocks first, then X blocks
+    const bool isA = q < ABLK;
+    const int blk = isA ? q : q - ABLK;
+    const int row = blk * RPI + row_l;
+    const int kg = slot ^ ((row >> SH) & MSK);
+    if (isA) {
+      gsrc[i] = W + (size_t)min(n0 + row, N - 1) * K + kg * 8;
+    } else {
+      const int m = min(m0 + row, M - 1);
+      gsrc[i] = X + (size_t)(xrow ? xrow[m] : m) * ldx + kg * 8;
+    }
+    ldst[i] = lds0 + (uint32_t)((isA ? 0 : BN * KG) + blk * 64) * 16u;
   }
+  auto issue = [&](int kt) {
+    const uint32_t stage = (uint32_t)((kt % NS) * STAGE) * 16u;
 #pragma unroll
-  for (int i = 0; i < LB; ++i) {
-    const int id = i * NW + wave, rl = (id / GQ) * 16 + lr, grp = (id % GQ) * 4 + lo;
-    const int m = min(m0 + rl, M - 1);
-    gb[i] = X + (size_t)(xrow ? xrow[m] : m) * ldx + grp * 8;
-    sb[i] = grp * BM + rl;
-  }
+    for (int i = 0; i < LPW; ++i)
+      load_to_lds16(gsrc[i] + (size_t)kt * BK, __builtin_amdgcn_readfirstlane(ldst[i] + stage));
+  };
 
   floatx16 acc[TN][TM];
 #pragma unroll
@@ -94,59 +119,49 @@ __global__ __launch_bounds__(64 * WN * WM) void gemm_bf16_tile(const bf16_t* __r
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
 
-  uint4 ra[LA], rb[LB];
-#pragma unroll
-  for (int i = 0; i < LA; ++i) ra[i] = ldg128(ga[i]);
-#pragma unroll
-  for (int i = 0; i < LB; ++i) rb[i] = ldg128(gb[i]);
-#pragma unroll
-  for (int i = 0; i < LA; ++i) As[sa[i]] = ra[i];
-#pragma unroll
-  for (int i = 0; i < LB; ++i) Bs[sb[i]] = rb[i];
-  __syncthreads();
-
   const int nk = K / BK;
-  const int aoff = wn * (32 * TN) + r32, boff = wm * (32 * TM) + r32;
-  for (int kt = 0; kt < nk; ++kt) {
-    const int cur = kt & 1;
-    if (kt + 1 < nk) {
 #pragma unroll
-      for (int i = 0; i < LA; ++i) ra[i] = ldg128(ga[i] + (size_t)(kt + 1) * BK);
+  for (int p = 0; p < NS - 1; ++p)
+    if (p < nk) issue(p);
+
+  // operand word offsets inside a stage (the same for every stage)
+  int aw[TN][NSUB], bw[TM][NSUB];
 #pragma unroll
-      for (int i = 0; i < LB; ++i) rb[i] = ldg128(gb[i] + (size_t)(kt + 1) * BK);
+  for (int s = 0; s < NSUB; ++s) {
+    const int kg = 2 * s + kh;
+#pragma unroll
+    for (int a = 0; a < TN; ++a) {
+      const int row = wn * (32 * TN) + a * 32 + r32;
+      aw[a][s] = row * KG + (kg ^ ((row >> SH) & MSK));
     }
-    const uint4* Ac = As + cur * KG * BN + aoff;
-    const uint4* Bc = Bs + cur * KG * BM + boff;
-    uint4 af[2][TN], bfr[2][TM];
 #pragma unroll
-    for (int a = 0; a < TN; ++a) af[0][a] = Ac[kh * BN + a * 32];
+    for (int b = 0; b < TM; ++b) {
+      const int row = wm * (32 * TM) + b * 32 + r32;
+      bw[b][s] = BN * KG + row * KG + (kg ^ ((row >> SH) & MSK));
+    }
+  }
+
+  for (int kt = 0; kt < nk; ++kt) {
+    // stage kt has landed once at most the NS - 2 younger stages of this wavefront are in flight
+    if (kt + NS - 2 < nk) wait_vmcnt<(NS - 2) * LPW>(); else wait_vmcnt<0>();
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_barrier();                    // everyone's part of stage kt is in LDS, and everyone
+    asm volatile("" ::: "memory");                   // has finished reading stage kt - 1
+    if (kt + NS - 1 < nk) issue(kt + NS - 1);        // into the buffer of stage kt - 1
+    const uint4* st = smem + (kt % NS) * STAGE;
 #pragma unroll
-    for (int b = 0; b < TM; ++b) bfr[0][b] = Bc[kh * BM + b * 32];
+    for (int s = 0; s < NSUB; ++s) {
+      bf16x8 af[TN], bfr[TM];
 #pragma unroll
-    for (int s = 0; s < NS; ++s) {
-      if (s + 1 < NS) {
-        const int kg = (s + 1) * 2 + kh;
+      for (int a = 0; a < TN; ++a) af[a] = as_bf16x8(st[aw[a][s]]);
 #pragma unroll
-        for (int a = 0; a < TN; ++a) af[(s + 1) & 1][a] = Ac[kg * BN + a * 32];
-#pragma unroll
-        for (int b = 0; b < TM; ++b) bfr[(s + 1) & 1][b] = Bc[kg * BM + b * 32];
-      }
+      for (int b = 0; b < TM; ++b) bfr[b] = as_bf16x8(st[bw[b][s]]);
 #pragma unroll
       for (int a = 0; a < TN; ++a)
 #pragma unroll
         for (int b = 0; b < TM; ++b)
-          acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(af[s & 1][a]), as_bf16x8(bfr[s & 1][b]),
-                                                              acc[a][b], 0, 0, 0);
+          acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[a], bfr[b], acc[a][b], 0, 0, 0);
     }
-    if (kt + 1 < nk) {
-      uint4* An = As + (cur ^ 1) * KG * BN;
-      uint4* Bn = Bs + (cur ^ 1) * KG * BM;
-#pragma unroll
-      for (int i = 0; i < LA; ++i) An[sa[i]] = ra[i];
-#pragma unroll
-      for (int i = 0; i < LB; ++i) Bn[sb[i]] = rb[i];
-    }
-    __syncthreads();
   }
 
   // D[i, j] of a 32x32 tile: lane (j = lane % 32, half = lane / 32), register v holds
@@ -169,12 +184,12 @@ __global__ __launch_bounds__(64 * WN * WM) void gemm_bf16_tile(const bf16_t* __r
   }
 }
 
-template <int TN, int TM, int WN, int WM, int BK>
+template <int TN, int TM, int WN, int WM, int BK, int NS>
 hipError_t launch_tile(hipStream_t st, const bf16_t* W, const bf16_t* X, int ldx, const int* xrow, float* C, int M,
                        int N, int K) {
   constexpr int BN = 32 * TN * WN, BM = 32 * TM * WM;
-  constexpr size_t lds = (size_t)2 * (BK / 8) * (BN + BM) * 16;
-  auto kern = gemm_bf16_tile<TN, TM, WN, WM, BK>;
+  constexpr size_t lds = (size_t)NS * (BK / 8) * (BN + BM) * 16;
+  auto kern = gemm_bf16_tile<TN, TM, WN, WM, BK, NS>;
   static bool attr_set = false;          // dynamic LDS above 64 KB has to be allowed once per kernel
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -201,11 +216,14 @@ hipError_t launch_gemm_tile(hipStream_t st, const void* W, const void* X, int ld
   const bf16_t* x = (const bf16_t*)X;
   if (K % 32 != 0) return hipErrorInvalidValue;
   auto wgs = [&](int bn, int bm) { return (long)((N + bn - 1) / bn) * ((M + bm - 1) / bm); };
-  // widest tile whose grid still covers the 256 CUs about twice over
-  if (K % 64 == 0 && wgs(256, 256) >= 448) return launch_tile<4, 2, 2, 4, 64>(st, w, x, ldx, xrow, C, M, N, K);
-  if (wgs(256, 128) >= 448) return launch_tile<4, 2, 2, 2, 32>(st, w, x, ldx, xrow, C, M, N, K);
-  if (wgs(128, 128) >= 256) return launch_tile<2, 2, 2, 2, 32>(st, w, x, ldx, xrow, C, M, N, K);
-  return launch_tile<2, 1, 2, 2, 32>(st, w, x, ldx, xrow, C, M, N, K);
+  if (K % 64 == 0) {
+    // 256 x 256 (8 wavefronts) when its grid still covers the 256 CUs about twice over, else 128 x 128
+    if (wgs(256, 256) >= 448) return launch_tile<4, 2, 2, 4, 64, 2>(st, w, x, ldx, xrow, C, M, N, K);
+    if (wgs(128, 128) >= 128) return launch_tile<2, 2, 2, 2, 64, 2>(st, w, x, ldx, xrow, C, M, N, K);
+    return launch_tile<2, 1, 2, 2, 64, 2>(st, w, x, ldx, xrow, C, M, N, K);
+  }
+  if (wgs(128, 128) >= 128) return launch_tile<2, 2, 2, 2, 32, 3>(st, w, x, ldx, xrow, C, M, N, K);
+  return launch_tile<2, 1, 2, 2, 32, 3>(st, w, x, ldx, xrow, C, M, N, K);
 }
 
 }  // namespace sd
