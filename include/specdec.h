@@ -199,7 +199,7 @@ sd_status sd_profile_read(sd_ctx *ctx, int64_t *launches, double *seconds, doubl
  * W: DEVICE [N, K] and X: DEVICE [M, K], both `dtype`; Y: DEVICE fp32 [M, N]; ws: DEVICE
  * scratch of sd_gemm_workspace_bytes(...) bytes (per-K-slice partial sums, added in
  * slice order).  1 <= M <= 160; for SD_BF16, K % 128 == 0 and N % 16 == 0, pointers
- * 16-byte aligned.  Enqueued on `hip_stream`; does not synchronise. */
+ * 16-byte aligned (more than 32 rows are handed to the tiled kernel below).  Enqueued on `hip_stream`; does not synchronise. */
 sd_status sd_gemm_skinny(int32_t dtype, const void *W_dev, const void *X_dev, int32_t M, int32_t N, int32_t K,
                          float *Y_dev, void *ws_dev, void *hip_stream);
 
@@ -246,14 +246,17 @@ sd_status sd_trainer_read(sd_trainer *tr, int32_t layer, int32_t what, float *ho
  * like sd_head.W / sd_head.b (so that a head for sd_create can be built from them). */
 sd_status sd_trainer_export(sd_trainer *tr, int32_t dtype, void *const *W_out_dev, void *const *b_out_dev);
 
-/* The large-M GEMM of the prompt pass (both models ingest the prefix before the first
- * round of Algorithm 2; with hundreds of rows per weight this is bound by the matrix
- * cores, not by the weight stream): Y[m, n] = sum_k X[m, k] * W[n, k], bf16 in, fp32 out.
- * W: DEVICE bf16 [N, K]; X: DEVICE bf16 [M, K]; Y: DEVICE fp32 [M, N].  M >= 1,
- * K % 32 == 0, N % 4 == 0, pointers 16-byte aligned; SD_EDEVICE otherwise.  Enqueued on
- * `hip_stream`; does not synchronise; no workspace. */
+/* The tiled GEMM of the prompt pass and of wide (batched) target passes: both models ingest
+ * the prefix before the first round of Algorithm 2, and with hundreds of rows per weight the
+ * product is bound by the matrix cores, not by the weight stream.  Y[m, n] = sum_k X[m, k] *
+ * W[n, k], bf16 in, fp32 out.  W: DEVICE bf16 [N, K]; X: DEVICE bf16 [M, K]; Y: DEVICE fp32
+ * [M, N]; ws: DEVICE scratch of sd_gemm_tile_workspace_bytes(M, N, K) bytes (0 for large M: may
+ * then be null; for M <= 192 the product may be split along K to fill the chip and the slices
+ * are added in slice order).  1 <= M <= 1024, K % 32 == 0, N % 4 == 0, pointers 16-byte
+ * aligned; SD_EINVAL / SD_EDEVICE otherwise.  Enqueued on `hip_stream`; does not synchronise. */
+int64_t sd_gemm_tile_workspace_bytes(int32_t M, int32_t N, int32_t K);
 sd_status sd_gemm_tile(const void *W_dev, const void *X_dev, int32_t M, int32_t N, int32_t K, float *Y_dev,
-                       void *hip_stream);
+                       void *workspace_dev, void *hip_stream);
 int64_t sd_gemm_workspace_bytes(int32_t dtype, int32_t M, int32_t N, int32_t K);
 
 const char *sd_strerror(sd_status s);

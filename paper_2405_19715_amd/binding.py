@@ -87,7 +87,9 @@ _PROTOS = {
     "sd_trainer_predict": (C.c_int32, [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p]),
     "sd_trainer_read": (C.c_int32, [C.c_void_p, C.c_int32, C.c_int32, _f32p]),
     "sd_trainer_export": (C.c_int32, [C.c_void_p, C.c_int32, _vpp, _vpp]),
-    "sd_gemm_tile": (C.c_int32, [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]),
+    "sd_gemm_tile": (C.c_int32, [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p,
+                                 C.c_void_p]),
+    "sd_gemm_tile_workspace_bytes": (C.c_int64, [C.c_int32, C.c_int32, C.c_int32]),
     "sd_gemm_workspace_bytes": (C.c_int64, [C.c_int32, C.c_int32, C.c_int32, C.c_int32]),
     "sd_strerror": (C.c_char_p, [C.c_int32]),
     "sd_version": (C.c_char_p, []),
@@ -298,7 +300,12 @@ def sd_gemm_tile(W: torch.Tensor, X: torch.Tensor, out: Optional[torch.Tensor] =
     (N, K), (M, K2) = W.shape, X.shape
     assert K == K2
     Y = out if out is not None else torch.empty((M, N), dtype=torch.float32, device=W.device)
-    _check(lib.sd_gemm_tile(W.data_ptr(), X.data_ptr(), M, N, K, Y.data_ptr(), _stream_ptr()), "sd_gemm_tile")
+    nbytes = lib.sd_gemm_tile_workspace_bytes(M, N, K)
+    if nbytes < 0:
+        raise SpecDecError(SD_EINVAL, "sd_gemm_tile_workspace_bytes")
+    ws = torch.empty(max(nbytes, 16), dtype=torch.uint8, device=W.device)
+    _check(lib.sd_gemm_tile(W.data_ptr(), X.data_ptr(), M, N, K, Y.data_ptr(), ws.data_ptr(), _stream_ptr()),
+           "sd_gemm_tile")
     return Y
 
 

@@ -181,9 +181,11 @@ size_t part_floats(const sd_ctx* c) {
                               {2 * m.d_ffn, m.d_model},               {m.d_model, m.d_ffn},
                               {m.vocab, m.d_model}};
     for (auto& sh : shapes) best = std::max(best, part_floats_for(m.dtype, c->max_rows, sh[0], sh[1]));
-    // the prompt pass of a bf16 model writes whole [rows, N] products (no K slices)
+    // the prompt pass of a bf16 model: up to prefill_rows rows through the tiled kernel
     if (m.dtype == SD_BF16)
-      for (int i = 0; i < 4; ++i) best = std::max(best, (size_t)c->prefill_rows * shapes[i][0]);
+      for (int i = 0; i < 4; ++i)
+        for (int M = MAX_ROWS + 1; M <= c->prefill_rows; ++M)
+          best = std::max(best, (size_t)gemm_splits(m.dtype, M, shapes[i][0], shapes[i][1]) * M * shapes[i][0]);
   }
   if (c->head.present)
     for (int j = 0; j + 1 < c->head.n_layers; ++j)
@@ -231,9 +233,9 @@ sd_status gemm(sd_ctx* c, const ModelRt& rt, const void* W, const void* X, int l
 // final-RMSNorm rows in c->xn.  If logits_out != null, runs the LM head over n_lm rows
 // (gathered through lm_rows when non-null); LM row i = (group i / lm_rs, slot i % lm_rs) goes
 // to logits_out[group * ld_group + slot * ld_row + v].
-// tile = true (prompt pass of a bf16 model, one row group): the four layer GEMMs go through
-// the large-M tiled kernel, which writes whole products (one "slice"), and attention
-// through its unsplit variant; M may then reach c->prefill_rows.
+// tile = true (prompt pass of a bf16 model, one row group of more than 32 rows): M may reach
+// c->prefill_rows; the GEMMs then go through the tiled kernel (launch_gemm picks it by M) and
+// attention through its unsplit variant.
 sd_status forward(sd_ctx* c, ModelRt& rt, int M, int RS, int max_kv_len, const int* lm_rows, int n_lm,
                   float* logits_out, int lm_rs, int64_t ld_group, int64_t ld_row, bool profile, bool tile = false,
                   const int32_t* lm_dst = nullptr) {
@@ -243,11 +245,9 @@ sd_status forward(sd_ctx* c, ModelRt& rt, int M, int RS, int max_kv_len, const i
   if (tile && (dt != SD_BF16 || RS != M || logits_out)) return SD_EINVAL;
   if (!tile && M > MAX_ROWS) return SD_EINVAL;
   auto mm = [&](const void* W, const void* X, int ldx, int N, int K, int prof_kind) -> sd_status {
-    if (!tile) return gemm(c, rt, W, X, ldx, nullptr, M, N, K, prof_kind);
-    SD_HIP(launch_gemm_tile(st, W, X, ldx, nullptr, c->part, M, N, K));
-    return SD_OK;
+    return gemm(c, rt, W, X, ldx, nullptr, M, N, K, prof_kind);
   };
-  auto slices = [&](int N, int K) { return tile ? 1 : gemm_splits(dt, M, N, K); };
+  auto slices = [&](int N, int K) { return gemm_splits(dt, M, N, K); };
   SD_HIP(launch_embed_norm(st, dt, m.tok_emb, rt.na[0], m.rms_eps, c->rows.tok, c->x, c->xn, c->ssq, M, d, m.vocab));
   for (int l = 0; l < m.n_layers; ++l) {
     const bool pr = profile && c->prof_every > 0 && (l % c->prof_every) == 0;
@@ -863,9 +863,20 @@ sd_status sd_gemm_skinny(int32_t dtype, const void* W, const void* X, int32_t M,
   return SD_OK;
 }
 
-sd_status sd_gemm_tile(const void* W, const void* X, int32_t M, int32_t N, int32_t K, float* Y, void* hip_stream) {
-  if (!W || !X || !Y) return SD_EINVAL;
-  SD_HIP(launch_gemm_tile((hipStream_t)hip_stream, W, X, K, nullptr, Y, M, N, K));
+int64_t sd_gemm_tile_workspace_bytes(int32_t M, int32_t N, int32_t K) {
+  if (M < 1 || M > MAX_PREFILL_ROWS || N < 1 || K < 32 || K % 32 != 0) return -1;
+  const int S = gemm_tile_splits(M, N, K);
+  return S > 1 ? (int64_t)S * M * N * 4 : 0;
+}
+
+sd_status sd_gemm_tile(const void* W, const void* X, int32_t M, int32_t N, int32_t K, float* Y, void* ws,
+                       void* hip_stream) {
+  if (!W || !X || !Y || M < 1 || M > MAX_PREFILL_ROWS || N < 1 || K < 32 || K % 32 != 0) return SD_EINVAL;
+  hipStream_t st = (hipStream_t)hip_stream;
+  const int S = gemm_tile_splits(M, N, K);
+  if (S > 1 && !ws) return SD_EINVAL;
+  SD_HIP(launch_gemm_tile(st, W, X, K, nullptr, S > 1 ? (float*)ws : Y, M, N, K));
+  if (S > 1) SD_HIP(launch_reduce_rows(st, (const float*)ws, S, Y, M, 0, N, M, N));
   return SD_OK;
 }
 

@@ -278,22 +278,29 @@ hipError_t launch_stream(hipStream_t st, const bf16_t* W, const bf16_t* X, int l
   return hipGetLastError();
 }
 
+constexpr int STREAM_MAX_ROWS = 32;      // above this the X slice in LDS gets short and the tiled kernel wins
+
+bool use_tile(int M, int N, int K) { return M > STREAM_MAX_ROWS && K % 32 == 0 && N % 4 == 0; }
+
 }  // namespace
 
 int gemm_splits(int dtype, int M, int N, int K) {
   if (dtype == DT_F32) return 1;
+  if (use_tile(M, N, K)) return gemm_tile_splits(M, N, K);
   return plan_bf16(M, N, K).S;
 }
 
 hipError_t launch_gemm(hipStream_t st, int dtype, const void* W, const void* X, int ldx, const int* xrow,
                        float* part, int M, int N, int K) {
-  if (!W || !X || !part || M < 1 || M > MAX_ROWS || N < 1 || K < 1 || ldx < K) return hipErrorInvalidValue;
+  if (!W || !X || !part || M < 1 || M > MAX_PREFILL_ROWS || N < 1 || K < 1 || ldx < K) return hipErrorInvalidValue;
+  if (M > MAX_ROWS && !(dtype == DT_BF16 && use_tile(M, N, K))) return hipErrorInvalidValue;
   if (dtype == DT_F32) {
     hipLaunchKernelGGL(gemm_f32, dim3((N + 3) / 4), dim3(256), 0, st, (const float*)W, (const float*)X, ldx,
                        xrow, part, M, N, K);
     return hipGetLastError();
   }
   if (dtype != DT_BF16) return hipErrorInvalidValue;
+  if (use_tile(M, N, K)) return launch_gemm_tile(st, W, X, ldx, xrow, part, M, N, K);
   // 16-byte loads along K, 16-row tiles along N, 16-byte aligned rows
   if (K % KSTEP != 0 || N % 16 != 0 || ldx % 8 != 0) return hipErrorInvalidValue;
   if ((reinterpret_cast<uintptr_t>(W) | reinterpret_cast<uintptr_t>(X) | reinterpret_cast<uintptr_t>(part)) & 15)

@@ -61,7 +61,8 @@ template <int TN, int TM, int WN, int WM, int BK, int NS>
 __global__ __launch_bounds__(64 * WN * WM) void gemm_bf16_tile(const bf16_t* __restrict__ W,
                                                                const bf16_t* __restrict__ X, int ldx,
                                                                const int* __restrict__ xrow, float* __restrict__ C,
-                                                               int M, int N, int K, int n_tiles, int m_tiles) {
+                                                               int M, int N, int K, int n_tiles, int m_tiles,
+                                                               int steps_per) {
   constexpr int NWV = WN * WM;
   constexpr int KG = BK / 8;                         // 16-byte k-groups per row and stage (4 or 8)
   constexpr int BN = 32 * TN * WN, BM = 32 * TM * WM;
@@ -119,10 +120,12 @@ __global__ __launch_bounds__(64 * WN * WM) void gemm_bf16_tile(const bf16_t* __r
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
 
-  const int nk = K / BK;
+  // K slice of this workgroup (blockIdx.y): stages k_beg .. nk - 1; slice s writes C[s][M][N]
+  const int k_beg = blockIdx.y * steps_per, nk = min(K / BK, k_beg + steps_per);
+  C += (size_t)blockIdx.y * M * N;
 #pragma unroll
   for (int p = 0; p < NS - 1; ++p)
-    if (p < nk) issue(p);
+    if (k_beg + p < nk) issue(k_beg + p);
 
   // operand word offsets inside a stage (the same for every stage)
   int aw[TN][NSUB], bw[TM][NSUB];
@@ -141,7 +144,7 @@ __global__ __launch_bounds__(64 * WN * WM) void gemm_bf16_tile(const bf16_t* __r
     }
   }
 
-  for (int kt = 0; kt < nk; ++kt) {
+  for (int kt = k_beg; kt < nk; ++kt) {
     // stage kt has landed once at most the NS - 2 younger stages of this wavefront are in flight
     if (kt + NS - 2 < nk) wait_vmcnt<(NS - 2) * LPW>(); else wait_vmcnt<0>();
     asm volatile("" ::: "memory");
@@ -186,7 +189,7 @@ __global__ __launch_bounds__(64 * WN * WM) void gemm_bf16_tile(const bf16_t* __r
 
 template <int TN, int TM, int WN, int WM, int BK, int NS>
 hipError_t launch_tile(hipStream_t st, const bf16_t* W, const bf16_t* X, int ldx, const int* xrow, float* C, int M,
-                       int N, int K) {
+                       int N, int K, int S) {
   constexpr int BN = 32 * TN * WN, BM = 32 * TM * WM;
   constexpr size_t lds = (size_t)NS * (BK / 8) * (BN + BM) * 16;
   auto kern = gemm_bf16_tile<TN, TM, WN, WM, BK, NS>;
@@ -199,31 +202,65 @@ hipError_t launch_tile(hipStream_t st, const bf16_t* W, const bf16_t* X, int ldx
   }
   const int n_tiles = (N + BN - 1) / BN, m_tiles = (M + BM - 1) / BM;
   const int n_tiles_pad = (n_tiles + NXCD - 1) / NXCD * NXCD;
-  hipLaunchKernelGGL(kern, dim3(n_tiles_pad * m_tiles), dim3(64 * WN * WM), lds, st, W, X, ldx, xrow, C, M, N, K,
-                     n_tiles, m_tiles);
+  const int nk = K / BK, steps_per = (nk + S - 1) / S;
+  if ((S - 1) * steps_per >= nk) return hipErrorInvalidValue;      // every slice must own at least one stage
+  hipLaunchKernelGGL(kern, dim3(n_tiles_pad * m_tiles, S), dim3(64 * WN * WM), lds, st, W, X, ldx, xrow, C, M, N, K,
+                     n_tiles, m_tiles, steps_per);
   return hipGetLastError();
+}
+
+// Tile shape and K split for an (M, N, K) product.  Large M (prompt pass): the widest tile whose grid
+// covers the chip about twice, no split.  32 < M <= 192 (a batched target pass): one m-tile that holds
+// every row, so each weight is read once, and as many K slices as it takes to put about 384
+// workgroups on the 256 CUs; the few partial-sum slices are added by the consumer like the streaming kernel's.
+struct TilePlan { int kind, S; };          // kind: 0 = 256x256, 1 = 128x128, 2 = 128x64, 3 = 128x192
+
+TilePlan plan_tile(int M, int N, int K) {
+  const int bk = (K % 64 == 0) ? 64 : 32;
+  auto wgs = [&](int bn, int bm) { return (long)((N + bn - 1) / bn) * ((M + bm - 1) / bm); };
+  int kind;
+  if (M <= 64) kind = 2;
+  else if (M <= 128) kind = 1;
+  else if (M <= 192 && bk == 64) kind = 3;
+  else if (bk == 64 && wgs(256, 256) >= 448) kind = 0;
+  else kind = 1;
+  const int bn = kind == 0 ? 256 : 128, bm = kind == 0 ? 256 : kind == 1 ? 128 : kind == 2 ? 64 : 192;
+  const long w = wgs(bn, bm);
+  int S = 1;
+  constexpr int target = 384;                        // workgroups wanted: 1.5 per CU measured best (256 .. 512 tried)
+  if (M <= 192 && w < target - 32) {
+    S = (int)((target + w - 1) / w);
+    const int nk = K / bk;
+    while (S > 1 && nk / S < 8) --S;                 // keep slices long enough to amortise the pipeline fill
+    const int per = (nk + S - 1) / S;
+    S = (nk + per - 1) / per;                        // no empty slice
+  }
+  return TilePlan{kind, S};
 }
 
 }  // namespace
 
+int gemm_tile_splits(int M, int N, int K) { return plan_tile(M, N, K).S; }
+
 hipError_t launch_gemm_tile(hipStream_t st, const void* W, const void* X, int ldx, const int* xrow, float* C, int M,
                             int N, int K) {
-  if (!W || !X || !C || M < 1 || N < 1 || K < 32 || ldx < K || ldx % 8 != 0 || N % 4 != 0)
+  if (!W || !X || !C || M < 1 || N < 1 || K < 32 || K % 32 != 0 || ldx < K || ldx % 8 != 0 || N % 4 != 0)
     return hipErrorInvalidValue;
   if ((reinterpret_cast<uintptr_t>(W) | reinterpret_cast<uintptr_t>(X) | reinterpret_cast<uintptr_t>(C)) & 15)
     return hipErrorInvalidValue;
   const bf16_t* w = (const bf16_t*)W;
   const bf16_t* x = (const bf16_t*)X;
-  if (K % 32 != 0) return hipErrorInvalidValue;
-  auto wgs = [&](int bn, int bm) { return (long)((N + bn - 1) / bn) * ((M + bm - 1) / bm); };
+  const TilePlan p = plan_tile(M, N, K);
   if (K % 64 == 0) {
-    // 256 x 256 (8 wavefronts) when its grid still covers the 256 CUs about twice over, else 128 x 128
-    if (wgs(256, 256) >= 448) return launch_tile<4, 2, 2, 4, 64, 2>(st, w, x, ldx, xrow, C, M, N, K);
-    if (wgs(128, 128) >= 128) return launch_tile<2, 2, 2, 2, 64, 2>(st, w, x, ldx, xrow, C, M, N, K);
-    return launch_tile<2, 1, 2, 2, 64, 2>(st, w, x, ldx, xrow, C, M, N, K);
+    switch (p.kind) {
+      case 0: return launch_tile<4, 2, 2, 4, 64, 2>(st, w, x, ldx, xrow, C, M, N, K, p.S);
+      case 1: return launch_tile<2, 2, 2, 2, 64, 2>(st, w, x, ldx, xrow, C, M, N, K, p.S);
+      case 2: return launch_tile<2, 1, 2, 2, 64, 2>(st, w, x, ldx, xrow, C, M, N, K, p.S);
+      default: return launch_tile<2, 3, 2, 2, 64, 2>(st, w, x, ldx, xrow, C, M, N, K, p.S);
+    }
   }
-  if (wgs(128, 128) >= 128) return launch_tile<2, 2, 2, 2, 32, 3>(st, w, x, ldx, xrow, C, M, N, K);
-  return launch_tile<2, 1, 2, 2, 32, 3>(st, w, x, ldx, xrow, C, M, N, K);
+  if (p.kind == 2) return launch_tile<2, 1, 2, 2, 32, 3>(st, w, x, ldx, xrow, C, M, N, K, p.S);
+  return launch_tile<2, 2, 2, 2, 32, 3>(st, w, x, ldx, xrow, C, M, N, K, p.S);
 }
 
 }  // namespace sd

@@ -16,14 +16,17 @@ constexpr int MAX_PREFILL_ROWS = 1024; // most rows of one prompt-pass chunk (ti
 // W: [N, K] row-major in dtype; X: [M, K] rows (row stride ldx elements) in dtype,
 // optionally gathered through xrow (device int32 [M], may be null).
 // The number of K-slices is gemm_splits(dtype, M, N, K); consumers add the slices
-// in slice order.
+// in slice order.  bf16 products with more than 32 rows go through the tiled kernel
+// (launch_gemm_tile), which reads every weight once however many rows there are.
 int gemm_splits(int dtype, int M, int N, int K);
 hipError_t launch_gemm(hipStream_t st, int dtype, const void* W, const void* X, int ldx, const int* xrow,
                        float* part, int M, int N, int K);
 
-// ---------------------------------------------------------------- large-M GEMM (prompt pass)
-// C[m, n] = sum_k X[m, k] * W[n, k], bf16 in, fp32 out [M, N]; X rows optionally gathered
-// through xrow.  Any M >= 1; K % 32 == 0, N % 4 == 0, ldx % 8 == 0, 16-byte aligned pointers.
+// ---------------------------------------------------------------- tiled GEMM (prompt pass, wide target passes)
+// C[s, m, n] = sum over the s-th K-slice of X[m, k] * W[n, k], bf16 in, fp32 out [S][M][N] with
+// S = gemm_tile_splits(M, N, K) (1 for large M); X rows optionally gathered through xrow.
+// Any M >= 1; K % 32 == 0, N % 4 == 0, ldx % 8 == 0, 16-byte aligned pointers.
+int gemm_tile_splits(int M, int N, int K);
 hipError_t launch_gemm_tile(hipStream_t st, const void* W, const void* X, int ldx, const int* xrow, float* C,
                             int M, int N, int K);
 
