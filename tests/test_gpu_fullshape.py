@@ -77,3 +77,58 @@ def test_round_at_full_layer_shapes_matches_oracle():
             assert st["kv_len_draft"] == min(len(x) - 1, len(x) - 1 - (n + 1) + K)
     finally:
         ctx.close()
+
+
+def test_batched_rounds_at_full_layer_shapes_match_oracle():
+    """Three sequences with ragged prompts at the full layer shapes: the first round runs every
+    sequence to K_max (h = 1: 3 x 17 = 51 target rows, more than the streaming kernel takes, so
+    the tiled kernel with K slices serves the target pass), the second stops adaptively
+    (ragged K_b: packed row groups).  Logits rows against the oracle's teacher-forced forward,
+    accept / resample decisions replayed on the HIP path's own rows."""
+    from dataclasses import replace
+    from paper_2405_19715_amd import binding as B
+    dev = "cuda:0"
+    ts, ds = replace(synth.LLAMA_70B, n_layers=2), replace(synth.LLAMA_7B, n_layers=2)
+    t = synth.make_model(ts, 11, device=dev, dtype=torch.bfloat16)
+    d = synth.make_model(ds, 12, device=dev, dtype=torch.bfloat16)
+    h = synth.make_head([4096, 4096, 4096, 4096, 1], 13, device=dev, dtype=torch.bfloat16, residual=True)
+    k_max, seed, nb = 16, 6, 3
+    prompts = [synth.make_prompt(n, 32000, 20 + n) for n in (24, 57, 90)]
+    ctx = B.Context(t, d, h, batch=nb, max_seq=192, k_max=k_max)
+    try:
+        ot, od, xs = [], [], []
+        for b in range(nb):
+            ctx.sd_prefill(b, prompts[b])
+            ot.append(CachedForward(oracle_model(t)))
+            od.append(CachedForward(oracle_model(d)))
+            ot[b].extend(prompts[b][:-1])
+            od[b].extend(prompts[b][:-1])
+            xs.append(list(prompts[b]))
+        for rho, hh in enumerate((1.0, 0.7)):
+            res = ctx.specdec_round(B.make_params(h=hh, seed=seed))
+            if rho == 0:
+                assert all(r["K"] == k_max for r in res)
+            for b in range(nb):
+                g = res[b]
+                K = g["K"]
+                q, p, _ = ctx.sd_last_round_rows(b, K)
+                q, p = q.numpy(), p.numpy()
+                x = xs[b]
+                want_q = od[b].extend(x[od[b].len:] + g["cand"][:-1])[0][-K:]
+                want_p = ot[b].extend(x[ot[b].len:] + g["cand"])[0][-(K + 1):]
+                for got, want in ((p, want_p), (q, want_q)):
+                    err = (np.abs(got - want).max(-1) / np.abs(want).max(-1)).max()
+                    assert err < 2e-2, (rho, b, err)
+                o = sampling.accept_resample(p, q, g["cand"], K, seed=seed, rnd=rho, seq=b)
+                if o["n"] != g["n"]:
+                    i = min(o["n"], g["n"]) + 1
+                    assert abs(o["r"][i - 1] - o["ratio"][i - 1]) < 1e-3
+                    o = sampling.accept_resample(p, q, g["cand"], K, seed=seed, rnd=rho, seq=b,
+                                                 forced={("accept", i): 1 if g["n"] >= i else 0})
+                assert o["n"] == g["n"]
+                assert o["token"] == g["tokens"][-1] or o["margin"] < 1e-5
+                x += g["tokens"]
+                ot[b].truncate(len(x) - 1)
+                od[b].truncate(min(len(x) - 1, od[b].len))
+    finally:
+        ctx.close()
