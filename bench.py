@@ -281,7 +281,10 @@ def _sweep(args):
     tgt = synth.make_model(shape, args.seed, device=dev, dtype=torch.bfloat16)
     synth.damp_tail(tgt, n_draft, gain)
     drf = synth.make_perturbed_draft(tgt, n_draft, args.seed + 1, std=std)
-    head = synth.make_head([shape.d_model] * 4 + [1], args.seed + 2, device=dev, dtype=torch.bfloat16, residual=True)
+    if args.hard_frac > 0:
+        synth.mark_hard_tokens(tgt, drf, args.hard_frac, args.hard_marker, args.hard_c, args.seed + 9)
+    head = synth.make_head([shape.d_model] * (args.head_layers + 1) + [1], args.seed + 2, device=dev,
+                           dtype=torch.bfloat16, residual=True)
     prompt = synth.make_prompt(n_prompt, shape.vocab, args.seed + 3)
     train_info = None
     if args.train_head > 0:
@@ -341,7 +344,9 @@ def _sweep(args):
         metric="generated tokens/s (fixed-K and threshold sweep, aligned 7B-shaped pair)", value=best["tokens_per_s"],
         unit="tokens/s", n_gpus=1, steps=len(rows), warmup=0, ms_per_step=None, higher_is_better=True,
         scaling="weak", vs_baseline=None, dtype="bf16", data="synthetic",
-        config=dict(workload=f"aligned pair: llama2-7b-shaped target with layers {n_draft}.. damped x{gain}, draft = "
+        config=dict(workload=f"aligned pair: llama2-7b-shaped target with layers {n_draft}.. "
+                             f"damped x{gain}, "
+                             f"{'hard-token subset ' + str(args.hard_frac) + ' (c ' + str(args.hard_c) + '), ' if args.hard_frac > 0 else ''}draft = "
                              f"its first {n_draft} layers + N(0,{std}), random-init head, batch 1, prompt {n_prompt}, "
                              f"{n_gen} tokens per setting, top_k {args.top_k}", best=dict(mode=best["mode"], K=best["K"], h=best["h"]),
                     head="trained" if train_info else "random-init", head_training=train_info),
@@ -364,6 +369,15 @@ def main():
     ap.add_argument("--sweep", action="store_true", help="fixed-K / threshold sweep on an aligned synthetic pair")
     ap.add_argument("--sweep-tokens", type=int, default=256)
     ap.add_argument("--align-std", type=float, default=0.001)
+    ap.add_argument("--learnable", action="store_true",
+                    help="with --sweep: the pair on which a trained head helps (marked hard-token subset, linear head, "
+                         "48 training prompts); same as --hard-frac 0.3 --hard-c 1 --align-std 0.0005 --head-layers 0 "
+                         "--train-head 48 --train-epochs 30 --lr 1e-3 --sweep-tokens 384")
+    ap.add_argument("--hard-frac", type=float, default=0.0,
+                    help="with --sweep: mark this fraction of the vocabulary as tokens the draft mis-scores")
+    ap.add_argument("--hard-marker", type=float, default=30.0)
+    ap.add_argument("--hard-c", type=float, default=2.0)
+    ap.add_argument("--head-layers", type=int, default=3, help="with --sweep: hidden layers D of the head (0 = linear)")
     ap.add_argument("--train-head", type=int, default=0, metavar="PROMPTS",
                     help="with --sweep: first train the acceptance head on this many synthetic prompts")
     ap.add_argument("--train-epochs", type=int, default=3)
@@ -375,6 +389,9 @@ def main():
     if args.gpus != 1:
         raise SystemExit("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)")
     if args.sweep:
+        if args.learnable:
+            args.hard_frac, args.hard_c, args.align_std, args.head_layers = 0.3, 1.0, 0.0005, 0
+            args.train_head, args.train_epochs, args.lr, args.sweep_tokens = 48, 30, 1e-3, 384
         return _sweep(args)
     if args.workload == "accept":
         return _accept_bench(args)

@@ -127,6 +127,31 @@ def damp_tail(model: Dict, first: int, gain: float) -> None:
             lay[name].mul_(gain)
 
 
+def mark_hard_tokens(target: Dict, draft: Dict, frac: float, marker: float, c: float, seed: int) -> torch.Tensor:
+    """Give the pair a marked subset H of the vocabulary (a fraction `frac` of the token ids) on
+    which the draft's output layer disagrees with the target's: the draft gets its own LM head
+    whose rows in H carry extra N(0, c^2 / d) noise (a logit shift of about N(0, c^2) per
+    context), and the shared embedding of every token in H gets `marker` times one fixed unit
+    vector, so that the final embedding of a row whose input token is in H says so.  Whether a
+    drafted token will be accepted then depends on the token, and the token is visible to an
+    acceptance-prediction head.  Returns the boolean mask of H."""
+    dev, dt = target["tok_emb"].device, target["dtype"]
+    V, d = target["tok_emb"].shape
+    g = _gen(seed, dev)
+    hard = torch.rand((V,), generator=g, device=dev) < frac
+    u = torch.randn((d,), generator=g, device=dev, dtype=torch.float32)
+    u = u / u.norm()
+    emb = target["tok_emb"].float()
+    emb[hard] += marker * u
+    target["tok_emb"].copy_(emb.to(dt))
+    draft["tok_emb"] = target["tok_emb"]
+    lm = target["lm_head"].float()
+    noise = torch.randn((int(hard.sum()), d), generator=g, device=dev, dtype=torch.float32) * (c / math.sqrt(d))
+    lm[hard] += noise
+    draft["lm_head"] = lm.to(dt).contiguous()
+    return hard
+
+
 def make_head(dims: List[int], seed: int, device="cpu", dtype=torch.float32, residual: bool = False,
               out_bias: float = 1.386, std: float = 0.02) -> Dict:
     """Acceptance-head weights: len(dims)-1 layers, dims[-1] == 1.  The output bias
