@@ -73,7 +73,7 @@ __device__ float block_kth_largest(const float* __restrict__ l, int V, int k, in
 }
 
 // Inverse-CDF draw over v in [0, V) with weight f(v) >= 0; returns -1 when the total
-// mass is not positive.  sh_w: SB/64 floats, sh_res: 1 int (sh_incl is unused scratch).
+// mass is not positive.  sh_w: SB/64 floats, sh_res: 1 int.
 //
 // The cumulative sum runs in index order, but it is not formed left to right by one
 // thread: wavefront w owns the contiguous range [w CW, (w+1) CW), walks it in rows of 256
@@ -82,8 +82,7 @@ __device__ float block_kth_largest(const float* __restrict__ l, int V, int k, in
 // wavefront its total; the wavefront whose range contains u * S repeats its walk with
 // exactly the same additions to find the row, the lane and the element.
 template <typename F>
-__device__ int block_sample(F f, int V, float u, float* sh_incl, float* sh_w, int* sh_res) {
-  (void)sh_incl;
+__device__ int block_sample(F f, int V, float u, float* sh_w, int* sh_res) {
   const int t = threadIdx.x, lane = t & 63, w = t >> 6;
   constexpr int NW = SB / 64;
   const int CW = (((V + NW - 1) / NW) + 255) & ~255;            // elements per wavefront, whole rows
@@ -263,7 +262,6 @@ __global__ __launch_bounds__(SB) void sample_stop_k(SeqState s, const float* __r
                                                     const T* __restrict__ z, const int* __restrict__ z_rows, int z_dim,
                                                     const T* __restrict__ w_last, const T* __restrict__ b_last,
                                                     int have_head, DecodeParams p, int V, int step) {
-  __shared__ float sh_incl[SB];
   __shared__ float sh_w[SB / 64];
   __shared__ int sh_i[SB / 64];
   __shared__ int sh_res;
@@ -289,7 +287,7 @@ __global__ __launch_bounds__(SB) void sample_stop_k(SeqState s, const float* __r
     const float mx = am.v, inv_t = 1.0f / p.temperature;
     const float thr = (p.top_k > 0 && p.top_k < V) ? block_kth_largest(l, V, p.top_k, sh_i) : -INFINITY;
     const float u = philox_uniform(p.seed, (uint32_t)step, (uint32_t)s.round[b], (uint32_t)b, STREAM_DRAFT);
-    y = block_sample([&](int v) { return l[v] >= thr ? expf((l[v] - mx) * inv_t) : 0.f; }, V, u, sh_incl, sh_w,
+    y = block_sample([&](int v) { return l[v] >= thr ? expf((l[v] - mx) * inv_t) : 0.f; }, V, u, sh_w,
                      &sh_res);
     if (y < 0) y = am.i;                // only reachable with non-finite logits
   }
@@ -299,7 +297,7 @@ __global__ __launch_bounds__(SB) void sample_stop_k(SeqState s, const float* __r
   if (have_head && step > 1) {
     const T* zr = z + (size_t)(z_rows ? z_rows[b] : b) * z_dim;
     for (int i = threadIdx.x; i < z_dim; i += SB) dot = fmaf(Elem<T>::ld(zr + i), Elem<T>::ld(w_last + i), dot);
-    dot = block_sum(dot, sh_incl);
+    dot = block_sum(dot, sh_w);
   }
   if (threadIdx.x == 0) {
     float ph = s.p_hat[b];
@@ -385,7 +383,6 @@ __global__ __launch_bounds__(SB) void row_stats_k(RowSet A, RowSet Bq, const int
 __global__ __launch_bounds__(SB) void label_k(const float* __restrict__ p_logits, const float* __restrict__ q_logits,
                                               int V, float inv_t, int top_k, uint64_t seed, int slot0, int example,
                                               int32_t* __restrict__ Y, float* __restrict__ P) {
-  __shared__ float sh_incl[SB];
   __shared__ float sh_w[SB / 64];
   __shared__ int sh_i[SB / 64];
   __shared__ int sh_res;
@@ -400,8 +397,7 @@ __global__ __launch_bounds__(SB) void label_k(const float* __restrict__ p_logits
   const float qmx = am.v;
   const float qthr = warp ? block_kth_largest(lq, V, top_k, sh_i) : -INFINITY;
   const float u = philox_uniform(seed, (uint32_t)(slot0 + i), (uint32_t)example, 0u, 3u);
-  const int y = block_sample([&](int v) { return lq[v] >= qthr ? expf((lq[v] - qmx) * inv_t) : 0.f; }, V, u, sh_incl,
-                             sh_w, &sh_res);
+  const int y = block_sample([&](int v) { return lq[v] >= qthr ? expf((lq[v] - qmx) * inv_t) : 0.f; }, V, u, sh_w, &sh_res);
   __syncthreads();
   float local = 0.f;
   for (int v = threadIdx.x; v < V; v += SB) local += lq[v] >= qthr ? expf((lq[v] - qmx) * inv_t) : 0.f;
@@ -442,7 +438,6 @@ __global__ __launch_bounds__(SB) void accept_k(const float* __restrict__ p_logit
                                                int round_const, DecodeParams p, int Kmax, int V,
                                                int32_t* __restrict__ n_out, int32_t* __restrict__ tok_out,
                                                uint8_t* __restrict__ flags, int flags_ld) {
-  __shared__ float sh_incl[SB];
   __shared__ float sh_w[SB / 64];
   __shared__ int sh_res;
   __shared__ int sh_n;
@@ -500,12 +495,11 @@ __global__ __launch_bounds__(SB) void accept_k(const float* __restrict__ p_logit
             const float qv = qrow[v] >= qthr ? expf((qrow[v] - qmx) * inv_t) * qinv : 0.f;
             return fmaxf(pv - qv, 0.f);
           },
-          V, u, sh_incl, sh_w, &sh_res);
+          V, u, sh_w, &sh_res);
       __syncthreads();
     }
     if (y < 0)                                           // bonus token from p_{K+1}, or a residual with no mass
-      y = block_sample([&](int v) { return prow[v] >= pthr ? expf((prow[v] - pmx) * inv_t) * pinv : 0.f; }, V, u,
-                       sh_incl, sh_w, &sh_res);
+      y = block_sample([&](int v) { return prow[v] >= pthr ? expf((prow[v] - pmx) * inv_t) * pinv : 0.f; }, V, u, sh_w, &sh_res);
     if (y < 0) y = __float_as_int(ps[n * 4 + 2]);
   }
   if (threadIdx.x == 0) {
