@@ -68,7 +68,7 @@ def pmc_summary(path, skip_rounds, out):
     n_pass = 0
     for a, b in zip(starts, starts[1:] + [len(rows)]):
         rnd = rows[a:b]
-        cut = next((i for i, r in enumerate(rnd) if "plan_verify_k" in r[1]), None)
+        cut = next((i for i, r in enumerate(rnd) if "plan_verify" in r[1]), None)
         if cut is None:
             continue
         n_pass += 1
@@ -101,7 +101,7 @@ def main(argv=None):
     n_rounds = 0
     for a, b in zip(starts, starts[1:] + [len(rows)]):
         rnd = rows[a:b]
-        cut = next((i for i, r in enumerate(rnd) if "plan_verify_k" in r[0]), None)
+        cut = next((i for i, r in enumerate(rnd) if "plan_verify" in r[0]), None)
         commit = next((i for i, r in enumerate(rnd) if "commit_k" in r[0]), None)
         if cut is None or commit is None:
             continue
