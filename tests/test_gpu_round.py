@@ -262,6 +262,45 @@ def test_bf16_round_logits_match_oracle_forward():
         ctx.close()
 
 
+def test_long_context_batch_logits_match_oracle_forward():
+    """Eight sequences with 600-1000 tokens of context decoded together: ten to sixteen key
+    blocks per sequence, target rows packed per sequence (ragged K).  The rows
+    p_1..p_{K+1} and q_1..q_K of every sequence against the oracle's teacher-forced forward."""
+    from paper_2405_19715_amd import binding as B
+    from oracle.model import forward_full
+    ts = synth.ModelShape(1, 256, 32, 8, 64, 384, 2048)      # grouped queries, 4 per kv head
+    ds = synth.ModelShape(1, 256, 32, 32, 64, 384, 2048)     # one kv head per query head
+    t = synth.make_model(ts, 30, dtype=torch.bfloat16, std=0.04)
+    d = synth.make_model(ds, 31, dtype=torch.bfloat16, std=0.04)
+    h = synth.make_head([256, 256, 1], 32, dtype=torch.bfloat16, residual=True, std=0.04)
+    Bn, seed = 8, 4
+    lens = [1000, 640, 873, 702, 991, 600, 935, 777]
+    prompts = [synth.make_prompt(lens[b], 2048, 70 + b) for b in range(Bn)]
+    ctx = _context(t, d, h, k_max=16, max_seq=1088, batch=Bn)
+    try:
+        for b in range(Bn):
+            ctx.sd_prefill(b, prompts[b])
+        tw, dw = oracle_model(t), oracle_model(d)
+        xs = [list(p) for p in prompts]
+        seen_K = set()
+        for rho in range(2):
+            res = ctx.specdec_round(B.make_params(h=0.8, seed=seed))
+            for b in range(Bn):
+                g = res[b]
+                K = g["K"]
+                seen_K.add(K)
+                q, p, _ = ctx.sd_last_round_rows(b, K)
+                want_p = forward_full(tw, xs[b] + g["cand"])[0][-(K + 1):]
+                want_q = forward_full(dw, xs[b] + g["cand"][:-1])[0][-K:]
+                for got, want in ((p.numpy(), want_p), (q.numpy(), want_q)):
+                    err = (np.abs(got - want).max(-1) / np.abs(want).max(-1)).max()
+                    assert err < 2e-2, (rho, b, err)
+                xs[b] += g["tokens"]
+        assert len(seen_K) > 1
+    finally:
+        ctx.close()
+
+
 def test_batch_of_sequences_matches_single_sequence_runs():
     """Two sequences decoded together give the streams each gives alone (per-sequence
     stop rule, ragged K, per-sequence rollback; the sequence id keys the uniforms)."""
