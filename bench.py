@@ -469,7 +469,12 @@ def main():
         est_avg_us = sum(counts[k] * prof[k]["seconds"] / prof[k]["launches"] for k in counts) / sum(counts.values()) * 1e6
     achieved = tot_b / tot_s / 1e9 if tot_s > 0 else None
     verify_bytes = _algorithmic_bytes_verify(wl["target"], P_mid, wl["k_max"], batch=nb)
-    roofline = dict(bound="hbm", kernel="gemm_bf16_stream<NT> (target pass, M = K+1 rows: instance <1> for up to 16 rows, <2> for 17)",
+    rows_pass = nb * (k_mean + 1)
+    kernel = ("gemm_bf16_stream<NT> (target pass, M = K+1 rows: instance <1> for up to 16 rows, <2> for 17)"
+              if rows_pass <= 32 else
+              "gemm_bf16_tile<2,1,..> / <2,2,..> (target pass of the batch, M = sum of K_b+1 rows packed in groups "
+              "of 4: one 128x64 or 128x128 m-tile holds every row, so each weight is read once)")
+    roofline = dict(bound="hbm", kernel=kernel,
                     achieved=achieved, peak=HBM_PEAK_GBS, unit="GB/s",
                     frac=(achieved / HBM_PEAK_GBS) if achieved else None,
                     traffic=_measured_traffic() if args.workload == "paper" else None,
