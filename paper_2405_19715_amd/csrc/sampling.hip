@@ -85,30 +85,41 @@ template <typename F>
 __device__ int block_sample(F f, int V, float u, float* sh_w, int* sh_res) {
   const int t = threadIdx.x, lane = t & 63, w = t >> 6;
   constexpr int NW = SB / 64;
+  constexpr int NR = 8;                                         // rows evaluated together (V = 32000: a wavefront's whole range)
   const int CW = (((V + NW - 1) / NW) + 255) & ~255;            // elements per wavefront, whole rows
   const int beg = min(w * CW, V), end = min(beg + CW, V);
-  auto row_scan = [&](int r0, float* fv, float& incl, float& tot) {
-    float ls = 0.f;
+  // NR rows from c0 on: all weights are fetched before the first scan (the loads of a row do not
+  // wait for the scan of the row before); per row the lane sum ls, the inclusive lane scan and the total
+  auto rows_scan = [&](int c0, float (*fv)[4], float* ls, float* incl, float* tot) {
 #pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      const int v = r0 + 4 * lane + e;
-      fv[e] = v < end ? f(v) : 0.f;
-      ls += fv[e];
-    }
-    incl = ls;
+    for (int r = 0; r < NR; ++r)
 #pragma unroll
-    for (int o = 1; o < 64; o <<= 1) {
-      const float n = __shfl_up(incl, o, WAVE);
-      if (lane >= o) incl += n;
+      for (int e = 0; e < 4; ++e) {
+        const int v = c0 + r * 256 + 4 * lane + e;
+        fv[r][e] = v < end ? f(v) : 0.f;
+      }
+#pragma unroll
+    for (int r = 0; r < NR; ++r) {
+      float a = 0.f;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) a += fv[r][e];
+      ls[r] = a;
+#pragma unroll
+      for (int o = 1; o < 64; o <<= 1) {
+        const float n = __shfl_up(a, o, WAVE);
+        if (lane >= o) a += n;
+      }
+      incl[r] = a;
+      tot[r] = __shfl(a, 63, WAVE);
     }
-    tot = __shfl(incl, 63, WAVE);
-    return ls;
   };
   float cw = 0.f;
-  for (int r0 = beg; r0 < end; r0 += 256) {
-    float fv[4], incl, tot;
-    row_scan(r0, fv, incl, tot);
-    cw += tot;
+  for (int c0 = beg; c0 < end; c0 += NR * 256) {
+    float fv[NR][4], ls[NR], incl[NR], tot[NR];
+    rows_scan(c0, fv, ls, incl, tot);
+#pragma unroll
+    for (int r = 0; r < NR; ++r)
+      if (c0 + r * 256 < end) cw += tot[r];
   }
   if (lane == 0) sh_w[w] = cw;
   if (t == 0) *sh_res = -1;
@@ -122,25 +133,31 @@ __device__ int block_sample(F f, int V, float u, float* sh_w, int* sh_res) {
   const float target = u * total;
   if (off <= target && target < off + cw) {                     // wave-uniform
     float run = 0.f;
-    for (int r0 = beg; r0 < end; r0 += 256) {
-      float fv[4], incl, tot;
-      const float ls = row_scan(r0, fv, incl, tot);
-      if (off + (run + tot) > target) {
-        const unsigned long long m = __ballot(off + (run + incl) > target);
-        if (lane == __ffsll((long long)m) - 1) {
-          float r = run + (incl - ls);
-          int pick = -1, last_pos = -1;
+    bool found = false;
+    for (int c0 = beg; c0 < end && !found; c0 += NR * 256) {
+      float fv[NR][4], ls[NR], incl[NR], tot[NR];
+      rows_scan(c0, fv, ls, incl, tot);
 #pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            r += fv[e];
-            if (fv[e] > 0.f) last_pos = r0 + 4 * lane + e;
-            if (pick < 0 && off + r > target) pick = r0 + 4 * lane + e;
+      for (int r = 0; r < NR; ++r) {
+        if (found || c0 + r * 256 >= end) continue;
+        if (off + (run + tot[r]) > target) {
+          const unsigned long long m = __ballot(off + (run + incl[r]) > target);
+          if (lane == __ffsll((long long)m) - 1) {
+            float acc = run + (incl[r] - ls[r]);
+            int pick = -1, last_pos = -1;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              acc += fv[r][e];
+              if (fv[r][e] > 0.f) last_pos = c0 + r * 256 + 4 * lane + e;
+              if (pick < 0 && off + acc > target) pick = c0 + r * 256 + 4 * lane + e;
+            }
+            *sh_res = pick >= 0 ? pick : last_pos;
           }
-          *sh_res = pick >= 0 ? pick : last_pos;
+          found = true;
+        } else {
+          run += tot[r];
         }
-        break;
       }
-      run += tot;
     }
   }
   __syncthreads();
@@ -272,10 +289,36 @@ __global__ __launch_bounds__(SB) void sample_stop_k(SeqState s, const float* __r
   // row maximum (and argmax), non-finite check
   ArgMax am{-INFINITY, 0x7fffffff};
   bool bad = false;
-  for (int v = threadIdx.x; v < V; v += SB) {
-    const float x = l[v];
-    bad |= !isfinite(x);
-    am = better(am, ArgMax{x, v});
+  if ((V & 3) == 0 && (reinterpret_cast<uintptr_t>(l) & 15) == 0) {
+    // a thread's 16-byte loads of a chunk all go out before the first is looked at
+    constexpr int NQ = 8;
+    const float4* l4 = reinterpret_cast<const float4*>(l);
+    const int nq = V / 4;
+    for (int q0 = 0; q0 < nq; q0 += NQ * SB) {
+      float4 x[NQ];
+#pragma unroll
+      for (int u = 0; u < NQ; ++u) {
+        const int q = q0 + u * SB + threadIdx.x;
+        if (q < nq) x[u] = l4[q];
+      }
+#pragma unroll
+      for (int u = 0; u < NQ; ++u) {
+        const int q = q0 + u * SB + threadIdx.x;
+        if (q < nq) {
+          bad |= !(isfinite(x[u].x) && isfinite(x[u].y) && isfinite(x[u].z) && isfinite(x[u].w));
+          am = better(am, ArgMax{x[u].x, 4 * q});
+          am = better(am, ArgMax{x[u].y, 4 * q + 1});
+          am = better(am, ArgMax{x[u].z, 4 * q + 2});
+          am = better(am, ArgMax{x[u].w, 4 * q + 3});
+        }
+      }
+    }
+  } else {
+    for (int v = threadIdx.x; v < V; v += SB) {
+      const float x = l[v];
+      bad |= !isfinite(x);
+      am = better(am, ArgMax{x, v});
+    }
   }
   am = block_argmax(am, sh_w, sh_i);
   if (bad) atomicOr(s.err, 1);
@@ -348,10 +391,48 @@ __global__ __launch_bounds__(SB) void row_stats_k(RowSet A, RowSet Bq, const int
     }
   };
   if ((V & 3) == 0 && (reinterpret_cast<uintptr_t>(l) & 15) == 0) {
+    // A chunk = NQ 16-byte pieces per thread, all requested before the first is consumed (the row is
+    // read once, from HBM).  From registers: the chunk's maximum first, then one exponential per
+    // element relative to it, no branches (one workgroup per row is bound by its CU's vector ALUs,
+    // not by memory); chunks are folded into the running pair like single elements.
+    constexpr int NQ = 8;                            // V = 32000: the whole row in one chunk
     const float4* l4 = reinterpret_cast<const float4*>(l);
-    for (int q = threadIdx.x; q < V / 4; q += SB) {
-      const float4 x = l4[q];
-      take(x.x, 4 * q); take(x.y, 4 * q + 1); take(x.z, 4 * q + 2); take(x.w, 4 * q + 3);
+    const int nq = V / 4;
+    for (int q0 = 0; q0 < nq; q0 += NQ * SB) {
+      float4 x[NQ];
+#pragma unroll
+      for (int u = 0; u < NQ; ++u) {
+        const int q = q0 + u * SB + threadIdx.x;
+        x[u] = q < nq ? l4[q] : float4{-INFINITY, -INFINITY, -INFINITY, -INFINITY};
+      }
+      ArgMax cm{-INFINITY, 0x7fffffff};
+      float chk = 0.f;                               // NaN as soon as one element is NaN or infinite
+#pragma unroll
+      for (int u = 0; u < NQ; ++u) {
+        const int q = q0 + u * SB + threadIdx.x;
+        if (q < nq) {
+          chk = fmaf(x[u].x, 0.f, chk); chk = fmaf(x[u].y, 0.f, chk);
+          chk = fmaf(x[u].z, 0.f, chk); chk = fmaf(x[u].w, 0.f, chk);
+        }
+        if (x[u].x > cm.v) cm = ArgMax{x[u].x, 4 * q};         // indices grow: ties keep the lowest id
+        if (x[u].y > cm.v) cm = ArgMax{x[u].y, 4 * q + 1};
+        if (x[u].z > cm.v) cm = ArgMax{x[u].z, 4 * q + 2};
+        if (x[u].w > cm.v) cm = ArgMax{x[u].w, 4 * q + 3};
+      }
+      bad |= !(chk == 0.f);
+      if (cm.i == 0x7fffffff) continue;              // nothing finite and above -inf in this chunk
+      float cs = 0.f;
+#pragma unroll
+      for (int u = 0; u < NQ; ++u) {                 // padding elements are -inf: exp gives 0
+        cs += expf((x[u].x - cm.v) * inv_t); cs += expf((x[u].y - cm.v) * inv_t);
+        cs += expf((x[u].z - cm.v) * inv_t); cs += expf((x[u].w - cm.v) * inv_t);
+      }
+      if (cm.v > am.v) {
+        run = run * expf((am.v - cm.v) * inv_t) + cs;
+        am = cm;
+      } else {
+        run += cs * expf((cm.v - am.v) * inv_t);
+      }
     }
   } else {
     for (int v = threadIdx.x; v < V; v += SB) take(l[v], v);
