@@ -63,6 +63,30 @@ def _measured_traffic():
     return None
 
 
+def _measured_stream_GBs():
+    """What this machine's HBM delivers to plain streaming kernels, measured in the same run: a
+    device-to-device copy of 1 GiB (read + write bytes) and a read-only reduction over it, both
+    torch's own kernels on the current stream (a reference figure, not part of the path)."""
+    import torch
+    n = 1 << 30
+    a = torch.empty(n, dtype=torch.uint8, device="cuda").fill_(1)
+    b = torch.empty_like(a)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    out = {}
+    for name, fn, nbytes in (("copy_GBs", lambda: b.copy_(a), 2 * n), ("read_GBs", lambda: a.view(torch.int64).sum(), n)):
+        for _ in range(3):
+            fn()
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(10):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        out[name] = 10 * nbytes / (e0.elapsed_time(e1) * 1e-3) / 1e9
+    del a, b
+    return out
+
+
 def _blas_threads():
     """Threads of the BLAS behind numpy's matmul, which is where the oracle's time goes."""
     try:
@@ -485,6 +509,9 @@ def main():
                     verify_pass=dict(algorithmic_bytes=verify_bytes, seconds=t_target,
                                      achieved_GBs=verify_bytes / t_target / 1e9,
                                      frac=verify_bytes / t_target / 1e9 / HBM_PEAK_GBS))
+    box = _measured_stream_GBs()
+    roofline["measured_stream"] = dict(box, frac_of_copy=(achieved / box["copy_GBs"]) if achieved else None,
+                                       frac_of_read=(achieved / box["read_GBs"]) if achieved else None)
     cpu = None
     if not args.no_cpu_baseline and nb == 1:
         cpu = _cpu_baseline(tgt, drf, k_mean, n_mean, wl["prompt"], wl["k_max"])

@@ -144,3 +144,49 @@ def test_full_vocab_acceptance_rate_near_closed_form():
     f = flags.cpu().numpy()
     want_n = [int(np.argmin(r)) if not r.all() else K for r in f]
     assert n.cpu().tolist() == want_n
+
+
+def test_emitted_token_follows_the_target_distribution():
+    """Appendix C's property, checked on the HIP path alone: with y_1 ~ q, the first token the
+    step emits (y_1 when accepted, else the residual draw) is distributed as p, and the
+    residual draws alone follow Norm[(p - q)_+].  64 tokens, 64 sequences x 200 rounds with
+    the same two rows (every trial has its own Philox counters); chi-square at the 99.9 %
+    quantile (63 degrees of freedom: 103.4; the residual has fewer non-empty cells)."""
+    from paper_2405_19715_amd import binding as Bd
+    B, K, V, seed, rounds = 64, 1, 64, 21, 200
+    g = torch.Generator().manual_seed(4)
+    p_row = torch.randn((K + 1, V), generator=g)
+    q_row = p_row[:K] + 0.7 * torch.randn((K, V), generator=g)
+    p = p_row.expand(B, K + 1, V).contiguous()
+    q = q_row.expand(B, K, V).contiguous()
+    pp = sampling.softmax(p_row[0].double().numpy())
+    qq = sampling.softmax(q_row[0].double().numpy())
+    res = np.maximum(pp - qq, 0.0)
+    res /= res.sum()
+    rng = np.random.default_rng(8)
+    pc, qc = p.cuda(), q.cuda()
+    Ks = torch.full((B,), K, dtype=torch.int32).cuda()
+    emitted = np.zeros(V)
+    resampled = np.zeros(V)
+    for rnd in range(rounds):
+        cand = rng.choice(V, size=(B, K), p=qq).astype(np.int32)
+        n, tok, flags = Bd.sd_accept_resample(pc, qc, torch.from_numpy(cand).cuda(), Ks,
+                                              Bd.make_params(seed=seed), rnd)
+        n, tok = n.cpu().numpy(), tok.cpu().numpy()
+        for b in range(B):
+            if n[b] >= 1:
+                emitted[cand[b, 0]] += 1
+            else:
+                emitted[tok[b]] += 1
+                resampled[tok[b]] += 1
+    trials = B * rounds
+    assert emitted.sum() == trials
+    chi = ((emitted - trials * pp) ** 2 / (trials * pp)).sum()
+    assert (trials * pp).min() > 5 and chi < 103.4, chi
+    nz = res * resampled.sum() > 5
+    assert resampled[res == 0].sum() == 0                     # never a token with p <= q
+    chi_r = ((resampled[nz] - resampled.sum() * res[nz]) ** 2 / (resampled.sum() * res[nz])).sum()
+    assert chi_r < 103.4, chi_r
+    # rejection frequency = 1 - sum_v min(p_v, q_v)
+    beta = np.minimum(pp, qq).sum()
+    assert abs(resampled.sum() / trials - (1 - beta)) < 4 * np.sqrt(beta * (1 - beta) / trials)
