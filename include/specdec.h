@@ -16,7 +16,11 @@
  *   - Every function returns an sd_status; 0 is success, negative is an error.
  *     Nothing throws or aborts.  Host out-parameters are written only on SD_OK.
  *     On an error the sequences' committed state (tokens, lengths) is unchanged.
- *   - Calls on one context must not overlap.
+ *   - Calls on one context must not overlap.  The library keeps a little per-process
+ *     state that is set on a kernel's first launch (the permission to use more than
+ *     64 KB of LDS): make the first calls from one thread, and use one GPU per
+ *     process (the device that is current when sd_create runs must be current in
+ *     every later call on that context).
  */
 #ifndef SPECDEC_H
 #define SPECDEC_H
