@@ -50,18 +50,34 @@ __device__ __forceinline__ float key_to_float(uint32_t k) {
   return __uint_as_float((k & 0x80000000u) ? (k & 0x7fffffffu) : ~k);
 }
 
-// The k-th largest of l[0..V) (1 <= k <= V), found bit by bit on the order keys: 32 passes
-// over the row (it stays in L2), each a block-wide count.  Top-k warping keeps l[v] >= it.
-// sh: SB/64 ints.
+// The k-th largest of l[0..V) (1 <= k <= V), found bit by bit on the order keys: 32 block-wide
+// counts of "key >= candidate".  Top-k warping keeps l[v] >= it.  A row of up to 32 elements per
+// thread (V = 32000 with 1024 threads) is read once into registers and every count is a compare
+// whose lane mask is popcounted; longer rows are re-read from L2 in every pass.  sh: SB/64 ints.
 __device__ float block_kth_largest(const float* __restrict__ l, int V, int k, int* sh) {
+  constexpr int NK = 32;
   uint32_t t = 0;
   const int w = threadIdx.x >> 6, nw = blockDim.x >> 6;
+  const bool in_regs = V <= NK * (int)blockDim.x;
+  uint32_t key[NK];
+  if (in_regs) {
+#pragma unroll
+    for (int u = 0; u < NK; ++u) {
+      const int v = u * blockDim.x + threadIdx.x;
+      key[u] = v < V ? order_key(l[v]) : 0u;         // 0 is below every candidate (a candidate has a bit set)
+    }
+  }
   for (int bit = 31; bit >= 0; --bit) {
     const uint32_t cand = t | (1u << bit);
     int c = 0;
-    for (int v = threadIdx.x; v < V; v += blockDim.x) c += order_key(l[v]) >= cand ? 1 : 0;
+    if (in_regs) {
 #pragma unroll
-    for (int o = 32; o > 0; o >>= 1) c += __shfl_xor(c, o, WAVE);
+      for (int u = 0; u < NK; ++u) c += __popcll(__ballot(key[u] >= cand));      // wave-uniform
+    } else {
+      for (int v = threadIdx.x; v < V; v += blockDim.x) c += order_key(l[v]) >= cand ? 1 : 0;
+#pragma unroll
+      for (int o = 32; o > 0; o >>= 1) c += __shfl_xor(c, o, WAVE);
+    }
     if ((threadIdx.x & 63) == 0) sh[w] = c;
     __syncthreads();
     int tot = 0;
