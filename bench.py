@@ -440,8 +440,11 @@ def main():
     head = synth.make_head(wl["head"], args.seed + 2, device=dev, dtype=torch.bfloat16, residual=True)
     torch.cuda.synchronize()
     t_build = time.perf_counter() - t_build
-    max_seq = -(-(wl["prompt"] + wl["gen"] + (args.steps + args.warmup + 16) * (wl["k_max"] + 1) + 2) // 64) * 64
     nb = wl.get("batch", 1)
+    sweep_h = [h for h in (0.3, 0.5, 0.7, 0.9) if abs(h - args.h) > 1e-9] if nb == 1 else []
+    sweep_rounds = 16
+    max_seq = -(-(wl["prompt"] + wl["gen"] + (args.steps + args.warmup + 16 + len(sweep_h) * sweep_rounds)
+                  * (wl["k_max"] + 1) + 2) // 64) * 64
     lens = wl.get("prompts", [wl["prompt"]])
     ctx = B.Context(tgt, drf, head, batch=nb, max_seq=max_seq, k_max=wl["k_max"])
     prompts = [synth.make_prompt(lens[b], wl["target"].vocab, args.seed + 3 + b) for b in range(nb)]
@@ -482,6 +485,22 @@ def main():
     t_target = st2["t_target_s"] / st2["rounds"]
     t_draft = st2["t_draft_s"] / max(st2["N_draft"], 1)
     t_accept = st2["t_accept_s"] / st2["rounds"]
+
+    # the other thresholds of the paper's sweep (Sec. 5.1), a few rounds each on the same context: rates and tokens/s
+    def _rates(K_list, n_list, seconds):
+        tok = sum(n + 1 for n in n_list)
+        return dict(tokens_per_s=tok / seconds, mean_K=sum(K_list) / len(K_list), mean_n=sum(n_list) / len(n_list),
+                    discard_rate=(sum(K_list) - sum(n_list)) / tok, verification_rate=len(K_list) / tok)
+    h_table = [dict(h=args.h, rounds=args.steps, **_rates(Ks, ns, dt))]
+    for hh in sweep_h:
+        ph = B.make_params(h=hh, temperature=1.0, greedy=False, seed=args.seed, top_k=args.top_k)
+        torch.cuda.synchronize()
+        th = time.perf_counter()
+        got = [ctx.specdec_round(ph)[0] for _ in range(sweep_rounds)]
+        torch.cuda.synchronize()
+        h_table.append(dict(h=hh, rounds=sweep_rounds,
+                            **_rates([g["K"] for g in got], [g["n"] for g in got], time.perf_counter() - th)))
+    h_table.sort(key=lambda e: e["h"])
 
     tot_b = sum(v["weight_bytes"] for v in prof.values())
     tot_s = sum(v["seconds"] for v in prof.values())
@@ -526,6 +545,7 @@ def main():
                            t_draft_ms=t_draft * 1e3, t_target_ms=t_target * 1e3, t_accept_ms=t_accept * 1e3,
                            eq4_tokens_per_s=1.0 / (t_draft + t_draft * (sum(Ks) - sum(ns)) / n_tok
                                                    + (t_target - t_draft) * len(Ks) / n_tok),
+                           h_sweep=h_table if nb == 1 else None,
                            weights_init_s=t_build,
                            prompt_pass=dict(seconds=t_prefill, rows=rows, gemm_tflops=prefill_flops / t_prefill / 1e12,
                                             frac_of_bf16_mfma_peak=prefill_flops / t_prefill / 2.5e15)),
