@@ -30,6 +30,12 @@ def _workload(name):
     if name == "paper":      # Llama-2-70B-shaped target, Llama-2-7B-shaped draft
         return dict(target=synth.LLAMA_70B, draft=synth.LLAMA_7B, head=[4096, 4096, 4096, 4096, 1], prompt=1024,
                     gen=512, k_max=16, label="llama2-70b/7b-shaped bf16 random-init, batch 1, prompt 1024, K_max 16")
+    if name == "paper-aligned":   # the same shapes and work, weights arranged so that the draft predicts the target
+        return dict(target=synth.LLAMA_70B, draft=synth.LLAMA_7B, head=[4096, 4096, 4096, 4096, 1], prompt=1024,
+                    gen=512, k_max=16, align=(2e-5, 0.5),
+                    label="llama2-70b/7b-shaped bf16, ALIGNED synthetic pair (all layers damped by 2e-5, draft "
+                          "embedding / LM head = first 4096 columns of the target's, the target's other LM-head "
+                          "columns scaled by 0.5), batch 1, prompt 1024, K_max 16")
     if name == "mid":        # Llama-2-7B-shaped target, 1.1B-shaped draft
         return dict(target=synth.LLAMA_7B, draft=synth.LLAMA_1B, head=[2048, 2048, 2048, 2048, 1], prompt=512,
                     gen=256, k_max=16, label="llama2-7b/1.1b-shaped bf16 random-init, batch 1, prompt 512, K_max 16")
@@ -438,6 +444,8 @@ def main():
     tgt = synth.make_model(wl["target"], args.seed, device=dev, dtype=torch.bfloat16)
     drf = synth.make_model(wl["draft"], args.seed + 1, device=dev, dtype=torch.bfloat16)
     head = synth.make_head(wl["head"], args.seed + 2, device=dev, dtype=torch.bfloat16, residual=True)
+    if "align" in wl:
+        synth.align_narrow_draft(tgt, drf, *wl["align"])
     torch.cuda.synchronize()
     t_build = time.perf_counter() - t_build
     nb = wl.get("batch", 1)

@@ -127,6 +127,26 @@ def damp_tail(model: Dict, first: int, gain: float) -> None:
             lay[name].mul_(gain)
 
 
+def align_narrow_draft(target: Dict, draft: Dict, layer_gain: float, extra_gain: float) -> None:
+    """Make, in place, a pair of DIFFERENT widths whose next-token distributions agree to a
+    tunable degree without trained weights (d_draft < d_target, same vocabulary):
+      * every layer of both models is damped by `layer_gain` (damp_tail from layer 0), so the
+        final hidden state of a row is close to the embedding of its input token and both
+        models are essentially bigram tables, while all weights are still streamed and multiplied;
+      * the draft's embedding and LM head become the first d_draft columns of the target's, so its
+        logits are the part of the target's logit sum that runs over those columns;
+      * the remaining columns of the target's LM head are scaled by `extra_gain`: they add a
+        per-token logit shift of about N(0, (0.02 extra_gain)^2 (d_target - d_draft)) that the
+        draft cannot see.  With sigma that standard deviation, the acceptance rate
+        sum_v min(p_v, q_v) is about 2 Phi(-sigma / 2) for a large vocabulary."""
+    dd = draft["tok_emb"].shape[1]
+    damp_tail(target, 0, layer_gain)
+    damp_tail(draft, 0, layer_gain)
+    draft["tok_emb"] = target["tok_emb"][:, :dd].contiguous()
+    draft["lm_head"] = target["lm_head"][:, :dd].contiguous()
+    target["lm_head"][:, dd:].mul_(extra_gain)
+
+
 def mark_hard_tokens(target: Dict, draft: Dict, frac: float, marker: float, c: float, seed: int) -> torch.Tensor:
     """Give the pair a marked subset H of the vocabulary (a fraction `frac` of the token ids) on
     which the draft's output layer disagrees with the target's: the draft gets its own LM head
