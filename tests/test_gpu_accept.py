@@ -190,3 +190,17 @@ def test_emitted_token_follows_the_target_distribution():
     # rejection frequency = 1 - sum_v min(p_v, q_v)
     beta = np.minimum(pp, qq).sum()
     assert abs(resampled.sum() / trials - (1 - beta)) < 4 * np.sqrt(beta * (1 - beta) / trials)
+
+
+@pytest.mark.parametrize("V", [7, 1001, 4100])
+def test_odd_vocabulary_sizes(V):
+    """Vocabulary sizes that are not multiples of 4 or of the 256-element sampling rows (rows then
+    start at addresses that are not 16-byte aligned, and the last row of a wavefront's range is
+    ragged): same parity as the full-size cases."""
+    _, exempt, _ = _run_case(3, 4, V, seed=12, rounds=6)
+    assert exempt <= 2
+    _, exempt, _ = _run_case(2, 3, V, seed=13, rounds=3, greedy=True)
+    assert exempt == 0
+    if V > 100:
+        _, exempt, _ = _run_case(2, 4, V, seed=14, rounds=3, top_k=50)
+        assert exempt <= 2
