@@ -87,6 +87,64 @@ def test_tiny_pair_free_running_parity_top_k(top_k):
         ctx.close()
 
 
+@pytest.mark.parametrize("greedy", [True, False])
+def test_largest_supported_candidate_length(greedy):
+    """K_max = 32, the largest the library takes, with h = 1 so that every round drafts all 32
+    (Algorithm 1 with fixed K): 33 target rows, 65 softmax rows, 32 accept tests per round.  Tiny
+    fp32 pair, free-running against the oracle."""
+    from paper_2405_19715_amd import binding as B
+    t, d, h = tiny_pair()
+    prompt = synth.make_prompt(40, 1024, 2)
+    ctx = _context(t, d, h, k_max=32, max_seq=320)
+    try:
+        ctx.sd_prefill(0, prompt)
+        op = R.Params(h=1.0, temperature=1.0, greedy=greedy, seed=3)
+        gp = B.make_params(h=1.0, temperature=1.0, greedy=greedy, seed=3)
+        toks, exempt, hist = run_free_running(ctx, oracle_model(t), oracle_model(d), oracle_head(h), prompt, op, gp,
+                                              96, 32, 320)
+        assert len(toks) == 96 and exempt <= 2
+        assert all(k == 32 for k, _ in hist)
+    finally:
+        ctx.close()
+
+
+def test_largest_supported_candidate_length_bf16_rows():
+    """The same on a bf16 pair: 33 target rows is more than the streaming GEMM takes, so the target
+    pass goes through the tiled kernel with K slices and attention through three query-tile groups
+    per kv head; rows against the oracle's teacher-forced forward, decisions replayed."""
+    from paper_2405_19715_amd import binding as B
+    from oracle.model import forward_full
+    t, d, h = _bf16_pair()
+    prompt = synth.make_prompt(70, 2048, 15)
+    ctx = _context(t, d, h, k_max=32, max_seq=256)
+    try:
+        ctx.sd_prefill(0, prompt)
+        x = list(prompt)
+        tw, dw = oracle_model(t), oracle_model(d)
+        for rho in range(2):
+            g = ctx.specdec_round(B.make_params(h=1.0, seed=7))[0]
+            K = g["K"]
+            assert K == 32
+            q, p, _ = ctx.sd_last_round_rows(0, K)
+            q, p = q.numpy(), p.numpy()
+            want_p = forward_full(tw, x + g["cand"])[0][-(K + 1):]
+            want_q = forward_full(dw, x + g["cand"][:-1])[0][-K:]
+            for got, want in ((p, want_p), (q, want_q)):
+                err = (np.abs(got - want).max(-1) / np.abs(want).max(-1)).max()
+                assert err < 2e-2, (rho, err)
+            o = sampling.accept_resample(p, q, g["cand"], K, seed=7, rnd=rho)
+            if o["n"] != g["n"]:
+                i = min(o["n"], g["n"]) + 1
+                assert abs(o["r"][i - 1] - o["ratio"][i - 1]) < 1e-3
+                o = sampling.accept_resample(p, q, g["cand"], K, seed=7, rnd=rho,
+                                             forced={("accept", i): 1 if g["n"] >= i else 0})
+            assert o["n"] == g["n"]
+            assert o["token"] == g["tokens"][-1] or o["margin"] < 1e-5
+            x += g["tokens"]
+    finally:
+        ctx.close()
+
+
 def test_greedy_generate_equals_target_only_greedy_and_counters():
     from paper_2405_19715_amd import binding as B
     t, d, h = tiny_pair(seed=3)
