@@ -378,15 +378,13 @@ def test_batch_of_sequences_matches_single_sequence_runs():
         ctx.close()
 
 
-def test_ragged_batch_of_eight_bf16_decision_replay():
-    """Eight sequences with different prompt lengths decoded together on a bf16 pair
-    (136 activation rows in the target pass, ragged K per sequence, per-sequence
-    rollback): every sequence's K, n and y' replayed by the oracle on the HIP path's own
-    rows, and the sequence state stays consistent."""
+def _ragged_batch_replay(Bn, k_max, hs, seed, max_exempt):
+    """Bn sequences with different prompt lengths decoded together on a bf16 pair, one round per
+    threshold in `hs`: every sequence's K, candidates, n and y' replayed by the oracle on the HIP
+    path's own rows, and the sequence state stays consistent.  Returns the set of K seen."""
     from paper_2405_19715_amd import binding as B
     from oracle import philox
     t, d, h = _bf16_pair()
-    Bn, k_max, hh, seed = 8, 16, 0.8, 9
     g0 = torch.Generator().manual_seed(123)
     lens = torch.randint(20, 90, (Bn,), generator=g0).tolist()
     prompts = [synth.make_prompt(lens[b], 2048, 50 + b) for b in range(Bn)]
@@ -397,7 +395,7 @@ def test_ragged_batch_of_eight_bf16_decision_replay():
         P = list(lens)
         exempt = 0
         seen_K = set()
-        for rho in range(4):
+        for rho, hh in enumerate(hs):
             res = ctx.specdec_round(B.make_params(h=hh, seed=seed))
             for b in range(Bn):
                 g = res[b]
@@ -427,9 +425,25 @@ def test_ragged_batch_of_eight_bf16_decision_replay():
                 P[b] += g["n"] + 1
                 st = ctx.sd_seq_state(b)
                 assert st["P"] == P[b] and st["kv_len_target"] == P[b] - 1
-        assert exempt <= 3 and len(seen_K) > 1
+        assert exempt <= max_exempt
+        return seen_K
     finally:
         ctx.close()
+
+
+def test_ragged_batch_of_eight_bf16_decision_replay():
+    """Eight sequences (136 activation rows in the target pass when all draft K_max, ragged K per
+    sequence otherwise, per-sequence rollback)."""
+    seen_K = _ragged_batch_replay(8, 16, [0.8] * 4, seed=9, max_exempt=3)
+    assert len(seen_K) > 1
+
+
+def test_batch_at_the_row_limit():
+    """Twenty sequences with K_max = 7: 20 x 8 = 160 target rows, the most a context takes, and 40
+    draft rows per step (both through the tiled kernel); first every sequence drafts all 7 (h = 1),
+    then the stop rule makes K ragged and the rows are packed."""
+    seen_K = _ragged_batch_replay(20, 7, [1.0, 0.8, 0.8], seed=10, max_exempt=4)
+    assert 7 in seen_K and len(seen_K) > 1
 
 
 @pytest.mark.parametrize("n_prompt", [1, 2, 3])
