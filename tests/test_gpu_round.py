@@ -378,13 +378,16 @@ def test_batch_of_sequences_matches_single_sequence_runs():
         ctx.close()
 
 
-def _ragged_batch_replay(Bn, k_max, hs, seed, max_exempt):
+def _ragged_batch_replay(Bn, k_max, hs, seed, max_exempt, check_rows=0):
     """Bn sequences with different prompt lengths decoded together on a bf16 pair, one round per
     threshold in `hs`: every sequence's K, candidates, n and y' replayed by the oracle on the HIP
-    path's own rows, and the sequence state stays consistent.  Returns the set of K seen."""
+    path's own rows, and the sequence state stays consistent; for the first `check_rows` sequences
+    the rows themselves against the oracle's teacher-forced forward.  Returns the set of K seen."""
     from paper_2405_19715_amd import binding as B
     from oracle import philox
+    from oracle.model import forward_full
     t, d, h = _bf16_pair()
+    tw, dw = oracle_model(t), oracle_model(d)
     g0 = torch.Generator().manual_seed(123)
     lens = torch.randint(20, 90, (Bn,), generator=g0).tolist()
     prompts = [synth.make_prompt(lens[b], 2048, 50 + b) for b in range(Bn)]
@@ -393,6 +396,7 @@ def _ragged_batch_replay(Bn, k_max, hs, seed, max_exempt):
         for b in range(Bn):
             ctx.sd_prefill(b, prompts[b])
         P = list(lens)
+        xs = [list(pr) for pr in prompts]
         exempt = 0
         seen_K = set()
         for rho, hh in enumerate(hs):
@@ -403,6 +407,13 @@ def _ragged_batch_replay(Bn, k_max, hs, seed, max_exempt):
                 seen_K.add(K)
                 q, p, s = ctx.sd_last_round_rows(b, K)
                 q, p, s = q.numpy(), p.numpy(), s.numpy()
+                if b < check_rows:
+                    want_p = forward_full(tw, xs[b] + g["cand"])[0][-(K + 1):]
+                    want_q = forward_full(dw, xs[b] + g["cand"][:-1])[0][-K:]
+                    for got, want in ((p, want_p), (q, want_q)):
+                        err = (np.abs(got - want).max(-1) / np.abs(want).max(-1)).max()
+                        assert err < 2e-2, (rho, b, err)
+                xs[b] += g["tokens"]
                 want_K = OH.candidate_length(list(s.astype(np.float64)) + [1.0] * 40, hh, k_max)
                 if want_K != K:
                     ph = np.cumprod(np.concatenate([[1.0], s.astype(np.float64)]))
@@ -442,7 +453,7 @@ def test_batch_at_the_row_limit():
     """Twenty sequences with K_max = 7: 20 x 8 = 160 target rows, the most a context takes, and 40
     draft rows per step (both through the tiled kernel); first every sequence drafts all 7 (h = 1),
     then the stop rule makes K ragged and the rows are packed."""
-    seen_K = _ragged_batch_replay(20, 7, [1.0, 0.8, 0.8], seed=10, max_exempt=4)
+    seen_K = _ragged_batch_replay(20, 7, [1.0, 0.8, 0.8], seed=10, max_exempt=4, check_rows=4)
     assert 7 in seen_K and len(seen_K) > 1
 
 
