@@ -96,6 +96,7 @@ def test_bf16_long_context_many_key_splits():
     (synth.ModelShape(2, 256, 2, 2, 128, 384, 2048), 201, 256),     # MHA, head_dim 128, ragged tiles
     (synth.ModelShape(2, 1024, 8, 1, 128, 1280, 2048), 230, 256),   # 8:1 grouped queries, head_dim 128
     (synth.ModelShape(1, 256, 4, 2, 64, 256, 512), 1101, 1152),     # two prompt chunks (1024 + 76 rows)
+    (synth.ModelShape(1, 128, 2, 1, 64, 128, 512), 8000, 8064),     # long context: 8 chunks, 126 key blocks to merge
 ])
 def test_bf16_prompt_pass_matches_oracle(shape, n, max_seq):
     """The prompt pass (tiled large-M GEMM + unsplit causal attention) fills the KV cache
@@ -113,5 +114,50 @@ def test_bf16_prompt_pass_matches_oracle(shape, n, max_seq):
         l, h = ctx.sd_forward(0, 0, n - 1, toks[n - 1:], want_hidden=True)
         assert _row_err(l.numpy(), want_logits[n - 1:]) < TOL[torch.bfloat16]
         assert _row_err(h.numpy(), want_hid[n - 1:]) < TOL[torch.bfloat16]
+    finally:
+        ctx.close()
+
+
+def _last_rows_of_a_one_layer_model(m, toks, n):
+    """Logits of rows n-1 .. of a ONE-layer model from the oracle's layer functions: every key and
+    value depends on its own token only, so the last rows need no full T x T forward."""
+    from oracle import model as OM
+    shape = m["shape"]
+    w = oracle_model(m)
+    lw = w.layers[0]
+    T = len(toks)
+    pos = np.arange(T)
+    x = w.tok_emb[np.asarray(toks)]
+    a = OM.rmsnorm(x, lw.norm_attn, w.rms_eps)
+    k = OM.rope((a @ lw.wk.T).reshape(T, shape.n_kv_heads, shape.head_dim), pos, w.rope_theta)
+    v = (a @ lw.wv.T).reshape(T, shape.n_kv_heads, shape.head_dim)
+    last = slice(n - 1, T)
+    q = OM.rope((a[last] @ lw.wq.T).reshape(-1, shape.n_heads, shape.head_dim), pos[last], w.rope_theta)
+    xl = x[last] + OM.attention(q, k, v, pos[last]) @ lw.wo.T
+    h = OM.rmsnorm(xl, lw.norm_mlp, w.rms_eps)
+    xl = xl + (OM.silu(h @ lw.w_gate.T) * (h @ lw.w_up.T)) @ lw.w_down.T
+    return OM.rmsnorm(xl, w.final_norm, w.rms_eps) @ w.lm_head.T
+
+
+def test_context_at_the_largest_cache_size():
+    """max_seq = 32768, the most the attention kernels take (512 key blocks per row): 32700 prompt
+    tokens through the prompt pass, then 6 teacher-forced rows whose attention merges 511 partials.
+    The expected rows come from the oracle's layer functions applied to the last rows only (shown
+    equal to its full forward on a short sequence first)."""
+    from paper_2405_19715_amd import binding as B
+    shape = synth.ModelShape(1, 128, 2, 1, 64, 128, 512)
+    m = synth.make_model(shape, 8, dtype=torch.bfloat16, std=0.04)
+    n, tail = 32700, 6
+    toks = synth.make_prompt(n + tail, shape.vocab, 9)
+    short = toks[:206]
+    assert np.abs(_last_rows_of_a_one_layer_model(m, short, 200) - forward_full(oracle_model(m), short)[0][199:]).max() < 1e-12
+    want = _last_rows_of_a_one_layer_model(m, toks, n)
+    mc = _cuda(m)
+    ctx = B.Context(mc, mc, None, batch=1, max_seq=32768, k_max=8)
+    try:
+        ctx.sd_prefill(0, toks[:n])
+        got = ctx.sd_forward(0, 0, n - 1, toks[n - 1:]).numpy()
+        assert _row_err(got, want) < TOL[torch.bfloat16]
+        assert ctx.sd_seq_state(0)["P"] == n
     finally:
         ctx.close()
