@@ -81,7 +81,8 @@ typedef struct {
 
 typedef struct {
   int32_t batch;                   /* sequences decoded together (>= 1)                */
-  int32_t max_seq;                 /* KV-cache capacity per sequence, in tokens        */
+  int32_t max_seq;                 /* KV-cache capacity per sequence, in tokens: a multiple
+                                      of 64, at most 32768 (bf16) or 12288 (fp32 models) */
   int32_t k_max;                   /* cap on candidates per round (Sec. 5.1), 1..SD_MAX_K */
   void *hip_stream;                /* hipStream_t all work is enqueued on (NULL = default) */
 } sd_config;

@@ -383,6 +383,9 @@ sd_status sd_create(sd_ctx** out, const sd_model* target, const sd_model* draft,
   if (cfg->batch < 1 || cfg->k_max < 1 || cfg->k_max > SD_MAX_K || cfg->max_seq < 64 || cfg->max_seq % 64 != 0)
     return SD_EINVAL;
   if (cfg->batch * (cfg->k_max + 1) > MAX_ROWS) return SD_EINVAL;
+  // what the attention kernels take: 512 key blocks of 64 (bf16); a prefix of scores in 64 KB of LDS (fp32)
+  for (const sd_model* m : {target, draft})
+    if (cfg->max_seq > (m->dtype == SD_BF16 ? 32768 : 12288)) return SD_EINVAL;
   if (head) {
     if (head->n_layers < 1 || head->n_layers > SD_MAX_HEAD_LAYERS || !head->dims || !head->W || !head->b)
       return SD_EINVAL;

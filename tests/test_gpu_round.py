@@ -196,6 +196,10 @@ def test_sampled_generate_matches_oracle_generate_and_resumes():
 def test_cache_capacity_and_bad_arguments():
     from paper_2405_19715_amd import binding as B
     t, d, h = tiny_pair(seed=1)
+    for bad_seq in (100, 12352):                            # not a multiple of 64; more than an fp32 model takes
+        with pytest.raises(B.SpecDecError) as e:
+            _context(t, d, h, k_max=8, max_seq=bad_seq)
+        assert e.value.status == B.SD_EINVAL
     ctx = _context(t, d, h, k_max=8, max_seq=64)
     try:
         with pytest.raises(B.SpecDecError) as e:
