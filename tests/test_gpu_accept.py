@@ -204,3 +204,27 @@ def test_odd_vocabulary_sizes(V):
     if V > 100:
         _, exempt, _ = _run_case(2, 4, V, seed=14, rounds=3, top_k=50)
         assert exempt <= 2
+
+
+def test_sequences_without_candidates():
+    """K_b = 0 (a sequence that drafted nothing): no accept test, n = 0, and y' is drawn from
+    p_1 with the bonus-token uniform; mixed with sequences that do have candidates."""
+    from paper_2405_19715_amd import binding as Bd
+    B, Kmax, V, seed = 4, 4, 32000, 17
+    p, q = synth.make_accept_logits(B, Kmax, V, seed)
+    Ks = np.array([0, 3, 0, 4], dtype=np.int32)
+    for greedy in (False, True):
+        cand = np.zeros((B, Kmax), dtype=np.int32)
+        for b in range(B):
+            cand[b, : Ks[b]] = _candidates(q[b], Ks[b], seed, 0, b) if not greedy else q[b, : Ks[b]].argmax(-1).numpy()
+        n, tok, flags = Bd.sd_accept_resample(p.cuda(), q.cuda(), torch.from_numpy(cand).cuda(),
+                                              torch.from_numpy(Ks).cuda(), Bd.make_params(seed=seed, greedy=greedy), 0)
+        n, tok, flags = n.cpu().numpy(), tok.cpu().numpy(), flags.cpu().numpy()
+        for b in range(B):
+            o = sampling.accept_resample(p[b].numpy(), q[b].numpy(), cand[b], int(Ks[b]), greedy=greedy, seed=seed,
+                                         rnd=0, seq=b)
+            if Ks[b] == 0:
+                assert n[b] == 0 and (flags[b] == 0).all()
+                assert tok[b] == o["token"] or (not greedy and o["margin"] < CDF_TOL)
+            elif (flags[b, : Ks[b]] == o["flags"]).all():
+                assert n[b] == o["n"] and (tok[b] == o["token"] or (not greedy and o["margin"] < CDF_TOL))
