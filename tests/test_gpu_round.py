@@ -87,6 +87,32 @@ def test_tiny_pair_free_running_parity_top_k(top_k):
         ctx.close()
 
 
+@pytest.mark.parametrize("h,want_K", [(-0.5, 1), (0.0, 2), (1.0, 8)])
+def test_degenerate_thresholds(h, want_K):
+    """h < 0 stops after the first candidate (1 - p_hat = 0 > h before any prediction), h = 0
+    after the second (the first prediction below 1), h >= 1 never (fixed K = K_max): free-running
+    parity with the oracle at each, without and with the head (without it p_hat stays 1)."""
+    from paper_2405_19715_amd import binding as B
+    t, d, hd = tiny_pair()
+    prompt = synth.make_prompt(30, 1024, 6)
+    for head in (hd, None):
+        ctx = _context(t, d, head, k_max=8, max_seq=192)
+        try:
+            ctx.sd_prefill(0, prompt)
+            op = R.Params(h=h, temperature=1.0, greedy=False, seed=5)
+            gp = B.make_params(h=h, temperature=1.0, greedy=False, seed=5)
+            toks, exempt, hist = run_free_running(ctx, oracle_model(t), oracle_model(d),
+                                                  oracle_head(head) if head is not None else None, prompt, op, gp,
+                                                  40, 8, 192)
+            assert exempt <= 1
+            if head is not None or h < 0 or h >= 1:
+                assert all(k == want_K for k, _ in hist), hist
+            else:
+                assert all(k == 8 for k, _ in hist), hist          # no head: p_hat = 1, 1 - p_hat = 0 is not > 0
+        finally:
+            ctx.close()
+
+
 @pytest.mark.parametrize("greedy", [True, False])
 def test_largest_supported_candidate_length(greedy):
     """K_max = 32, the largest the library takes, with h = 1 so that every round drafts all 32
