@@ -545,3 +545,28 @@ def test_eos_stops_generation_like_the_oracle():
         assert (st["N"], st["N_draft"], st["N_target"]) == (ost.N, ost.N_draft, ost.N_target)
     finally:
         ctx.close()
+
+
+def test_first_emitted_token_of_a_round_follows_the_target():
+    """Speculative sampling leaves the output distribution unchanged (Appendix C), whatever rule
+    chose K: over 3000 seeds on the tiny pair, the first token a round emits (y_1 if accepted, else
+    the residual draw) must be distributed as the target's p_1.  Tokens are binned into 16 groups
+    of 64 consecutive ids; chi-square at the 99.9 % quantile of 15 degrees of freedom."""
+    from paper_2405_19715_amd import binding as B
+    from oracle.model import forward_full
+    t, d, h = tiny_pair()
+    prompt = synth.make_prompt(24, 1024, 11)
+    p1 = sampling.softmax(forward_full(oracle_model(t), prompt)[0][-1])
+    ctx = _context(t, d, h, k_max=8, max_seq=64)
+    try:
+        trials, bins = 3000, 16
+        counts = np.zeros(bins)
+        for seed in range(trials):
+            ctx.sd_prefill(0, prompt)
+            g = ctx.specdec_round(B.make_params(h=0.7, seed=1000 + seed))[0]
+            counts[g["tokens"][0] * bins // 1024] += 1
+        want = trials * p1.reshape(bins, -1).sum(-1)
+        chi = ((counts - want) ** 2 / want).sum()
+        assert want.min() > 50 and chi < 37.7, chi
+    finally:
+        ctx.close()
