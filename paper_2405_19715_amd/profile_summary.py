@@ -2,6 +2,7 @@
 short text summary per phase of a round.
 
     python -m paper_2405_19715_amd.profile_summary <..._kernel_trace.csv> [--skip-rounds W]
+    python -m paper_2405_19715_amd.profile_summary <..._counter_collection.csv> --pmc | --counters
 
 The whole-process statistics rocprofv3 prints mix the untimed prefill (which runs the
 same GEMM kernel over 32-row prompt chunks of both models) into every average.  This
@@ -82,14 +83,51 @@ def pmc_summary(path, skip_rounds, out):
                   f"{tot / n * scale * 1024 / 1e6:.2f} MB (scaled), per pass {tot / n_pass * scale * 1024 / 1e9:.3f} GB\n")
 
 
+def counters_summary(path, skip_rounds, out):
+    """Per-launch averages of every counter in a `rocprofv3 --pmc <counters> --output-format csv`
+    run of bench.py, for the GEMM launches of the target passes (everything between the kernel that
+    plans the verify rows and the round's end)."""
+    rows = []
+    with open(path, newline="") as f:
+        for r in csv.DictReader(f):
+            rows.append((int(r["Dispatch_Id"]), short_name(r["Kernel_Name"]), r["Counter_Name"], float(r["Counter_Value"])))
+    rows.sort()
+    starts = [i for i, r in enumerate(rows) if "begin_round_k" in r[1]]
+    starts = sorted(set(starts))
+    # one row per (dispatch, counter): a round opens at the first row of a begin_round_k dispatch
+    first = {}
+    for i in starts:
+        first.setdefault(rows[i][0], i)
+    starts = sorted(first.values())[skip_rounds:]
+    agg = collections.OrderedDict()
+    for a, b in zip(starts, starts[1:] + [len(rows)]):
+        rnd = rows[a:b]
+        cut = next((i for i, r in enumerate(rnd) if "plan_verify" in r[1]), None)
+        end = next((i for i, r in enumerate(rnd) if "commit_k" in r[1]), None)
+        if cut is None or end is None:
+            continue
+        for d, n, c, v in rnd[cut:end]:
+            if "gemm_bf16" in n:
+                e = agg.setdefault((n, c), [set(), 0.0])
+                e[0].add(d)
+                e[1] += v
+    for (n, c), (ds, tot) in agg.items():
+        out.write(f"{n:40s} {c:36s} {tot / len(ds):18.1f} per launch ({len(ds)} launches)\n")
+
+
 def main(argv=None):
     ap = argparse.ArgumentParser()
     ap.add_argument("trace")
     ap.add_argument("--skip-rounds", type=int, default=2)
     ap.add_argument("--pmc", action="store_true", help="the file is a counter_collection.csv of a --pmc run")
+    ap.add_argument("--counters", action="store_true",
+                    help="the file is a counter_collection.csv: average every counter over the target pass's GEMM launches")
     args = ap.parse_args(argv)
     if args.pmc:
         pmc_summary(args.trace, args.skip_rounds, sys.stdout)
+        return
+    if args.counters:
+        counters_summary(args.trace, args.skip_rounds, sys.stdout)
         return
     rows = load(args.trace)
     starts = [i for i, r in enumerate(rows) if "begin_round_k" in r[0]]
