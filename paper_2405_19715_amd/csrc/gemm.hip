@@ -12,9 +12,15 @@
 //                (already in the order the multiply needs) and never synchronises again.
 //   wavefront  = walks its own list of 16-row weight tiles (tile = slot, slot + NW, ...)
 //                (NW = 8 G) with ONE continuous software pipeline of 16-byte loads that runs across
-//                tile boundaries; lane (r = lane % 16, g = lane / 16) loads, per 128-k
-//                step, 4 x 16 B of row r (instruction j covers the 64 contiguous bytes
-//                k0 + 32 j .. of every row, lane group g the 16 B at + 8 g).
+//                tile boundaries; per 128-k step it issues 4 load instructions, each covering
+//                8 rows x one whole 128-byte line (lane (r = lane % 16, g = lane / 16) of
+//                instruction 2 seg + a: row 8 a + r % 8, bytes seg * 128 + ((r / 8) * 4 + g) * 16).
+//                The MFMA wants lane (r, g) to hold row r, so half of every operand sits 8 lanes
+//                away: one v_mov_b32_dpp row_ror:8 per dword puts it in place (the vector ALU is
+//                idle anyway).  Whole lines per instruction are what lets non-temporal loads pay:
+//                a pure-read test of this pattern streams 6.4 TB/s with them against 5.9-6.0
+//                without, or with 64-byte row pieces per instruction (the MFMA's native operand
+//                layout, 16 rows x 64 B) with or without them.
 //   rotation   = each wavefront starts its slice at a different k-step (and wraps), so
 //                that the thousands of concurrent row streams, whose row stride is a
 //                large power of two, do not all hit the same HBM channels at once.
@@ -94,6 +100,30 @@ Split plan_bf16(int M, int N, int K) {
 
 __device__ __forceinline__ uint4 ldg128(const bf16_t* p) { return *reinterpret_cast<const uint4*>(p); }
 
+// 16-byte non-temporal load (compiles to one global_load_dwordx4 ... nt): for the weights, which are read
+// once per call.  It only pays when one instruction covers whole 128-byte lines (see the file comment).
+__device__ __forceinline__ uint4 ldg128_stream(const bf16_t* p) {
+  const uint32_t* q = reinterpret_cast<const uint32_t*>(p);
+  uint4 v;
+  v.x = __builtin_nontemporal_load(q);
+  v.y = __builtin_nontemporal_load(q + 1);
+  v.z = __builtin_nontemporal_load(q + 2);
+  v.w = __builtin_nontemporal_load(q + 3);
+  return v;
+}
+
+// dst lanes 8..15 (HI) or 0..7 (!HI) of every 16-lane row take `src` from the lane 8 away; the rest keep `old`.
+template <bool HI>
+__device__ __forceinline__ uint4 take_rot8(const uint4& old, const uint4& src) {
+  constexpr int ROW_ROR8 = 0x128, BANKS = HI ? 0xC : 0x3;
+  uint4 r;
+  r.x = (uint32_t)__builtin_amdgcn_update_dpp((int)old.x, (int)src.x, ROW_ROR8, 0xF, BANKS, false);
+  r.y = (uint32_t)__builtin_amdgcn_update_dpp((int)old.y, (int)src.y, ROW_ROR8, 0xF, BANKS, false);
+  r.z = (uint32_t)__builtin_amdgcn_update_dpp((int)old.z, (int)src.z, ROW_ROR8, 0xF, BANKS, false);
+  r.w = (uint32_t)__builtin_amdgcn_update_dpp((int)old.w, (int)src.w, ROW_ROR8, 0xF, BANKS, false);
+  return r;
+}
+
 __device__ __forceinline__ bf16x8 as_bf16x8(const uint4& v) {
   union { uint4 u; bf16x8 b; } c;
   c.u = v;
@@ -154,7 +184,10 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_stream(const bf16_t* _
   const int my_tiles = wslot < ntiles ? (ntiles - wslot + nslots - 1) / nslots : 0;
 
   WaveWalk ww;
-  ww.base = W + ((size_t)wslot * 16 + r) * K + kbeg + g * 8;
+  // lane (r, g) of load instruction j = 2 seg + a of a step: row 8 a + r % 8 of the tile, 16 bytes at byte
+  // seg * 128 + ((r / 8) * 4 + g) * 16 of the step's 256: eight lanes cover one 128-byte line of a row
+  ww.base = W + ((size_t)wslot * 16 + (r & 7)) * K + kbeg + ((r >> 3) * 4 + g) * 8;
+  const size_t half_tile = (size_t)8 * K;            // elements from row i to row i + 8
   ww.tile_stride = (size_t)nslots * 16 * K;
   ww.steps = steps;
   ww.rot = (wslot * 5 + ks * 3) % steps;
@@ -167,7 +200,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_stream(const bf16_t* _
     if (p < ww.nwork) {
       const bf16_t* q = ww.at(p);
 #pragma unroll
-      for (int j = 0; j < 4; ++j) a[p][j] = ldg128(q + j * 32);
+      for (int j = 0; j < 4; ++j) a[p][j] = ldg128_stream(q + (j & 1) * half_tile + (j >> 1) * 64);
     }
 
   stage_x(lds, X, ldx, xrow, M, kbeg, steps);
@@ -186,13 +219,17 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_stream(const bf16_t* _
     for (int p = 0; p < PREFETCH; ++p) {
       const int i = i0 + p;
       if (i < ww.nwork) {
+        // MFMA 2 seg + m wants lane (r, g) to hold row r, bytes seg * 128 + m * 64 + 16 g: lanes r < 8 have that
+        // for m = 0 from instruction a = 0 and lanes r >= 8 for m = 1 from a = 1; the other halves sit 8 lanes away
         uint4 cur[4];
-#pragma unroll
-        for (int j = 0; j < 4; ++j) cur[j] = a[p][j];
+        cur[0] = take_rot8<true>(a[p][0], a[p][1]);
+        cur[1] = take_rot8<false>(a[p][1], a[p][0]);
+        cur[2] = take_rot8<true>(a[p][2], a[p][3]);
+        cur[3] = take_rot8<false>(a[p][3], a[p][2]);
         if (i + PREFETCH < ww.nwork) {
           const bf16_t* q = ww.at(i + PREFETCH);
 #pragma unroll
-          for (int j = 0; j < 4; ++j) a[p][j] = ldg128(q + j * 32);
+          for (int j = 0; j < 4; ++j) a[p][j] = ldg128_stream(q + (j & 1) * half_tile + (j >> 1) * 64);
         }
         int s = sl + ww.rot;
         if (s >= steps) s -= steps;
