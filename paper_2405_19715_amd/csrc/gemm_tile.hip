@@ -56,6 +56,10 @@ __device__ __forceinline__ void wait_vmcnt() {
 __device__ __forceinline__ void load_to_lds16(const bf16_t* g, uint32_t lds_bytes) {
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_bytes), "v"(g) : "memory", "m0");
 }
+// the same, non-temporal: for weights that no other workgroup will read again (one m-tile)
+__device__ __forceinline__ void load_to_lds16_stream(const bf16_t* g, uint32_t lds_bytes) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off nt" ::"s"(lds_bytes), "v"(g) : "memory", "m0");
+}
 
 template <int TN, int TM, int WN, int WM, int BK, int NS>
 __global__ __launch_bounds__(64 * WN * WM) void gemm_bf16_tile(const bf16_t* __restrict__ W,
@@ -89,6 +93,7 @@ __global__ __launch_bounds__(64 * WN * WM) void gemm_bf16_tile(const bf16_t* __r
 
   const bf16_t* gsrc[LPW];
   uint32_t ldst[LPW];
+  bool stream[LPW];                                  // a weight block of a launch with one m-tile: read once
   const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint4*)smem;   // LDS byte address
 #pragma unroll
   for (int i = 0; i < LPW; ++i) {
@@ -104,12 +109,16 @@ __global__ __launch_bounds__(64 * WN * WM) void gemm_bf16_tile(const bf16_t* __r
       gsrc[i] = X + (size_t)(xrow ? xrow[m] : m) * ldx + kg * 8;
     }
     ldst[i] = lds0 + (uint32_t)((isA ? 0 : BN * KG) + blk * 64) * 16u;
+    stream[i] = isA && m_tiles == 1;
   }
   auto issue = [&](int kt) {
     const uint32_t stage = (uint32_t)((kt % NS) * STAGE) * 16u;
 #pragma unroll
-    for (int i = 0; i < LPW; ++i)
-      load_to_lds16(gsrc[i] + (size_t)kt * BK, __builtin_amdgcn_readfirstlane(ldst[i] + stage));
+    for (int i = 0; i < LPW; ++i) {
+      const uint32_t dst = __builtin_amdgcn_readfirstlane(ldst[i] + stage);
+      if (stream[i]) load_to_lds16_stream(gsrc[i] + (size_t)kt * BK, dst);       // wave-uniform
+      else load_to_lds16(gsrc[i] + (size_t)kt * BK, dst);
+    }
   };
 
   floatx16 acc[TN][TM];
