@@ -315,7 +315,10 @@ hipError_t launch_stream(hipStream_t st, const bf16_t* W, const bf16_t* X, int l
   return hipGetLastError();
 }
 
-constexpr int STREAM_MAX_ROWS = 32;      // above this the X slice in LDS gets short and the tiled kernel wins
+// One 16-row MFMA tile of activations: up to here this kernel wins or ties on every matrix (6 rows, 70B gate|up:
+// 164 us against 174 us); from 17 rows on the tiled kernel with its non-temporal whole-line loads is equal or
+// faster (17 rows: 173 against 179 us, 32 rows: 176 against 189 us).
+constexpr int STREAM_MAX_ROWS = 16;
 
 bool use_tile(int M, int N, int K) { return M > STREAM_MAX_ROWS && K % 32 == 0 && N % 4 == 0; }
 

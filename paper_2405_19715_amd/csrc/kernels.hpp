@@ -16,7 +16,7 @@ constexpr int MAX_PREFILL_ROWS = 1024; // most rows of one prompt-pass chunk (ti
 // W: [N, K] row-major in dtype; X: [M, K] rows (row stride ldx elements) in dtype,
 // optionally gathered through xrow (device int32 [M], may be null).
 // The number of K-slices is gemm_splits(dtype, M, N, K); consumers add the slices
-// in slice order.  bf16 products with more than 32 rows go through the tiled kernel
+// in slice order.  bf16 products with more than 16 rows go through the tiled kernel
 // (launch_gemm_tile), which reads every weight once however many rows there are.
 int gemm_splits(int dtype, int M, int N, int K);
 hipError_t launch_gemm(hipStream_t st, int dtype, const void* W, const void* X, int ldx, const int* xrow,

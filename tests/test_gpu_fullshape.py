@@ -150,7 +150,7 @@ def test_full_depth_pair_rounds_decisions_and_launch_shape_invariance():
         and ingests the same rows in one launch of the same shape must give the same bits
         (this is what the KV rollback has to guarantee);
       * the logits of a position do not depend on how rows are grouped into launches: a third
-        context (prompt in chunks of 32 rows through the streaming kernel, then one row per
+        context (prompt in chunks of 32 rows, without the prompt pass's unsplit attention, then one row per
         launch) must agree up to bf16 rounding noise.  That noise grows with depth: between
         any two launch shapes the row-wise max-norm error was measured at 0.65 %, 1.6 %, 3.0 %,
         4.6 %, 7.3 % for 2, 8, 20, 40, 80 layers of this shape (activations are rounded to bf16
