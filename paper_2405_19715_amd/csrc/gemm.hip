@@ -56,8 +56,8 @@ struct Split { int S, steps_per, G; };
 // Pick the K-slice length (steps_per) and the number of row groups G by a small cost
 // model of the stream, fitted to measurements on the MI355X:
 //   - every workgroup must be resident at once (it is a persistent design): one per CU;
-//   - a wavefront with PREFETCH steps in flight sustains about 2.6 GB/s under load, and all
-//     of them together about 5.3 TB/s;
+//   - a wavefront with PREFETCH steps in flight sustains about 3.6 GB/s under load, and all
+//     of them together about 6.2 TB/s (whole-line non-temporal loads; 2.6 GB/s and 5.3 TB/s before them);
 //   - the slowest wavefront (most tiles x steps) ends the kernel;
 //   - partial sums are written once and read once by the consumer, slice after slice.
 Split plan_bf16(int M, int N, int K) {
@@ -67,7 +67,7 @@ Split plan_bf16(int M, int N, int K) {
   if (max_steps < 1) max_steps = 1;
   if (max_steps > total) max_steps = total;
   const int g_max = (ntiles + GEMM_WAVES - 1) / GEMM_WAVES;
-  const double bw = 5.3e12, wave_rate = 2.6e9, step_bytes = 16.0 * KSTEP * 2;
+  const double bw = 6.2e12, wave_rate = 3.6e9, step_bytes = 16.0 * KSTEP * 2;
   Split best{1, total, 1};
   double best_cost = 1e30;
   for (int sp = max_steps; sp >= 1; --sp) {
