@@ -419,7 +419,12 @@ __global__ __launch_bounds__(SB) void row_stats_k(RowSet A, RowSet Bq, const int
 #pragma unroll
       for (int u = 0; u < NQ; ++u) {
         const int q = q0 + u * SB + threadIdx.x;
-        x[u] = q < nq ? l4[q] : float4{-INFINITY, -INFINITY, -INFINITY, -INFINITY};
+        x[u] = float4{-INFINITY, -INFINITY, -INFINITY, -INFINITY};
+        if (q < nq) {                                // read once: non-temporal, whole 128-byte lines per instruction
+          const float* src = reinterpret_cast<const float*>(l4 + q);
+          x[u] = float4{__builtin_nontemporal_load(src), __builtin_nontemporal_load(src + 1),
+                        __builtin_nontemporal_load(src + 2), __builtin_nontemporal_load(src + 3)};
+        }
       }
       ArgMax cm{-INFINITY, 0x7fffffff};
       float chk = 0.f;                               // NaN as soon as one element is NaN or infinite
