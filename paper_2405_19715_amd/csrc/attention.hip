@@ -10,9 +10,9 @@
 //   S^T = K Q^T : A operand = 16 keys x 32 d (a lane loads its key's row),
 //                 B operand = 32 d x 16 query vectors.  Result lane (qv = lane%16,
 //                 g = lane/16) holds scores of one query vector for 4 keys per tile.
-//                 The 16 rows of key tile t are the keys key0 + 16*(i/4) + 4t + i%4,
-//                 so after 4 tiles lane group g owns the 16 consecutive keys
-//                 key0 + 16g .. key0 + 16g + 15.
+//                 The 16 rows of key tile t are the keys key0 + 32 (t/2) + 8 (i/4) + 4 (t%2) + i%4,
+//                 so after 4 tiles lane group g owns the keys key0 + 8g .. + 7 (tiles 0, 1) and
+//                 key0 + 32 + 8g .. + 7 (tiles 2, 3): the k-blocks of the two value products.
 //   O^T = V^T P^T: A operand = 16 d x 32 keys = two 16-byte loads of a transposed
 //                 value row; B operand = 32 keys x 16 query vectors = exactly the
 //                 registers the scores sit in (after exp and rounding to bf16).
@@ -97,9 +97,11 @@ __global__ __launch_bounds__(256) void attn_mfma_k(const bf16_t* __restrict__ qb
         limit[q] = row_pos[m];
         orow[q] = m;
         ohead[q] = kh * G + gh;
-        const bf16_t* qp = qbuf + ((size_t)m * Hq + ohead[q]) * HD + g * (HD / 4);
+        // k-step j, lane group g takes the 8 head dimensions 32 j + 8 g .. (the same for keys below), so that
+        // one load instruction reads 64 contiguous bytes of each of its rows
+        const bf16_t* qp = qbuf + ((size_t)m * Hq + ohead[q]) * HD + g * 8;
 #pragma unroll
-        for (int j = 0; j < KS; ++j) qf[q][j] = ld16(qp + j * 8);
+        for (int j = 0; j < KS; ++j) qf[q][j] = ld16(qp + j * 32);
       }
     }
   }
@@ -128,9 +130,9 @@ __global__ __launch_bounds__(256) void attn_mfma_k(const bf16_t* __restrict__ qb
     uint4 vf[DT][2];
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt) {
-      const bf16_t* vp = vbase + (size_t)(dt * 16 + li) * max_seq + key0 + 16 * g;
-      vf[dt][0] = ld16(vp);
-      vf[dt][1] = ld16(vp + 8);
+      const bf16_t* vp = vbase + (size_t)(dt * 16 + li) * max_seq + key0 + 8 * g;
+      vf[dt][0] = ld16(vp);                    // keys key0 + 8 g .. + 7: the four lane groups read 64 contiguous bytes
+      vf[dt][1] = ld16(vp + 32);               // keys key0 + 32 + 8 g ..
     }
     // ---- scores: 4 key tiles x QTW query tiles
     floatx4 sacc[QTW][4];
@@ -140,11 +142,11 @@ __global__ __launch_bounds__(256) void attn_mfma_k(const bf16_t* __restrict__ qb
       for (int kt = 0; kt < 4; ++kt) sacc[q][kt] = floatx4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int kt = 0; kt < 4; ++kt) {
-      const int key = key0 + 16 * (li >> 2) + 4 * kt + (li & 3);          // < max_seq (multiple of 64)
-      const bf16_t* kp = kbase + (size_t)key * HD + g * (HD / 4);
+      const int key = key0 + 32 * (kt >> 1) + 8 * (li >> 2) + 4 * (kt & 1) + (li & 3);   // < max_seq (multiple of 64)
+      const bf16_t* kp = kbase + (size_t)key * HD + g * 8;
       uint4 kf[KS];
 #pragma unroll
-      for (int j = 0; j < KS; ++j) kf[j] = ld16(kp + j * 8);
+      for (int j = 0; j < KS; ++j) kf[j] = ld16(kp + j * 32);
 #pragma unroll
       for (int j = 0; j < KS; ++j)
 #pragma unroll
@@ -152,7 +154,7 @@ __global__ __launch_bounds__(256) void attn_mfma_k(const bf16_t* __restrict__ qb
           sacc[q][kt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(kf[j]), as_bf16x8(qf[q][j]),
                                                                 sacc[q][kt], 0, 0, 0);
     }
-    // ---- online softmax; lane (li, g) holds keys key0 + 16 g + 4 kt + r of query vector li
+    // ---- online softmax; lane (li, g) holds keys key0 + 32 (kt/2) + 8 g + 4 (kt%2) + r of query vector li
     uint4 pf[QTW][2];
 #pragma unroll
     for (int q = 0; q < QTW; ++q) {
@@ -161,7 +163,7 @@ __global__ __launch_bounds__(256) void attn_mfma_k(const bf16_t* __restrict__ qb
       for (int kt = 0; kt < 4; ++kt)
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-          const int key = key0 + 16 * g + 4 * kt + r;
+          const int key = key0 + 32 * (kt >> 1) + 8 * g + 4 * (kt & 1) + r;
           const float s = sacc[q][kt][r] * scale;
           sacc[q][kt][r] = s;
           if (key <= limit[q]) bmax = fmaxf(bmax, s);
@@ -176,7 +178,7 @@ __global__ __launch_bounds__(256) void attn_mfma_k(const bf16_t* __restrict__ qb
       for (int kt = 0; kt < 4; ++kt)
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-          const int key = key0 + 16 * g + 4 * kt + r;
+          const int key = key0 + 32 * (kt >> 1) + 8 * g + 4 * (kt & 1) + r;
           const float e = (key <= limit[q]) ? __expf(sacc[q][kt][r] - mnew) : 0.f;
           p[kt][r] = e;
           lsum += e;
