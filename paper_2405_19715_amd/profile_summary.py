@@ -70,10 +70,11 @@ def pmc_summary(path, skip_rounds, out):
     for a, b in zip(starts, starts[1:] + [len(rows)]):
         rnd = rows[a:b]
         cut = next((i for i, r in enumerate(rnd) if "plan_verify" in r[1]), None)
-        if cut is None:
+        end = next((i for i, r in enumerate(rnd) if "commit_k" in r[1]), None)
+        if cut is None or end is None:
             continue
         n_pass += 1
-        for _, n, _, v in rnd[cut:]:
+        for _, n, _, v in rnd[cut:end]:
             if "gemm_bf16_stream<" in n:
                 a2 = per_grid.setdefault("gemm_bf16_stream<*> (target pass)", [0, 0.0])
                 a2[0] += 1
