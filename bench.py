@@ -537,7 +537,8 @@ def main():
     achieved = tot_b / tot_s / 1e9 if tot_s > 0 else None
     verify_bytes = _algorithmic_bytes_verify(wl["target"], P_mid, wl["k_max"], batch=nb)
     rows_pass = nb * (k_mean + 1)
-    kernel = ("gemm_bf16_stream<NT> (target pass, M = K+1 rows: instance <1> for up to 16 rows, <2> for 17)"
+    kernel = ("gemm_bf16_stream<1> (target pass, M = K+1 <= 16 rows; a round that drafts all 16 has 17 rows and takes "
+              "the tiled kernel)"
               if rows_pass <= 32 else
               "gemm_bf16_tile<2,1,..> / <2,2,..> (target pass of the batch, M = sum of K_b+1 rows packed in groups "
               "of 4: one 128x64 or 128x128 m-tile holds every row, so each weight is read once)")

@@ -348,20 +348,10 @@ hipError_t launch_gemm(hipStream_t st, int dtype, const void* W, const void* X, 
   const Split sp = plan_bf16(M, N, K);
   const bf16_t* w = (const bf16_t*)W;
   const bf16_t* x = (const bf16_t*)X;
-  const int nt = (M + 15) / 16;
-  switch (nt) {
-    case 1: return launch_stream<1>(st, w, x, ldx, xrow, part, M, N, K, sp);
-    case 2: return launch_stream<2>(st, w, x, ldx, xrow, part, M, N, K, sp);
-    case 3: return launch_stream<3>(st, w, x, ldx, xrow, part, M, N, K, sp);
-    case 4: return launch_stream<4>(st, w, x, ldx, xrow, part, M, N, K, sp);
-    case 5: return launch_stream<5>(st, w, x, ldx, xrow, part, M, N, K, sp);
-    case 6: return launch_stream<6>(st, w, x, ldx, xrow, part, M, N, K, sp);
-    case 7: return launch_stream<7>(st, w, x, ldx, xrow, part, M, N, K, sp);
-    case 8: return launch_stream<8>(st, w, x, ldx, xrow, part, M, N, K, sp);
-    case 9: return launch_stream<9>(st, w, x, ldx, xrow, part, M, N, K, sp);
-    case 10: return launch_stream<10>(st, w, x, ldx, xrow, part, M, N, K, sp);
-    default: return hipErrorInvalidValue;
-  }
+  // more than one 16-row activation tile never gets here (use_tile took it); the kernel itself is written
+  // for any number of tiles, which is how the two paths were compared
+  if (M > 16) return hipErrorInvalidValue;
+  return launch_stream<1>(st, w, x, ldx, xrow, part, M, N, K, sp);
 }
 
 }  // namespace sd
