@@ -219,7 +219,7 @@ hipError_t launch_tile(hipStream_t st, const bf16_t* W, const bf16_t* X, int ldx
 }
 
 // Tile shape and K split for an (M, N, K) product.  Large M (prompt pass): the widest tile whose grid
-// covers the chip about twice, no split.  32 < M <= 192 (a batched target pass): one m-tile that holds
+// covers the chip about twice, no split unless the grid would leave CUs idle.  16 < M <= 192 (a batched target pass): one m-tile that holds
 // every row, so each weight is read once, and as many K slices as it takes to put about 384
 // workgroups on the 256 CUs; the few partial-sum slices are added by the consumer like the streaming kernel's.
 struct TilePlan { int kind, S; };          // kind: 0 = 256x256, 1 = 128x128, 2 = 128x64, 3 = 128x192
@@ -237,7 +237,8 @@ TilePlan plan_tile(int M, int N, int K) {
   const long w = wgs(bn, bm);
   int S = 1;
   constexpr int target = 384;                        // workgroups wanted: 1.5 per CU measured best (256 .. 512 tried)
-  if (M <= 192 && w < target - 32) {
+  // a prompt chunk (several m-tiles) is split only when its grid would leave CUs idle: the extra slices cost traffic
+  if (w < (M <= 192 ? target - 32 : 320)) {
     S = (int)((target + w - 1) / w);
     const int nk = K / bk;
     while (S > 1 && nk / S < 8) --S;                 // keep slices long enough to amortise the pipeline fill
