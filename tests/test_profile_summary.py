@@ -1,0 +1,46 @@
+"""The rocprofv3 trace condenser: rounds are cut at begin_round_k, a target pass at the kernel
+that plans the verify rows, and the per-kernel averages are taken over the kept rounds only."""
+import csv
+import io
+from contextlib import redirect_stdout
+
+from paper_2405_19715_amd import profile_summary as PS
+
+
+def _trace(path, n_rounds):
+    t = 1000
+    rows = []
+
+    def add(name, dur):
+        nonlocal t
+        rows.append({"Kernel_Name": name, "Start_Timestamp": t, "End_Timestamp": t + dur})
+        t += dur + 100
+    add("void sd::(anonymous namespace)::gemm_bf16_tile<2, 2, 2, 2, 64, 2>(int)", 900)      # prompt pass
+    for r in range(n_rounds):
+        add("sd::(anonymous namespace)::begin_round_k(int)", 10)
+        for _ in range(2):                                                                   # two draft steps
+            add("sd::(anonymous namespace)::plan_draft_k(int)", 10)
+            add("void sd::(anonymous namespace)::gemm_bf16_stream<1>(int)", 200)
+        add("sd::(anonymous namespace)::plan_verify_k(int)", 10)
+        for _ in range(3):
+            add("void sd::(anonymous namespace)::gemm_bf16_stream<1>(int)", 700 if r >= 1 else 5000)
+        add("sd::(anonymous namespace)::commit_k(int)", 10)
+    with open(path, "w", newline="") as f:
+        w = csv.DictWriter(f, fieldnames=list(rows[0]))
+        w.writeheader()
+        w.writerows(rows)
+
+
+def test_summary_counts_rounds_and_averages(tmp_path):
+    p = tmp_path / "trace.csv"
+    _trace(p, 4)
+    out = io.StringIO()
+    with redirect_stdout(out):
+        PS.main([str(p), "--skip-rounds", "1"])
+    text = out.getvalue()
+    assert "rounds summarised: 3 (first 1 skipped)" in text
+    assert "draft steps: 6" in text
+    # the slow first round is skipped: the target pass's GEMM averages 0.70 us over 9 launches
+    line = [l for l in text.splitlines() if "gemm_bf16_stream<1>" in l][-1]
+    assert "calls      9" in line and "avg      0.70 us" in line
+    assert "prompt pass" in text and "gemm_bf16_tile<2, 2, 2, 2, 64, 2>" in text
