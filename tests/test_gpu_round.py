@@ -570,3 +570,34 @@ def test_first_emitted_token_of_a_round_follows_the_target():
         assert want.min() > 50 and chi < 37.7, chi
     finally:
         ctx.close()
+
+
+def test_rounds_on_a_stream_of_the_callers():
+    """The context enqueues everything on the stream it was created with: built and driven under
+    a non-default torch stream, the free-running token stream must match the oracle as on the
+    default stream (a kernel or copy left on another stream would read data that is not there yet)."""
+    from paper_2405_19715_amd import binding as B
+    t, d, h = tiny_pair()
+    prompt = synth.make_prompt(40, 1024, 21)
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        ctx = _context(t, d, h, k_max=8, max_seq=192)
+        try:
+            ctx.sd_prefill(0, prompt)
+            op = R.Params(h=0.7, temperature=1.0, greedy=False, seed=8)
+            gp = B.make_params(h=0.7, temperature=1.0, greedy=False, seed=8)
+            toks, exempt, hist = run_free_running(ctx, oracle_model(t), oracle_model(d), oracle_head(h), prompt, op, gp,
+                                                  64, 8, 192)
+            assert len(toks) == 64 and exempt <= 2
+            # the isolated accept step on the same stream
+            p, q = synth.make_accept_logits(2, 4, 1024, 3)
+            cand = torch.zeros((2, 4), dtype=torch.int32)
+            n, tok, flags = B.sd_accept_resample(p.cuda(), q.cuda(), cand.cuda(),
+                                                 torch.full((2,), 4, dtype=torch.int32).cuda(), gp, 0)
+            side.synchronize()
+            for b in range(2):
+                o = sampling.accept_resample(p[b].numpy(), q[b].numpy(), cand[b].numpy(), 4, seed=8, rnd=0, seq=b)
+                assert int(n[b]) == o["n"]
+        finally:
+            ctx.close()
+    side.synchronize()
