@@ -40,6 +40,7 @@
 #include "kernels.hpp"
 
 #include <cstdlib>
+#include <vector>
 
 namespace sd {
 
@@ -60,7 +61,7 @@ struct Split { int S, steps_per, G; };
 //     of them together about 6.2 TB/s (whole-line non-temporal loads; 2.6 GB/s and 5.3 TB/s before them);
 //   - the slowest wavefront (most tiles x steps) ends the kernel;
 //   - partial sums are written once and read once by the consumer, slice after slice.
-Split plan_bf16(int M, int N, int K) {
+Split plan_bf16_search(int M, int N, int K) {
   const int total = K / KSTEP;
   const int ntiles = N / 16;
   int max_steps = LDS_MAX / (M * KSTEP * 2);
@@ -96,6 +97,20 @@ Split plan_bf16(int M, int N, int K) {
     }
   }
   return best;
+}
+
+// The search walks a few thousand candidates (tens of microseconds on the host), and every launch and every
+// consumer of the partial sums asks for the plan: remember it per shape (a forward pass has a handful of
+// shapes; the table is per host thread).
+Split plan_bf16(int M, int N, int K) {
+  struct Entry { int M, N, K; Split sp; };
+  static thread_local std::vector<Entry> table;
+  for (const Entry& e : table)
+    if (e.M == M && e.N == N && e.K == K) return e.sp;
+  const Split sp = plan_bf16_search(M, N, K);
+  if (table.size() >= 1024) table.clear();
+  table.push_back(Entry{M, N, K, sp});
+  return sp;
 }
 
 __device__ __forceinline__ uint4 ldg128(const bf16_t* p) { return *reinterpret_cast<const uint4*>(p); }
