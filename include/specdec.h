@@ -204,7 +204,9 @@ sd_status sd_profile_read(sd_ctx *ctx, int64_t *launches, double *seconds, doubl
  * W: DEVICE [N, K] and X: DEVICE [M, K], both `dtype`; Y: DEVICE fp32 [M, N]; ws: DEVICE
  * scratch of sd_gemm_workspace_bytes(...) bytes (per-K-slice partial sums, added in
  * slice order).  1 <= M <= 160; for SD_BF16, K % 128 == 0 and N % 16 == 0, pointers
- * 16-byte aligned (more than 16 rows are handed to the tiled kernel below).  Enqueued on `hip_stream`; does not synchronise. */
+ * 16-byte aligned (more than 16 rows are handed to the tiled kernel below; up to 8 rows with
+ * K % 2048 == 0 and K <= 16384 go through a kernel that streams whole 1 KB pieces of single weight
+ * rows and takes any N >= 1).  Enqueued on `hip_stream`; does not synchronise. */
 sd_status sd_gemm_skinny(int32_t dtype, const void *W_dev, const void *X_dev, int32_t M, int32_t N, int32_t K,
                          float *Y_dev, void *ws_dev, void *hip_stream);
 

@@ -281,6 +281,223 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_stream(const bf16_t* _
   }
 }
 
+
+// ----------------------------------------------------------------------------- stripe kernel
+// Few activation rows (M <= 8).  Every load instruction covers 1 KB of ONE weight row (lane l: k = 8 l .. 8 l + 7
+// of a 512-k piece); a step is four such pieces, 4 KB contiguous.  A wavefront owns one 2048-k stripe of a
+// contiguous range of rows and takes one row per step, so its stripe of X (4 x 16 bytes per lane and
+// activation row) lives in registers for the whole kernel: no LDS, no barrier.  This access pattern reads
+// HBM at 6.5-6.8 TB/s in a pure-read test (70B gate|up) where the MFMA kernel's 8 rows x 128 B per instruction
+// reach 6.4: rows are 16 KB apart, and addresses 16 KB apart meet in the same DRAM channel (the interleave is
+// 4 KB).  The matrix core cannot take operands laid out this way (it wants 16 rows x 32 k across the lanes), so
+// the products are v_dot2_f32_bf16 on the vector ALU, 4 per 16 bytes of weights and activation row, and each
+// row ends with a butterfly over the 64 lanes that reduces all MM sums at once (the lanes halve the set of
+// sums they carry at each of the first log2 MM exchanges).  The K / 2048 stripes are the K-slices of part[].
+constexpr int STRIPE_MAX_M = 8;
+constexpr size_t STRIPE_LDS_MAX = 64 * 1024;
+constexpr int PIECE = 512;               // k per 1 KB piece
+constexpr int RSTEP = 4 * PIECE;         // k per stripe = per step of 4 load instructions
+
+typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2;
+
+__device__ __forceinline__ float dot8(const uint4& w, const uint4& x, float c) {
+  union { uint32_t u; bf16x2 v; } a, b;
+  a.u = w.x; b.u = x.x; c = __builtin_amdgcn_fdot2_f32_bf16(a.v, b.v, c, false);
+  a.u = w.y; b.u = x.y; c = __builtin_amdgcn_fdot2_f32_bf16(a.v, b.v, c, false);
+  a.u = w.z; b.u = x.z; c = __builtin_amdgcn_fdot2_f32_bf16(a.v, b.v, c, false);
+  a.u = w.w; b.u = x.w; c = __builtin_amdgcn_fdot2_f32_bf16(a.v, b.v, c, false);
+  return c;
+}
+
+// Cross-lane sums without the LDS crossbar.  v_permlane32_swap (a, b) returns {a with its upper 32 lanes replaced
+// by b's lower 32, b with its lower 32 lanes replaced by a's upper 32}; v_permlane16_swap does the same with the
+// odd 16-lane rows of a and the even rows of b.  So for a pair of per-lane values (lo, hi), r = swap(lo, hi) and
+// r[0] + r[1] leaves, in the lanes whose OFF bit is clear, their own lo plus the partner's (lane ^ OFF) lo, and in
+// the lanes whose bit is set, their own hi plus the partner's hi: one exchange of a transposing butterfly.
+template <int OFF>
+__device__ __forceinline__ float swap_add(float lo, float hi) {
+  static_assert(OFF == 32 || OFF == 16, "row-crossing exchanges");
+  if constexpr (OFF == 32) {
+    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(lo), __float_as_uint(hi), false, false);
+    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+  } else {
+    const auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(lo), __float_as_uint(hi), false, false);
+    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+  }
+}
+
+template <int CTRL>
+__device__ __forceinline__ float dpp_move(float v) {
+  return __uint_as_float((uint32_t)__builtin_amdgcn_update_dpp(0, (int)__float_as_uint(v), CTRL, 0xF, 0xF, false));
+}
+constexpr int DPP_QUAD_XOR1 = 0xB1, DPP_QUAD_XOR2 = 0x4E, DPP_HALF_MIRROR = 0x141, DPP_ROR8 = 0x128;
+
+// N sums per lane become N / 2; lanes with bit OFF set keep the upper half.
+template <int N, int OFF>
+__device__ __forceinline__ void fold_stage(float* acc, int lane) {
+  constexpr int H = N / 2;
+  if constexpr (OFF >= 16) {
+#pragma unroll
+    for (int k = 0; k < H; ++k) acc[k] = swap_add<OFF>(acc[k], acc[k + H]);
+  } else {
+    static_assert(OFF == 8, "inside a 16-lane row only the 8-lane exchange is used");
+    const bool hi = (lane & 8) != 0;
+#pragma unroll
+    for (int k = 0; k < H; ++k) {
+      const float keep = hi ? acc[k + H] : acc[k];
+      const float send = hi ? acc[k] : acc[k + H];
+      acc[k] = keep + dpp_move<DPP_ROR8>(send);
+    }
+  }
+}
+
+// Sums P2 (a power of two <= 8) per-lane values over the 64 lanes; lane l ends with the total of value l / (64 / P2).
+template <int P2>
+__device__ __forceinline__ float reduce_lanes(float* acc, int lane) {
+  static_assert(P2 == 1 || P2 == 2 || P2 == 4 || P2 == 8, "power of two");
+  if constexpr (P2 == 8) { fold_stage<8, 32>(acc, lane); fold_stage<4, 16>(acc, lane); fold_stage<2, 8>(acc, lane); }
+  if constexpr (P2 == 4) { fold_stage<4, 32>(acc, lane); fold_stage<2, 16>(acc, lane); }
+  if constexpr (P2 == 2) { fold_stage<2, 32>(acc, lane); }
+  float v = acc[0];
+  if constexpr (P2 <= 1) v = swap_add<32>(v, v);
+  if constexpr (P2 <= 2) v = swap_add<16>(v, v);
+  if constexpr (P2 <= 4) v += dpp_move<DPP_ROR8>(v);
+  v += dpp_move<DPP_QUAD_XOR1>(v);
+  v += dpp_move<DPP_QUAD_XOR2>(v);
+  v += dpp_move<DPP_HALF_MIRROR>(v);
+  return v;
+}
+
+struct StripePlan { int S, G, ranges, rpw; };     // S = K / 2048 stripes; G workgroups; row ranges; rows per range
+
+StripePlan plan_stripe(int M, int N, int K) {
+  StripePlan sp{0, 0, 0, 0};
+  if (M < 1 || M > STRIPE_MAX_M || K % RSTEP != 0) return sp;
+  const int S = K / RSTEP;
+  if (S > 8) return sp;       // K > 16384: that many slices cost the consumers more than the stream gains (measured)
+  const int slots = 256 * GEMM_WAVES;
+  int ranges = slots / S;
+  if (ranges > N) ranges = N;
+  const int rpw = (N + ranges - 1) / ranges;
+  ranges = (N + rpw - 1) / rpw;
+  const int G = (ranges * S + GEMM_WAVES - 1) / GEMM_WAVES;
+  if ((size_t)GEMM_WAVES * M * rpw * sizeof(float) > STRIPE_LDS_MAX) return sp;      // the workgroup's output tiles
+  return StripePlan{S, G, ranges, rpw};
+}
+
+template <int MM>
+__global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_stripe(const bf16_t* __restrict__ W,
+                                                                 const bf16_t* __restrict__ X, int ldx,
+                                                                 const int* __restrict__ xrow,
+                                                                 float* __restrict__ part, int M, int N, int K,
+                                                                 int ranges, int rpw) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int slot = blockIdx.x * GEMM_WAVES + wave;
+  const int stripes = K / RSTEP;
+  const int c = slot % stripes, rg = slot / stripes;
+  if (rg >= ranges) return;                          // no barrier below
+  const int r0 = rg * rpw;
+  const int rows = min(rpw, N - r0);                 // >= 1: ranges = ceil(N / rpw)
+  const int rot = (slot * 5) % rows;
+  const bf16_t* base = W + (size_t)r0 * K + c * RSTEP + lane * 8;
+  auto at = [&](int t) -> const bf16_t* {
+    int r = t + rot;
+    if (r >= rows) r -= rows;
+    return base + (size_t)r * K;
+  };
+
+  // X first: its loads are then older than every weight load, and waiting for a weight step never waits for them
+  uint4 x[MM][4];                                    // M == MM (the launcher picks the instantiation)
+#pragma unroll
+  for (int m = 0; m < MM; ++m) {
+    const bf16_t* xp = X + (size_t)(xrow ? xrow[m] : m) * ldx + c * RSTEP + lane * 8;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) x[m][j] = ldg128(xp + j * PIECE);
+  }
+
+  // Every step issues its four loads without a branch around them, so that the compiler can count the loads in
+  // flight and wait for the oldest step only; past the wave's last row the address is the start of W (a
+  // line every wave shares: served by L2) and the data is not used.
+  uint4 a[PREFETCH][4];
+#pragma unroll
+  for (int p = 0; p < PREFETCH; ++p) {
+    const bf16_t* q = p < rows ? at(p) : W + lane * 8;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) a[p][j] = ldg128_stream(q + j * PIECE);
+  }
+
+  // after the butterfly lane l holds the sum of activation row l / (64 / P2); its lanes with the low bits
+  // clear put it into the wave's LDS tile [MM][rpw], which goes to part[] in one coalesced sweep at the end
+  // (no global store inside the loop: stores count like loads, and a store under a branch would make the
+  // compiler wait for every load in flight)
+  extern __shared__ float obuf[];
+  constexpr int P2 = MM <= 1 ? 1 : MM <= 2 ? 2 : MM <= 4 ? 4 : 8;
+  constexpr int LPM = 64 / P2;
+  const int my_m = lane / LPM;
+  const bool writer = (lane % LPM) == 0 && my_m < MM;
+  float* otile = obuf + (size_t)wave * MM * rpw;
+
+  for (int i0 = 0; i0 < rows; i0 += PREFETCH) {
+#pragma unroll
+    for (int p = 0; p < PREFETCH; ++p) {
+      const int i = i0 + p;
+      __builtin_amdgcn_sched_barrier(0);             // steps stay in order: the next step's data is still in flight
+      float acc[P2];
+#pragma unroll
+      for (int m = 0; m < P2; ++m) acc[m] = 0.f;
+      // the sums of one activation row form a dependent chain: the chains of the MM rows interleave
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+#pragma unroll
+        for (int m = 0; m < MM; ++m) acc[m] = dot8(a[p][j], x[m][j], acc[m]);
+      {
+        const bf16_t* q = i + PREFETCH < rows ? at(i + PREFETCH) : W + lane * 8;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) a[p][j] = ldg128_stream(q + j * PIECE);
+      }
+      const float v = reduce_lanes<P2>(acc, lane);
+      int r = i + rot;
+      if (r >= rows) r -= rows;
+      if (writer && i < rows) otile[my_m * rpw + r] = v;
+    }
+  }
+  // the wave's own tile: no barrier needed, only its LDS writes to have landed
+  __builtin_amdgcn_s_waitcnt(0xc07f);                // lgkmcnt(0)
+#pragma unroll
+  for (int m = 0; m < MM; ++m)
+    for (int r = lane; r < rows; r += WAVE) part[((size_t)c * M + m) * N + r0 + r] = otile[m * rpw + r];
+}
+
+template <int MM>
+hipError_t launch_stripe_mm(hipStream_t st, const bf16_t* W, const bf16_t* X, int ldx, const int* xrow, float* part,
+                            int M, int N, int K, StripePlan sp) {
+  const size_t lds = (size_t)GEMM_WAVES * MM * sp.rpw * sizeof(float);
+  if (lds > STRIPE_LDS_MAX) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(gemm_bf16_stripe<MM>, dim3(sp.G), dim3(GEMM_THREADS), lds, st, W, X, ldx, xrow, part, M, N, K,
+                     sp.ranges, sp.rpw);
+  return hipGetLastError();
+}
+
+hipError_t launch_stripe(hipStream_t st, const bf16_t* W, const bf16_t* X, int ldx, const int* xrow, float* part, int M,
+                         int N, int K, StripePlan sp) {
+  switch (M) {
+    case 1: return launch_stripe_mm<1>(st, W, X, ldx, xrow, part, M, N, K, sp);
+    case 2: return launch_stripe_mm<2>(st, W, X, ldx, xrow, part, M, N, K, sp);
+    case 3: return launch_stripe_mm<3>(st, W, X, ldx, xrow, part, M, N, K, sp);
+    case 4: return launch_stripe_mm<4>(st, W, X, ldx, xrow, part, M, N, K, sp);
+    case 5: return launch_stripe_mm<5>(st, W, X, ldx, xrow, part, M, N, K, sp);
+    case 6: return launch_stripe_mm<6>(st, W, X, ldx, xrow, part, M, N, K, sp);
+    case 7: return launch_stripe_mm<7>(st, W, X, ldx, xrow, part, M, N, K, sp);
+    case 8: return launch_stripe_mm<8>(st, W, X, ldx, xrow, part, M, N, K, sp);
+    default: return hipErrorInvalidValue;
+  }
+}
+
+// Up to 8 activation rows and K a multiple of 2048 up to 16384: measured equal or faster than the MFMA kernel on
+// every such matrix of the 70B / 7B shapes, alone and inside the forward pass (70B target pass, 1 .. 8 rows:
+// 2 - 6 % shorter).
+bool use_stripe(int M, int N, int K) { return plan_stripe(M, N, K).S > 0; }
+
 // ----------------------------------------------------------------------------- fp32 path
 // One wavefront per output column n; lanes stride over k; up to 8 activation rows at
 // a time.  Sizes here are tiny (d = 256), so nothing is tuned.
@@ -342,6 +559,7 @@ bool use_tile(int M, int N, int K) { return M > STREAM_MAX_ROWS && K % 32 == 0 &
 int gemm_splits(int dtype, int M, int N, int K) {
   if (dtype == DT_F32) return 1;
   if (use_tile(M, N, K)) return gemm_tile_splits(M, N, K);
+  if (use_stripe(M, N, K)) return plan_stripe(M, N, K).S;
   return plan_bf16(M, N, K).S;
 }
 
@@ -356,6 +574,12 @@ hipError_t launch_gemm(hipStream_t st, int dtype, const void* W, const void* X, 
   }
   if (dtype != DT_BF16) return hipErrorInvalidValue;
   if (use_tile(M, N, K)) return launch_gemm_tile(st, W, X, ldx, xrow, part, M, N, K);
+  if (use_stripe(M, N, K)) {
+    if (ldx % 8 != 0 ||
+        ((reinterpret_cast<uintptr_t>(W) | reinterpret_cast<uintptr_t>(X) | reinterpret_cast<uintptr_t>(part)) & 15))
+      return hipErrorInvalidValue;
+    return launch_stripe(st, (const bf16_t*)W, (const bf16_t*)X, ldx, xrow, part, M, N, K, plan_stripe(M, N, K));
+  }
   // 16-byte loads along K, 16-row tiles along N, 16-byte aligned rows
   if (K % KSTEP != 0 || N % 16 != 0 || ldx % 8 != 0) return hipErrorInvalidValue;
   if ((reinterpret_cast<uintptr_t>(W) | reinterpret_cast<uintptr_t>(X) | reinterpret_cast<uintptr_t>(part)) & 15)

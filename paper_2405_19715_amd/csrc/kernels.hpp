@@ -17,7 +17,10 @@ constexpr int MAX_PREFILL_ROWS = 1024; // most rows of one prompt-pass chunk (ti
 // optionally gathered through xrow (device int32 [M], may be null).
 // The number of K-slices is gemm_splits(dtype, M, N, K); consumers add the slices
 // in slice order.  bf16 products with more than 16 rows go through the tiled kernel
-// (launch_gemm_tile), which reads every weight once however many rows there are.
+// (launch_gemm_tile), which reads every weight once however many rows there are; up to 8
+// rows with K % 2048 == 0, K <= 16384 through the row-stripe kernel (vector-ALU dot products
+// on whole 1 KB row pieces: the access pattern that reads HBM fastest), the rest through the
+// MFMA streaming kernel.
 int gemm_splits(int dtype, int M, int N, int K);
 hipError_t launch_gemm(hipStream_t st, int dtype, const void* W, const void* X, int ldx, const int* xrow,
                        float* part, int M, int N, int K);

@@ -32,6 +32,31 @@ def test_bf16_model_shapes(shape):
     _check(*shape, torch.bfloat16, 7, 3e-5)
 
 
+# Up to 8 rows with K a multiple of 2048 (up to 16384) take the kernel that streams whole 1 KB row pieces and
+# multiplies on the vector ALU: every row count (each has its own instantiation and lane reduction), one to eight
+# K stripes, row counts N that leave ragged row ranges (fewer rows than wavefronts, a short last range, N odd)
+@pytest.mark.parametrize("M", [1, 2, 3, 4, 5, 6, 7, 8])
+def test_bf16_row_stripes(M):
+    _check(M, 4096 + 16 * 7, 2048, torch.bfloat16, 40 + M, 2e-5)       # one stripe, 2 rows per wavefront + a ragged end
+    _check(M, 1001, 4096, torch.bfloat16, 50 + M, 2e-5)                 # two stripes, fewer rows than wavefronts, odd N
+    _check(M, 2560, 8192, torch.bfloat16, 60 + M, 3e-5)                 # four stripes (the 70B shape's K)
+
+
+@pytest.mark.parametrize("shape", [(8, 640, 16384), (3, 5, 2048), (1, 1, 2048), (7, 32000, 2048), (2, 57344, 8192)])
+def test_bf16_row_stripes_extremes(shape):
+    _check(*shape, torch.bfloat16, 9, 3e-5)
+
+
+def test_bf16_rows_beyond_the_stripe_kernel_take_the_matrix_cores():
+    from paper_2405_19715_amd import binding as B
+    # 9 rows, or K not a multiple of 2048, or more than 8 stripes: partial-sum slices follow the other planner
+    assert B.lib.sd_gemm_workspace_bytes(B.SD_BF16, 8, 8192, 8192) == 4 * 8 * 8192 * 4
+    assert B.lib.sd_gemm_workspace_bytes(B.SD_BF16, 2, 4096, 4096) == 2 * 2 * 4096 * 4
+    _check(9, 2560, 8192, torch.bfloat16, 3, 3e-5)
+    _check(4, 8192, 2048 * 9, torch.bfloat16, 3, 3e-5)
+    _check(4, 4096, 2048 + 128, torch.bfloat16, 3, 3e-5)
+
+
 @pytest.mark.parametrize("shape", [(1, 256, 256), (9, 1024, 256), (17, 688 * 2, 256), (32, 256, 688), (3, 7, 5)])
 def test_fp32(shape):
     _check(*shape, torch.float32, 11, 2e-6)
