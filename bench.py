@@ -537,8 +537,8 @@ def main():
     achieved = tot_b / tot_s / 1e9 if tot_s > 0 else None
     verify_bytes = _algorithmic_bytes_verify(wl["target"], P_mid, wl["k_max"], batch=nb)
     rows_pass = nb * (k_mean + 1)
-    kernel = ("gemm_bf16_stream<1> (target pass, M = K+1 <= 16 rows; a round that drafts all 16 has 17 rows and takes "
-              "the tiled kernel)"
+    kernel = ("weight-streaming GEMMs of the target pass: gemm_bf16_stripe<M> (q|k|v, o, gate|up, LM head with M = K+1 <= 8 "
+              "rows) and gemm_bf16_stream<1> (down; all five matrices with 9..16 rows; 17 rows take the tiled kernel)"
               if rows_pass <= 32 else
               "gemm_bf16_tile<2,1,..> / <2,2,..> (target pass of the batch, M = sum of K_b+1 rows packed in groups "
               "of 4: one 128x64 or 128x128 m-tile holds every row, so each weight is read once)")

@@ -368,21 +368,27 @@ __device__ __forceinline__ float reduce_lanes(float* acc, int lane) {
   return v;
 }
 
-struct StripePlan { int S, G, ranges, rpw; };     // S = K / 2048 stripes; G workgroups; row ranges; rows per range
+// cs stripes of the same rows sit in one workgroup and are added there, so part[] gets S = (K / 2048) / cs slices:
+// one for K up to 16384, two for the 70B down projection (14 stripes, 7 per workgroup).
+struct StripePlan { int S, cs, rpg, G, ranges, rpw; };   // rpg row ranges per workgroup (cs * rpg wavefronts); G workgroups per slice
 
 StripePlan plan_stripe(int M, int N, int K) {
-  StripePlan sp{0, 0, 0, 0};
-  if (M < 1 || M > STRIPE_MAX_M || K % RSTEP != 0) return sp;
-  const int S = K / RSTEP;
-  if (S > 8) return sp;       // K > 16384: that many slices cost the consumers more than the stream gains (measured)
-  const int slots = 256 * GEMM_WAVES;
-  int ranges = slots / S;
+  StripePlan sp{0, 0, 0, 0, 0, 0};
+  if (M < 1 || M > STRIPE_MAX_M || N < 1 || K < RSTEP || K % RSTEP != 0) return sp;
+  const int stripes = K / RSTEP;
+  int cs = 1;
+  for (int d = 2; d <= GEMM_WAVES; ++d)
+    if (stripes % d == 0) cs = d;
+  const int S = stripes / cs;
+  if (S > 4) return sp;                              // more slices than the consumers should have to walk
+  const int rpg = GEMM_WAVES / cs;
+  int ranges = 256 * rpg / S;                        // one workgroup per CU
   if (ranges > N) ranges = N;
   const int rpw = (N + ranges - 1) / ranges;
   ranges = (N + rpw - 1) / rpw;
-  const int G = (ranges * S + GEMM_WAVES - 1) / GEMM_WAVES;
-  if ((size_t)GEMM_WAVES * M * rpw * sizeof(float) > STRIPE_LDS_MAX) return sp;      // the workgroup's output tiles
-  return StripePlan{S, G, ranges, rpw};
+  const int G = (ranges + rpg - 1) / rpg;
+  if ((size_t)cs * rpg * M * rpw * sizeof(float) > STRIPE_LDS_MAX) return sp;         // the wavefronts' output tiles
+  return StripePlan{S, cs, rpg, G, ranges, rpw};
 }
 
 template <int MM>
@@ -390,16 +396,15 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_stripe(const bf16_t* _
                                                                  const bf16_t* __restrict__ X, int ldx,
                                                                  const int* __restrict__ xrow,
                                                                  float* __restrict__ part, int M, int N, int K,
-                                                                 int ranges, int rpw) {
+                                                                 int cs, int rpg, int ranges, int rpw) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int slot = blockIdx.x * GEMM_WAVES + wave;
-  const int stripes = K / RSTEP;
-  const int c = slot % stripes, rg = slot / stripes;
-  if (rg >= ranges) return;                          // no barrier below
+  const int lr = wave / cs, ls = wave - lr * cs;     // local row range, local stripe
+  const int rg = blockIdx.x * rpg + lr;
+  const int c = blockIdx.y * cs + ls;                // stripe of K
   const int r0 = rg * rpw;
-  const int rows = min(rpw, N - r0);                 // >= 1: ranges = ceil(N / rpw)
-  const int rot = (slot * 5) % rows;
-  const bf16_t* base = W + (size_t)r0 * K + c * RSTEP + lane * 8;
+  const int rows = rg < ranges ? min(rpw, N - r0) : 0;           // a wavefront without rows still meets the barrier
+  const int rot = rows > 0 ? ((rg * (K / RSTEP) + c) * 5) % rows : 0;
+  const bf16_t* base = W + (size_t)(rows > 0 ? r0 : 0) * K + c * RSTEP + lane * 8;
   auto at = [&](int t) -> const bf16_t* {
     int r = t + rot;
     if (r >= rows) r -= rows;
@@ -427,9 +432,9 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_stripe(const bf16_t* _
   }
 
   // after the butterfly lane l holds the sum of activation row l / (64 / P2); its lanes with the low bits
-  // clear put it into the wave's LDS tile [MM][rpw], which goes to part[] in one coalesced sweep at the end
-  // (no global store inside the loop: stores count like loads, and a store under a branch would make the
-  // compiler wait for every load in flight)
+  // clear put it into the wave's LDS tile [MM][rpw]; the tiles of the cs stripes are added and go to part[] in
+  // one coalesced sweep at the end (no global store inside the loop: stores count like loads, and a store
+  // under a branch would make the compiler wait for every load in flight)
   extern __shared__ float obuf[];
   constexpr int P2 = MM <= 1 ? 1 : MM <= 2 ? 2 : MM <= 4 ? 4 : 8;
   constexpr int LPM = 64 / P2;
@@ -461,20 +466,28 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_stripe(const bf16_t* _
       if (writer && i < rows) otile[my_m * rpw + r] = v;
     }
   }
-  // the wave's own tile: no barrier needed, only its LDS writes to have landed
-  __builtin_amdgcn_s_waitcnt(0xc07f);                // lgkmcnt(0)
-#pragma unroll
-  for (int m = 0; m < MM; ++m)
-    for (int r = lane; r < rows; r += WAVE) part[((size_t)c * M + m) * N + r0 + r] = otile[m * rpw + r];
+  __syncthreads();
+  // stripe tiles of one row range are added in stripe order
+  const int tile = MM * rpw;
+  for (int idx = threadIdx.x; idx < rpg * tile; idx += blockDim.x) {
+    const int l = idx / tile, rem = idx - l * tile;
+    const int m = rem / rpw, r = rem - m * rpw;
+    const int g = blockIdx.x * rpg + l;
+    if (g >= ranges || g * rpw + r >= N) continue;
+    const float* src = obuf + (size_t)l * cs * tile + rem;
+    float sum = src[0];
+    for (int t = 1; t < cs; ++t) sum += src[(size_t)t * tile];
+    part[((size_t)blockIdx.y * M + m) * N + g * rpw + r] = sum;
+  }
 }
 
 template <int MM>
 hipError_t launch_stripe_mm(hipStream_t st, const bf16_t* W, const bf16_t* X, int ldx, const int* xrow, float* part,
                             int M, int N, int K, StripePlan sp) {
-  const size_t lds = (size_t)GEMM_WAVES * MM * sp.rpw * sizeof(float);
+  const size_t lds = (size_t)sp.cs * sp.rpg * MM * sp.rpw * sizeof(float);
   if (lds > STRIPE_LDS_MAX) return hipErrorInvalidValue;
-  hipLaunchKernelGGL(gemm_bf16_stripe<MM>, dim3(sp.G), dim3(GEMM_THREADS), lds, st, W, X, ldx, xrow, part, M, N, K,
-                     sp.ranges, sp.rpw);
+  hipLaunchKernelGGL(gemm_bf16_stripe<MM>, dim3(sp.G, sp.S), dim3(sp.cs * sp.rpg * WAVE), lds, st, W, X, ldx, xrow, part,
+                     M, N, K, sp.cs, sp.rpg, sp.ranges, sp.rpw);
   return hipGetLastError();
 }
 

@@ -18,6 +18,9 @@ import re
 import sys
 
 
+STREAMING = "gemm_bf16_str"          # gemm_bf16_stripe<M> and gemm_bf16_stream<NT>
+
+
 def short_name(name: str) -> str:
     name = name.replace("(anonymous namespace)::", "")
     m = re.match(r"(?:void )?([\w:]+(?:<[^(]*>)?)", name)
@@ -47,6 +50,12 @@ def table(segments, title, out):
               f"idle between kernels {(span - busy) / 1e6:.3f} ms\n")
     for name, (n, t) in sorted(agg.items(), key=lambda kv: -kv[1][1]):
         out.write(f"  {name:48s} calls {n:6d}  avg {t / n / 1e3:9.2f} us  total {t / 1e6:9.3f} ms  {100.0 * t / span:5.1f}%\n")
+    # the weight-streaming GEMMs come as several kernels (one stripe instantiation per row count, the MFMA kernel)
+    ws = [(n, t) for name, (n, t) in agg.items() if STREAMING in name]
+    if len(ws) > 1:
+        n, t = sum(a for a, _ in ws), sum(b for _, b in ws)
+        out.write(f"  {'all weight-streaming GEMMs (stripe<*> + stream<*>)':48s} calls {n:6d}  avg {t / n / 1e3:9.2f} us  "
+                  f"total {t / 1e6:9.3f} ms  {100.0 * t / span:5.1f}%\n")
 
 
 def pmc_summary(path, skip_rounds, out):
@@ -75,8 +84,8 @@ def pmc_summary(path, skip_rounds, out):
             continue
         n_pass += 1
         for _, n, _, v in rnd[cut:end]:
-            if "gemm_bf16_stream<" in n:
-                a2 = per_grid.setdefault("gemm_bf16_stream<*> (target pass)", [0, 0.0])
+            if STREAMING in n:
+                a2 = per_grid.setdefault("gemm_bf16_stripe<*> + gemm_bf16_stream<*> (target pass)", [0, 0.0])
                 a2[0] += 1
                 a2[1] += v
     for k, (n, tot) in per_grid.items():

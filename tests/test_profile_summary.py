@@ -24,6 +24,7 @@ def _trace(path, n_rounds):
         add("sd::(anonymous namespace)::plan_verify_k(int)", 10)
         for _ in range(3):
             add("void sd::(anonymous namespace)::gemm_bf16_stream<1>(int)", 700 if r >= 1 else 5000)
+        add("void sd::(anonymous namespace)::gemm_bf16_stripe<5>(int)", 300)
         add("sd::(anonymous namespace)::commit_k(int)", 10)
     with open(path, "w", newline="") as f:
         w = csv.DictWriter(f, fieldnames=list(rows[0]))
@@ -43,4 +44,7 @@ def test_summary_counts_rounds_and_averages(tmp_path):
     # the slow first round is skipped: the target pass's GEMM averages 0.70 us over 9 launches
     line = [l for l in text.splitlines() if "gemm_bf16_stream<1>" in l][-1]
     assert "calls      9" in line and "avg      0.70 us" in line
+    # the weight-streaming kernels of the target pass also get one line together: (9 * 700 + 3 * 300) / 12 ns
+    line = [l for l in text.splitlines() if "all weight-streaming GEMMs" in l][-1]
+    assert "calls     12" in line and "avg      0.60 us" in line
     assert "prompt pass" in text and "gemm_bf16_tile<2, 2, 2, 2, 64, 2>" in text
