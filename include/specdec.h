@@ -210,6 +210,21 @@ sd_status sd_profile_read(sd_ctx *ctx, int64_t *launches, double *seconds, doubl
 sd_status sd_gemm_skinny(int32_t dtype, const void *W_dev, const void *X_dev, int32_t M, int32_t N, int32_t K,
                          float *Y_dev, void *ws_dev, void *hip_stream);
 
+/* The gated activation of a decoder layer's MLP as both forward passes of Algorithm 2 compute it:
+ *   act[m, f] = silu(sum_k X[m, k] W[f, k]) * (sum_k X[m, k] W[ffn + f, k]),   silu(z) = z / (1 + exp(-z)),
+ * W: DEVICE [2 ffn, K] = [gate; up] and X: DEVICE [M, K], both `dtype`; act: DEVICE [M, ffn] in `dtype`.
+ * Two ways to the same result, both rounding once, to `dtype`, at the end:
+ *   mode 1: ONE launch, the row-stripe GEMM with the activation in its final sweep; ws is not used.  Possible
+ *           (sd_mlp_act_is_fused returns 1) for SD_BF16, M <= 8, K a multiple of 2048 up to 8192; SD_EINVAL elsewhere.
+ *   mode 0: sd_gemm_skinny's product followed by an activation kernel; ws is DEVICE scratch of
+ *           sd_gemm_workspace_bytes(dtype, M, 2 ffn, K) bytes.
+ *   mode -1: what the forward passes do: mode 1 where it is possible, else mode 0.
+ * 1 <= M <= 160 and sd_gemm_skinny's shape rules with N = 2 ffn; SD_EINVAL / SD_EDEVICE otherwise.
+ * Enqueued on `hip_stream`; does not synchronise. */
+int32_t sd_mlp_act_is_fused(int32_t dtype, int32_t M, int32_t ffn, int32_t K);
+sd_status sd_mlp_act(int32_t dtype, const void *W_gate_up_dev, const void *X_dev, int32_t M, int32_t ffn, int32_t K,
+                     void *act_dev, void *ws_dev, int32_t mode, void *hip_stream);
+
 /* ---- Training of the acceptance-prediction head (Sec. 4.4) ---------------------------
  *
  * sd_head_examples builds the training examples of one (prompt, response) pair with the

@@ -87,6 +87,9 @@ _PROTOS = {
     "sd_trainer_predict": (C.c_int32, [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p]),
     "sd_trainer_read": (C.c_int32, [C.c_void_p, C.c_int32, C.c_int32, _f32p]),
     "sd_trainer_export": (C.c_int32, [C.c_void_p, C.c_int32, _vpp, _vpp]),
+    "sd_mlp_act": (C.c_int32, [C.c_int32, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p,
+                               C.c_void_p, C.c_int32, C.c_void_p]),
+    "sd_mlp_act_is_fused": (C.c_int32, [C.c_int32, C.c_int32, C.c_int32, C.c_int32]),
     "sd_gemm_tile": (C.c_int32, [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p,
                                  C.c_void_p]),
     "sd_gemm_tile_workspace_bytes": (C.c_int64, [C.c_int32, C.c_int32, C.c_int32]),
@@ -291,6 +294,26 @@ def sd_gemm_skinny(W: torch.Tensor, X: torch.Tensor, out=None) -> torch.Tensor:
     _check(lib.sd_gemm_skinny(dt, W.data_ptr(), X.data_ptr(), M, N, K, Y.data_ptr(), ws.data_ptr(), _stream_ptr()),
            "sd_gemm_skinny")
     return Y
+
+
+def sd_mlp_act(W_gate_up: torch.Tensor, X: torch.Tensor, mode: int = -1) -> torch.Tensor:
+    """silu(X Wg^T) * (X Wu^T) in the inputs' dtype.  W_gate_up [2 ffn, K] = [gate; up], X [M, K], CUDA, contiguous.
+    mode 1: the one-launch kernel, 0: product + activation kernel, -1: the forward passes' choice."""
+    W = W_gate_up
+    assert W.is_cuda and X.is_cuda and W.is_contiguous() and X.is_contiguous() and W.dtype == X.dtype
+    (N2, K), (M, K2) = W.shape, X.shape
+    assert K == K2 and N2 % 2 == 0
+    dt = _dtype_code(W.dtype)
+    act = torch.empty((M, N2 // 2), dtype=W.dtype, device=W.device)
+    nbytes = lib.sd_gemm_workspace_bytes(dt, M, N2, K)
+    ws = torch.empty(max(nbytes, 16), dtype=torch.uint8, device=W.device)
+    _check(lib.sd_mlp_act(dt, W.data_ptr(), X.data_ptr(), M, N2 // 2, K, act.data_ptr(), ws.data_ptr(), mode,
+                          _stream_ptr()), "sd_mlp_act")
+    return act
+
+
+def sd_mlp_act_is_fused(dtype: torch.dtype, M: int, ffn: int, K: int) -> bool:
+    return bool(lib.sd_mlp_act_is_fused(_dtype_code(dtype), M, ffn, K))
 
 
 def sd_gemm_tile(W: torch.Tensor, X: torch.Tensor, out: Optional[torch.Tensor] = None) -> torch.Tensor:

@@ -248,6 +248,7 @@ sd_status forward(sd_ctx* c, ModelRt& rt, int M, int RS, int max_kv_len, const i
     return gemm(c, rt, W, X, ldx, nullptr, M, N, K, prof_kind);
   };
   auto slices = [&](int N, int K) { return gemm_splits(dt, M, N, K); };
+  const bool fuse_act = gemm_silu_fused(dt, M, m.d_ffn, d);     // gate|up GEMM writes silu(gate) * up itself
   SD_HIP(launch_embed_norm(st, dt, m.tok_emb, rt.na[0], m.rms_eps, c->rows.tok, c->x, c->xn, c->ssq, M, d, m.vocab));
   for (int l = 0; l < m.n_layers; ++l) {
     const bool pr = profile && c->prof_every > 0 && (l % c->prof_every) == 0;
@@ -261,8 +262,14 @@ sd_status forward(sd_ctx* c, ModelRt& rt, int M, int RS, int max_kv_len, const i
                             m.n_kv_heads, m.head_dim, c->cfg.max_seq, max_kv_len, tile));
     if ((s = mm(rt.wo[l], c->attn, nq, d, nq, pr ? 1 : -1)) != SD_OK) return s;
     SD_HIP(launch_add_norm(st, dt, c->part, slices(d, nq), rt.nm[l], m.rms_eps, c->x, c->xn, c->ssq, M, d));
-    if ((s = mm(rt.wgu[l], c->xn, d, 2 * m.d_ffn, d, pr ? 2 : -1)) != SD_OK) return s;
-    SD_HIP(launch_silu_mul(st, dt, c->part, slices(2 * m.d_ffn, d), c->act, M, m.d_ffn));
+    if (fuse_act) {
+      ProfSample* ps = pr ? prof_begin(c, 2, 2.0 * m.d_ffn * d * rt.esz) : nullptr;
+      SD_HIP(launch_gemm_silu(st, dt, rt.wgu[l], c->xn, d, nullptr, c->act, M, m.d_ffn, d));
+      if (ps) (void)hipEventRecord(ps->b, st);
+    } else {
+      if ((s = mm(rt.wgu[l], c->xn, d, 2 * m.d_ffn, d, pr ? 2 : -1)) != SD_OK) return s;
+      SD_HIP(launch_silu_mul(st, dt, c->part, slices(2 * m.d_ffn, d), c->act, M, m.d_ffn));
+    }
     if ((s = mm(rt.wdown[l], c->act, m.d_ffn, d, m.d_ffn, pr ? 3 : -1)) != SD_OK) return s;
     const void* g_next = (l + 1 < m.n_layers) ? rt.na[l + 1] : m.final_norm;
     SD_HIP(launch_add_norm(st, dt, c->part, slices(d, m.d_ffn), g_next, m.rms_eps, c->x, c->xn, c->ssq, M, d));
@@ -863,6 +870,29 @@ sd_status sd_gemm_skinny(int32_t dtype, const void* W, const void* X, int32_t M,
   hipStream_t st = (hipStream_t)hip_stream;
   SD_HIP(launch_gemm(st, dtype, W, X, K, nullptr, (float*)ws, M, N, K));
   SD_HIP(launch_reduce_rows(st, (const float*)ws, gemm_splits(dtype, M, N, K), Y, M, 0, N, M, N));
+  return SD_OK;
+}
+
+int32_t sd_mlp_act_is_fused(int32_t dtype, int32_t M, int32_t ffn, int32_t K) {
+  if ((dtype != SD_F32 && dtype != SD_BF16) || M < 1 || M > MAX_ROWS || ffn < 1 || K < 1) return 0;
+  return gemm_silu_fused(dtype, M, ffn, K) ? 1 : 0;
+}
+
+sd_status sd_mlp_act(int32_t dtype, const void* W_gate_up, const void* X, int32_t M, int32_t ffn, int32_t K,
+                     void* act, void* ws, int32_t mode, void* hip_stream) {
+  if (!W_gate_up || !X || !act || (dtype != SD_F32 && dtype != SD_BF16) || M < 1 || M > MAX_ROWS || ffn < 1 || K < 1 ||
+      mode < -1 || mode > 1)
+    return SD_EINVAL;
+  hipStream_t st = (hipStream_t)hip_stream;
+  const bool can = gemm_silu_fused(dtype, M, ffn, K);
+  if (mode == 1 && !can) return SD_EINVAL;
+  if (mode != 0 && can) {
+    SD_HIP(launch_gemm_silu(st, dtype, W_gate_up, X, K, nullptr, act, M, ffn, K));
+    return SD_OK;
+  }
+  if (!ws) return SD_EINVAL;
+  SD_HIP(launch_gemm(st, dtype, W_gate_up, X, K, nullptr, (float*)ws, M, 2 * ffn, K));
+  SD_HIP(launch_silu_mul(st, dtype, (const float*)ws, gemm_splits(dtype, M, 2 * ffn, K), act, M, ffn));
   return SD_OK;
 }
 

@@ -372,7 +372,9 @@ __device__ __forceinline__ float reduce_lanes(float* acc, int lane) {
 // one for K up to 16384, two for the 70B down projection (14 stripes, 7 per workgroup).
 struct StripePlan { int S, cs, rpg, G, ranges, rpw; };   // rpg row ranges per workgroup (cs * rpg wavefronts); G workgroups per slice
 
-StripePlan plan_stripe(int M, int N, int K) {
+// paired: N is the row count of each half of a [gate; up] matrix, and a workgroup takes its ranges in pairs
+// (needs one slice and an even number of ranges per workgroup)
+StripePlan plan_stripe(int M, int N, int K, bool paired = false) {
   StripePlan sp{0, 0, 0, 0, 0, 0};
   if (M < 1 || M > STRIPE_MAX_M || N < 1 || K < RSTEP || K % RSTEP != 0) return sp;
   const int stripes = K / RSTEP;
@@ -382,27 +384,35 @@ StripePlan plan_stripe(int M, int N, int K) {
   const int S = stripes / cs;
   if (S > 4) return sp;                              // more slices than the consumers should have to walk
   const int rpg = GEMM_WAVES / cs;
-  int ranges = 256 * rpg / S;                        // one workgroup per CU
+  if (paired && (S != 1 || (rpg & 1))) return sp;
+  const int units = paired ? rpg / 2 : rpg;          // ranges of N a workgroup covers
+  int ranges = 256 * units / S;                      // one workgroup per CU
   if (ranges > N) ranges = N;
   const int rpw = (N + ranges - 1) / ranges;
   ranges = (N + rpw - 1) / rpw;
-  const int G = (ranges + rpg - 1) / rpg;
+  const int G = (ranges + units - 1) / units;
   if ((size_t)cs * rpg * M * rpw * sizeof(float) > STRIPE_LDS_MAX) return sp;         // the wavefronts' output tiles
   return StripePlan{S, cs, rpg, G, ranges, rpw};
 }
 
-template <int MM>
+// SILU: W = [gate; up] with N rows each (2 N in all), one slice (cs = K / 2048), rpg even: the workgroup's local
+// ranges come in pairs, range g of gate and range g of up, and the final sweep writes act[m, n] = silu(gate) * up in
+// bf16 instead of partial sums: the MLP's activation without a launch of its own.
+template <int MM, bool SILU>
 __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_stripe(const bf16_t* __restrict__ W,
                                                                  const bf16_t* __restrict__ X, int ldx,
                                                                  const int* __restrict__ xrow,
-                                                                 float* __restrict__ part, int M, int N, int K,
-                                                                 int cs, int rpg, int ranges, int rpw) {
+                                                                 float* __restrict__ part, bf16_t* __restrict__ act,
+                                                                 int M, int N, int K, int cs, int rpg, int ranges,
+                                                                 int rpw) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int lr = wave / cs, ls = wave - lr * cs;     // local row range, local stripe
-  const int rg = blockIdx.x * rpg + lr;
-  const int c = blockIdx.y * cs + ls;                // stripe of K
-  const int r0 = rg * rpw;
-  const int rows = rg < ranges ? min(rpw, N - r0) : 0;           // a wavefront without rows still meets the barrier
+  const int rg = SILU ? blockIdx.x * (rpg >> 1) + (lr >> 1) : blockIdx.x * rpg + lr;
+  // stripe of K.  SILU: gate and up are a multiple of 2^26 bytes apart for the 70B shape (the same DRAM channel and
+  // bank at equal k), and a pair's wavefronts run side by side: the up wavefronts take their stripes one further
+  const int c = blockIdx.y * cs + (SILU && (lr & 1) ? (ls + 1 == cs ? 0 : ls + 1) : ls);
+  const int r0 = rg * rpw + (SILU && (lr & 1) ? N : 0);          // SILU: odd local ranges are the rows of `up`
+  const int rows = rg < ranges ? min(rpw, N - rg * rpw) : 0;     // a wavefront without rows still meets the barrier
   const int rot = rows > 0 ? ((rg * (K / RSTEP) + c) * 5) % rows : 0;
   const bf16_t* base = W + (size_t)(rows > 0 ? r0 : 0) * K + c * RSTEP + lane * 8;
   auto at = [&](int t) -> const bf16_t* {
@@ -469,39 +479,58 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_stripe(const bf16_t* _
   __syncthreads();
   // stripe tiles of one row range are added in stripe order
   const int tile = MM * rpw;
-  for (int idx = threadIdx.x; idx < rpg * tile; idx += blockDim.x) {
-    const int l = idx / tile, rem = idx - l * tile;
-    const int m = rem / rpw, r = rem - m * rpw;
-    const int g = blockIdx.x * rpg + l;
-    if (g >= ranges || g * rpw + r >= N) continue;
-    const float* src = obuf + (size_t)l * cs * tile + rem;
-    float sum = src[0];
-    for (int t = 1; t < cs; ++t) sum += src[(size_t)t * tile];
-    part[((size_t)blockIdx.y * M + m) * N + g * rpw + r] = sum;
+  if constexpr (SILU) {
+    for (int idx = threadIdx.x; idx < (rpg >> 1) * tile; idx += blockDim.x) {
+      const int l = idx / tile, rem = idx - l * tile;
+      const int m = rem / rpw, r = rem - m * rpw;
+      const int g = blockIdx.x * (rpg >> 1) + l;
+      if (g >= ranges || g * rpw + r >= N) continue;
+      const float* sg = obuf + (size_t)(2 * l) * cs * tile + rem;
+      const float* su = sg + (size_t)cs * tile;
+      // both in stripe order (stripe t of `up` sits in the tile of local wavefront t - 1)
+      float gate = sg[0], up = su[(size_t)(cs - 1) * tile];
+      for (int t = 1; t < cs; ++t) {
+        gate += sg[(size_t)t * tile];
+        up += su[(size_t)(t - 1) * tile];
+      }
+      act[(size_t)m * N + g * rpw + r] = f2bf(gate / (1.0f + expf(-gate)) * up);
+    }
+  } else {
+    for (int idx = threadIdx.x; idx < rpg * tile; idx += blockDim.x) {
+      const int l = idx / tile, rem = idx - l * tile;
+      const int m = rem / rpw, r = rem - m * rpw;
+      const int g = blockIdx.x * rpg + l;
+      if (g >= ranges || g * rpw + r >= N) continue;
+      const float* src = obuf + (size_t)l * cs * tile + rem;
+      float sum = src[0];
+      for (int t = 1; t < cs; ++t) sum += src[(size_t)t * tile];
+      part[((size_t)blockIdx.y * M + m) * N + g * rpw + r] = sum;
+    }
   }
 }
 
-template <int MM>
+template <int MM, bool SILU>
 hipError_t launch_stripe_mm(hipStream_t st, const bf16_t* W, const bf16_t* X, int ldx, const int* xrow, float* part,
-                            int M, int N, int K, StripePlan sp) {
+                            bf16_t* act, int M, int N, int K, StripePlan sp) {
   const size_t lds = (size_t)sp.cs * sp.rpg * MM * sp.rpw * sizeof(float);
   if (lds > STRIPE_LDS_MAX) return hipErrorInvalidValue;
-  hipLaunchKernelGGL(gemm_bf16_stripe<MM>, dim3(sp.G, sp.S), dim3(sp.cs * sp.rpg * WAVE), lds, st, W, X, ldx, xrow, part,
-                     M, N, K, sp.cs, sp.rpg, sp.ranges, sp.rpw);
+  hipLaunchKernelGGL((gemm_bf16_stripe<MM, SILU>), dim3(sp.G, sp.S), dim3(sp.cs * sp.rpg * WAVE), lds, st, W, X, ldx,
+                     xrow, part, act, M, N, K, sp.cs, sp.rpg, sp.ranges, sp.rpw);
   return hipGetLastError();
 }
 
-hipError_t launch_stripe(hipStream_t st, const bf16_t* W, const bf16_t* X, int ldx, const int* xrow, float* part, int M,
-                         int N, int K, StripePlan sp) {
+template <bool SILU>
+hipError_t launch_stripe(hipStream_t st, const bf16_t* W, const bf16_t* X, int ldx, const int* xrow, float* part,
+                         bf16_t* act, int M, int N, int K, StripePlan sp) {
   switch (M) {
-    case 1: return launch_stripe_mm<1>(st, W, X, ldx, xrow, part, M, N, K, sp);
-    case 2: return launch_stripe_mm<2>(st, W, X, ldx, xrow, part, M, N, K, sp);
-    case 3: return launch_stripe_mm<3>(st, W, X, ldx, xrow, part, M, N, K, sp);
-    case 4: return launch_stripe_mm<4>(st, W, X, ldx, xrow, part, M, N, K, sp);
-    case 5: return launch_stripe_mm<5>(st, W, X, ldx, xrow, part, M, N, K, sp);
-    case 6: return launch_stripe_mm<6>(st, W, X, ldx, xrow, part, M, N, K, sp);
-    case 7: return launch_stripe_mm<7>(st, W, X, ldx, xrow, part, M, N, K, sp);
-    case 8: return launch_stripe_mm<8>(st, W, X, ldx, xrow, part, M, N, K, sp);
+    case 1: return launch_stripe_mm<1, SILU>(st, W, X, ldx, xrow, part, act, M, N, K, sp);
+    case 2: return launch_stripe_mm<2, SILU>(st, W, X, ldx, xrow, part, act, M, N, K, sp);
+    case 3: return launch_stripe_mm<3, SILU>(st, W, X, ldx, xrow, part, act, M, N, K, sp);
+    case 4: return launch_stripe_mm<4, SILU>(st, W, X, ldx, xrow, part, act, M, N, K, sp);
+    case 5: return launch_stripe_mm<5, SILU>(st, W, X, ldx, xrow, part, act, M, N, K, sp);
+    case 6: return launch_stripe_mm<6, SILU>(st, W, X, ldx, xrow, part, act, M, N, K, sp);
+    case 7: return launch_stripe_mm<7, SILU>(st, W, X, ldx, xrow, part, act, M, N, K, sp);
+    case 8: return launch_stripe_mm<8, SILU>(st, W, X, ldx, xrow, part, act, M, N, K, sp);
     default: return hipErrorInvalidValue;
   }
 }
@@ -591,7 +620,8 @@ hipError_t launch_gemm(hipStream_t st, int dtype, const void* W, const void* X, 
     if (ldx % 8 != 0 ||
         ((reinterpret_cast<uintptr_t>(W) | reinterpret_cast<uintptr_t>(X) | reinterpret_cast<uintptr_t>(part)) & 15))
       return hipErrorInvalidValue;
-    return launch_stripe(st, (const bf16_t*)W, (const bf16_t*)X, ldx, xrow, part, M, N, K, plan_stripe(M, N, K));
+    return launch_stripe<false>(st, (const bf16_t*)W, (const bf16_t*)X, ldx, xrow, part, nullptr, M, N, K,
+                                plan_stripe(M, N, K));
   }
   // 16-byte loads along K, 16-row tiles along N, 16-byte aligned rows
   if (K % KSTEP != 0 || N % 16 != 0 || ldx % 8 != 0) return hipErrorInvalidValue;
@@ -604,6 +634,18 @@ hipError_t launch_gemm(hipStream_t st, int dtype, const void* W, const void* X, 
   // for any number of tiles, which is how the two paths were compared
   if (M > 16) return hipErrorInvalidValue;
   return launch_stream<1>(st, w, x, ldx, xrow, part, M, N, K, sp);
+}
+
+bool gemm_silu_fused(int dtype, int M, int ffn, int K) {
+  return dtype == DT_BF16 && plan_stripe(M, ffn, K, true).S == 1;
+}
+
+hipError_t launch_gemm_silu(hipStream_t st, int dtype, const void* W, const void* X, int ldx, const int* xrow,
+                            void* act, int M, int ffn, int K) {
+  if (!W || !X || !act || ldx < K || ldx % 8 != 0 || !gemm_silu_fused(dtype, M, ffn, K)) return hipErrorInvalidValue;
+  if ((reinterpret_cast<uintptr_t>(W) | reinterpret_cast<uintptr_t>(X)) & 15) return hipErrorInvalidValue;
+  return launch_stripe<true>(st, (const bf16_t*)W, (const bf16_t*)X, ldx, xrow, nullptr, (bf16_t*)act, M, ffn, K,
+                             plan_stripe(M, ffn, K, true));
 }
 
 }  // namespace sd

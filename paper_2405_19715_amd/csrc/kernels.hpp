@@ -25,6 +25,15 @@ int gemm_splits(int dtype, int M, int N, int K);
 hipError_t launch_gemm(hipStream_t st, int dtype, const void* W, const void* X, int ldx, const int* xrow,
                        float* part, int M, int N, int K);
 
+// act[m, f] = silu(X[m, :] . W[f, :]) * (X[m, :] . W[ffn + f, :]) in bf16, W = [gate; up] = [2 ffn, K]: the
+// row-stripe kernel with the MLP's activation in its final sweep (no partial sums, no activation launch).
+// Possible where gemm_silu_fused says so: bf16, up to 8 rows, K a multiple of 2048 up to 8192 (all stripes of
+// a row range in one workgroup, and room for a gate and an up range in it); launch_gemm_silu returns
+// hipErrorInvalidValue elsewhere.  Same sums, same rounding as launch_gemm + launch_silu_mul on such a shape.
+bool gemm_silu_fused(int dtype, int M, int ffn, int K);
+hipError_t launch_gemm_silu(hipStream_t st, int dtype, const void* W, const void* X, int ldx, const int* xrow,
+                            void* act, int M, int ffn, int K);
+
 // ---------------------------------------------------------------- tiled GEMM (prompt pass, wide target passes)
 // C[s, m, n] = sum over the s-th K-slice of X[m, k] * W[n, k], bf16 in, fp32 out [S][M][N] with
 // S = gemm_tile_splits(M, N, K) (1 for large M); X rows optionally gathered through xrow.

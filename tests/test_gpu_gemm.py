@@ -105,3 +105,53 @@ def test_tile_gemm_rejects_bad_shapes():
     X = torch.zeros((4, 48), dtype=torch.bfloat16, device="cuda")
     with pytest.raises(B.SpecDecError):
         B.sd_gemm_tile(W, X)
+
+
+def _mlp_case(M, ffn, K, dtype, seed):
+    g = torch.Generator().manual_seed(seed)
+    W = (torch.randn((2 * ffn, K), generator=g) * (2.0 / K ** 0.5)).to(dtype)
+    X = torch.randn((M, K), generator=g).to(dtype)
+    return W, X
+
+
+def _mlp_check(M, ffn, K, dtype, seed, mode):
+    """The gated activation against the oracle's fp64 definition of it: one rounding to the storage type at
+    the end (2^-9 relative for bf16) plus fp32 accumulation noise relative to the largest product."""
+    from oracle.model import silu
+    from paper_2405_19715_amd import binding as B
+    W, X = _mlp_case(M, ffn, K, dtype, seed)
+    x, w = X.double().numpy(), W.double().numpy()
+    gate, up = x @ w[:ffn].T, x @ w[ffn:].T
+    want = silu(gate) * up
+    got_t = B.sd_mlp_act(W.cuda(), X.cuda(), mode=mode).cpu()
+    got = got_t.float().double().numpy()
+    assert got.shape == want.shape
+    rel = 2.0 ** -8 if dtype == torch.bfloat16 else 1e-5
+    tol = rel * np.abs(want) + 3e-5 * np.abs(gate).max() * np.abs(up).max()
+    bad = np.abs(got - want) > tol
+    assert not bad.any(), (M, ffn, K, mode, int(bad.sum()), float(np.abs(got - want).max()))
+    return got_t
+
+
+# one, two, three and four stripes per row range (K = 2048 .. 8192), every row count, ffn that leaves ragged and
+# idle row ranges; the one-launch kernel and the product + activation kernel take the same sums in the same order
+@pytest.mark.parametrize("M,ffn,K", [(1, 1376, 2048), (2, 5632, 2048), (3, 1376, 6144), (4, 688, 4096), (5, 100, 2048),
+                                     (6, 11008, 4096), (7, 3584, 8192), (8, 1001, 8192), (2, 28672, 8192)])
+def test_mlp_activation_one_launch_kernel(M, ffn, K):
+    from paper_2405_19715_amd import binding as B
+    assert B.sd_mlp_act_is_fused(torch.bfloat16, M, ffn, K)
+    fused = _mlp_check(M, ffn, K, torch.bfloat16, 31 + M, mode=1)
+    split = _mlp_check(M, ffn, K, torch.bfloat16, 31 + M, mode=0)
+    assert torch.equal(fused.view(torch.int16), split.view(torch.int16))
+
+
+@pytest.mark.parametrize("M,ffn,K,dtype", [(17, 688, 256, torch.bfloat16), (40, 1376, 1024, torch.bfloat16),
+                                           (9, 3584, 8192, torch.bfloat16), (4, 512, 16384, torch.bfloat16),
+                                           (3, 172, 256, torch.float32)])
+def test_mlp_activation_where_the_one_launch_kernel_does_not_apply(M, ffn, K, dtype):
+    from paper_2405_19715_amd import binding as B
+    assert not B.sd_mlp_act_is_fused(dtype, M, ffn, K)
+    _mlp_check(M, ffn, K, dtype, 5, mode=-1)
+    W, X = _mlp_case(M, ffn, K, dtype, 5)
+    with pytest.raises(B.SpecDecError):
+        B.sd_mlp_act(W.cuda(), X.cuda(), mode=1)
