@@ -249,6 +249,7 @@ sd_status forward(sd_ctx* c, ModelRt& rt, int M, int RS, int max_kv_len, const i
   };
   auto slices = [&](int N, int K) { return gemm_splits(dt, M, N, K); };
   const bool fuse_act = gemm_silu_fused(dt, M, m.d_ffn, d);     // gate|up GEMM writes silu(gate) * up itself
+  const int res_groups = fuse_act ? gemm_resid_groups(dt, M, d, nq) : 0;   // > 0: residual + norm ride on the o projection
   SD_HIP(launch_embed_norm(st, dt, m.tok_emb, rt.na[0], m.rms_eps, c->rows.tok, c->x, c->xn, c->ssq, M, d, m.vocab));
   for (int l = 0; l < m.n_layers; ++l) {
     const bool pr = profile && c->prof_every > 0 && (l % c->prof_every) == 0;
@@ -260,11 +261,20 @@ sd_status forward(sd_ctx* c, ModelRt& rt, int M, int RS, int max_kv_len, const i
                           M, m.n_heads, m.n_kv_heads, m.head_dim, c->cfg.max_seq));
     SD_HIP(launch_attention(st, dt, c->qbuf, kc, vc, c->rows, c->attn, c->attn_scratch, M, RS, m.n_heads,
                             m.n_kv_heads, m.head_dim, c->cfg.max_seq, max_kv_len, tile));
-    if ((s = mm(rt.wo[l], c->attn, nq, d, nq, pr ? 1 : -1)) != SD_OK) return s;
-    SD_HIP(launch_add_norm(st, dt, c->part, slices(d, nq), rt.nm[l], m.rms_eps, c->x, c->xn, c->ssq, M, d));
+    if (res_groups > 0) {
+      // the output projection adds itself to the residual rows and leaves x * gain for the MLP, whose first
+      // product applies the rows' RMSNorm factors to its sums: no launch between the two products
+      ProfSample* ps = pr ? prof_begin(c, 1, (double)d * nq * rt.esz) : nullptr;
+      SD_HIP(launch_gemm_resid(st, dt, rt.wo[l], c->attn, nq, nullptr, c->x, rt.nm[l], c->xn, c->ssq, M, d, nq));
+      if (ps) (void)hipEventRecord(ps->b, st);
+    } else {
+      if ((s = mm(rt.wo[l], c->attn, nq, d, nq, pr ? 1 : -1)) != SD_OK) return s;
+      SD_HIP(launch_add_norm(st, dt, c->part, slices(d, nq), rt.nm[l], m.rms_eps, c->x, c->xn, c->ssq, M, d));
+    }
     if (fuse_act) {
       ProfSample* ps = pr ? prof_begin(c, 2, 2.0 * m.d_ffn * d * rt.esz) : nullptr;
-      SD_HIP(launch_gemm_silu(st, dt, rt.wgu[l], c->xn, d, nullptr, c->act, M, m.d_ffn, d));
+      SD_HIP(launch_gemm_silu(st, dt, rt.wgu[l], c->xn, d, nullptr, c->act, M, m.d_ffn, d,
+                              res_groups > 0 ? c->ssq : nullptr, res_groups, d, m.rms_eps));
       if (ps) (void)hipEventRecord(ps->b, st);
     } else {
       if ((s = mm(rt.wgu[l], c->xn, d, 2 * m.d_ffn, d, pr ? 2 : -1)) != SD_OK) return s;

@@ -395,16 +395,34 @@ StripePlan plan_stripe(int M, int N, int K, bool paired = false) {
   return StripePlan{S, cs, rpg, G, ranges, rpw};
 }
 
-// SILU: W = [gate; up] with N rows each (2 N in all), one slice (cs = K / 2048), rpg even: the workgroup's local
-// ranges come in pairs, range g of gate and range g of up, and the final sweep writes act[m, n] = silu(gate) * up in
-// bf16 instead of partial sums: the MLP's activation without a launch of its own.
-template <int MM, bool SILU>
+// What the final sweep of the stripe kernel does with the sums (EPI):
+//   EPI_PART  part[slice][m][n] = sum                                   (any number of slices)
+//   EPI_SILU  W = [gate; up] with N rows each (2 N in all), one slice, rpg even: the workgroup's local ranges come
+//             in pairs, range g of gate and range g of up, and act[m, n] = silu(r_m gate) * (r_m up) in bf16: the
+//             MLP's activation without a launch of its own.  r_m = 1 unless the input rows were left unscaled by an
+//             EPI_RESID launch, whose sums of squares then give r_m = rsqrt(mean(x_m^2) + eps).
+//   EPI_RESID one slice: x[m, n] += sum (the residual stream, fp32); act[m, n] = bf16(x[m, n] * gain[n]), the next
+//             product's input WITHOUT the RMSNorm factor of its row (a per-row scalar commutes with the product, so
+//             the consumer applies it to its sums); ssq_out[m][workgroup] = sum of x[m, n]^2 over the workgroup's
+//             columns, added by the consumer in workgroup order.  Residual + RMSNorm without a launch of their own.
+enum { EPI_PART = 0, EPI_SILU = 1, EPI_RESID = 2 };
+struct StripeEpi {
+  bf16_t* act;             // SILU / RESID output [M][N]
+  float* x;                // RESID: residual rows [M][N], updated in place
+  const bf16_t* gain;      // RESID: [N]
+  float* ssq_out;          // RESID: [M][gridDim.x]
+  const float* ssq_in;     // SILU: [M][ssq_n] or null
+  int ssq_n;
+  float inv_d, eps;        // SILU: 1 / (length of the input rows whose squares ssq_in sums), RMSNorm epsilon
+};
+
+template <int MM, int EPI>
 __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_stripe(const bf16_t* __restrict__ W,
                                                                  const bf16_t* __restrict__ X, int ldx,
                                                                  const int* __restrict__ xrow,
-                                                                 float* __restrict__ part, bf16_t* __restrict__ act,
-                                                                 int M, int N, int K, int cs, int rpg, int ranges,
-                                                                 int rpw) {
+                                                                 float* __restrict__ part, StripeEpi epi, int M, int N,
+                                                                 int K, int cs, int rpg, int ranges, int rpw) {
+  constexpr bool SILU = EPI == EPI_SILU;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int lr = wave / cs, ls = wave - lr * cs;     // local row range, local stripe
   const int rg = SILU ? blockIdx.x * (rpg >> 1) + (lr >> 1) : blockIdx.x * rpg + lr;
@@ -420,6 +438,27 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_stripe(const bf16_t* _
     if (r >= rows) r -= rows;
     return base + (size_t)r * K;
   };
+
+  __shared__ float s_scale[STRIPE_MAX_M];            // SILU: r_m;  RESID: scratch of the sums of squares
+  __shared__ float s_red[GEMM_WAVES][STRIPE_MAX_M];
+  // SILU: the RMSNorm factors of the input rows come from the producer's per-workgroup sums of squares (at most 256
+  // per row).  Wavefront w takes rows w and w + (wavefronts in the workgroup): the loads go out first of all and
+  // are added after the stream, in a fixed order (four per lane, then the butterfly).
+  float sq[2][4] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
+  if constexpr (SILU) {
+    if (epi.ssq_in) {
+      const int nw = blockDim.x >> 6;
+#pragma unroll
+      for (int u = 0; u < 2; ++u) {
+        const int m = min(wave + u * nw, MM - 1);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const int idx = lane + WAVE * i;
+          sq[u][i] = idx < epi.ssq_n ? epi.ssq_in[m * epi.ssq_n + idx] : 0.f;
+        }
+      }
+    }
+  }
 
   // X first: its loads are then older than every weight load, and waiting for a weight step never waits for them
   uint4 x[MM][4];                                    // M == MM (the launcher picks the instantiation)
@@ -476,10 +515,19 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_stripe(const bf16_t* _
       if (writer && i < rows) otile[my_m * rpw + r] = v;
     }
   }
+  if constexpr (SILU) {
+    const int nw = blockDim.x >> 6;
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+      const int m = wave + u * nw;
+      const float t = wave_sum((sq[u][0] + sq[u][1]) + (sq[u][2] + sq[u][3]));
+      if (m < MM && lane == 0) s_scale[m] = epi.ssq_in ? 1.0f / sqrtf(t * epi.inv_d + epi.eps) : 1.0f;
+    }
+  }
   __syncthreads();
   // stripe tiles of one row range are added in stripe order
   const int tile = MM * rpw;
-  if constexpr (SILU) {
+  if constexpr (EPI == EPI_SILU) {
     for (int idx = threadIdx.x; idx < (rpg >> 1) * tile; idx += blockDim.x) {
       const int l = idx / tile, rem = idx - l * tile;
       const int m = rem / rpw, r = rem - m * rpw;
@@ -493,7 +541,38 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_stripe(const bf16_t* _
         gate += sg[(size_t)t * tile];
         up += su[(size_t)(t - 1) * tile];
       }
-      act[(size_t)m * N + g * rpw + r] = f2bf(gate / (1.0f + expf(-gate)) * up);
+      const float rm = s_scale[m];
+      gate *= rm;
+      up *= rm;
+      epi.act[(size_t)m * N + g * rpw + r] = f2bf(gate / (1.0f + expf(-gate)) * up);
+    }
+  } else if constexpr (EPI == EPI_RESID) {
+    float ssq[MM <= 1 ? 1 : MM <= 2 ? 2 : MM <= 4 ? 4 : 8];
+#pragma unroll
+    for (int m = 0; m < (int)(sizeof(ssq) / sizeof(float)); ++m) ssq[m] = 0.f;
+#pragma unroll
+    for (int m = 0; m < MM; ++m)
+      for (int e = threadIdx.x; e < rpg * rpw; e += blockDim.x) {
+        const int l = e / rpw, r = e - l * rpw;
+        const int g = blockIdx.x * rpg + l;
+        const int n = g * rpw + r;
+        if (g >= ranges || n >= N) continue;
+        const float* src = obuf + (size_t)l * cs * tile + m * rpw + r;
+        float sum = src[0];
+        for (int t = 1; t < cs; ++t) sum += src[(size_t)t * tile];
+        const float xv = epi.x[(size_t)m * N + n] + sum;
+        epi.x[(size_t)m * N + n] = xv;
+        epi.act[(size_t)m * N + n] = f2bf(xv * bf2f(epi.gain[n]));
+        ssq[m] += xv * xv;
+      }
+    // per-row sums of squares of this workgroup's columns: lanes, then wavefronts in order
+    const float v = reduce_lanes<sizeof(ssq) / sizeof(float)>(ssq, lane);
+    if (writer) s_red[wave][my_m] = v;
+    __syncthreads();
+    if (threadIdx.x < MM) {
+      float t = 0.f;
+      for (int w = 0; w < (int)(blockDim.x >> 6); ++w) t += s_red[w][threadIdx.x];
+      epi.ssq_out[threadIdx.x * gridDim.x + blockIdx.x] = t;
     }
   } else {
     for (int idx = threadIdx.x; idx < rpg * tile; idx += blockDim.x) {
@@ -509,28 +588,28 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_stripe(const bf16_t* _
   }
 }
 
-template <int MM, bool SILU>
+template <int MM, int EPI>
 hipError_t launch_stripe_mm(hipStream_t st, const bf16_t* W, const bf16_t* X, int ldx, const int* xrow, float* part,
-                            bf16_t* act, int M, int N, int K, StripePlan sp) {
+                            const StripeEpi& epi, int M, int N, int K, StripePlan sp) {
   const size_t lds = (size_t)sp.cs * sp.rpg * MM * sp.rpw * sizeof(float);
   if (lds > STRIPE_LDS_MAX) return hipErrorInvalidValue;
-  hipLaunchKernelGGL((gemm_bf16_stripe<MM, SILU>), dim3(sp.G, sp.S), dim3(sp.cs * sp.rpg * WAVE), lds, st, W, X, ldx,
-                     xrow, part, act, M, N, K, sp.cs, sp.rpg, sp.ranges, sp.rpw);
+  hipLaunchKernelGGL((gemm_bf16_stripe<MM, EPI>), dim3(sp.G, sp.S), dim3(sp.cs * sp.rpg * WAVE), lds, st, W, X, ldx,
+                     xrow, part, epi, M, N, K, sp.cs, sp.rpg, sp.ranges, sp.rpw);
   return hipGetLastError();
 }
 
-template <bool SILU>
+template <int EPI>
 hipError_t launch_stripe(hipStream_t st, const bf16_t* W, const bf16_t* X, int ldx, const int* xrow, float* part,
-                         bf16_t* act, int M, int N, int K, StripePlan sp) {
+                         const StripeEpi& epi, int M, int N, int K, StripePlan sp) {
   switch (M) {
-    case 1: return launch_stripe_mm<1, SILU>(st, W, X, ldx, xrow, part, act, M, N, K, sp);
-    case 2: return launch_stripe_mm<2, SILU>(st, W, X, ldx, xrow, part, act, M, N, K, sp);
-    case 3: return launch_stripe_mm<3, SILU>(st, W, X, ldx, xrow, part, act, M, N, K, sp);
-    case 4: return launch_stripe_mm<4, SILU>(st, W, X, ldx, xrow, part, act, M, N, K, sp);
-    case 5: return launch_stripe_mm<5, SILU>(st, W, X, ldx, xrow, part, act, M, N, K, sp);
-    case 6: return launch_stripe_mm<6, SILU>(st, W, X, ldx, xrow, part, act, M, N, K, sp);
-    case 7: return launch_stripe_mm<7, SILU>(st, W, X, ldx, xrow, part, act, M, N, K, sp);
-    case 8: return launch_stripe_mm<8, SILU>(st, W, X, ldx, xrow, part, act, M, N, K, sp);
+    case 1: return launch_stripe_mm<1, EPI>(st, W, X, ldx, xrow, part, epi, M, N, K, sp);
+    case 2: return launch_stripe_mm<2, EPI>(st, W, X, ldx, xrow, part, epi, M, N, K, sp);
+    case 3: return launch_stripe_mm<3, EPI>(st, W, X, ldx, xrow, part, epi, M, N, K, sp);
+    case 4: return launch_stripe_mm<4, EPI>(st, W, X, ldx, xrow, part, epi, M, N, K, sp);
+    case 5: return launch_stripe_mm<5, EPI>(st, W, X, ldx, xrow, part, epi, M, N, K, sp);
+    case 6: return launch_stripe_mm<6, EPI>(st, W, X, ldx, xrow, part, epi, M, N, K, sp);
+    case 7: return launch_stripe_mm<7, EPI>(st, W, X, ldx, xrow, part, epi, M, N, K, sp);
+    case 8: return launch_stripe_mm<8, EPI>(st, W, X, ldx, xrow, part, epi, M, N, K, sp);
     default: return hipErrorInvalidValue;
   }
 }
@@ -620,8 +699,8 @@ hipError_t launch_gemm(hipStream_t st, int dtype, const void* W, const void* X, 
     if (ldx % 8 != 0 ||
         ((reinterpret_cast<uintptr_t>(W) | reinterpret_cast<uintptr_t>(X) | reinterpret_cast<uintptr_t>(part)) & 15))
       return hipErrorInvalidValue;
-    return launch_stripe<false>(st, (const bf16_t*)W, (const bf16_t*)X, ldx, xrow, part, nullptr, M, N, K,
-                                plan_stripe(M, N, K));
+    return launch_stripe<EPI_PART>(st, (const bf16_t*)W, (const bf16_t*)X, ldx, xrow, part, StripeEpi{}, M, N, K,
+                                   plan_stripe(M, N, K));
   }
   // 16-byte loads along K, 16-row tiles along N, 16-byte aligned rows
   if (K % KSTEP != 0 || N % 16 != 0 || ldx % 8 != 0) return hipErrorInvalidValue;
@@ -641,11 +720,38 @@ bool gemm_silu_fused(int dtype, int M, int ffn, int K) {
 }
 
 hipError_t launch_gemm_silu(hipStream_t st, int dtype, const void* W, const void* X, int ldx, const int* xrow,
-                            void* act, int M, int ffn, int K) {
+                            void* act, int M, int ffn, int K, const float* ssq, int ssq_n, int d_in, float eps) {
   if (!W || !X || !act || ldx < K || ldx % 8 != 0 || !gemm_silu_fused(dtype, M, ffn, K)) return hipErrorInvalidValue;
   if ((reinterpret_cast<uintptr_t>(W) | reinterpret_cast<uintptr_t>(X)) & 15) return hipErrorInvalidValue;
-  return launch_stripe<true>(st, (const bf16_t*)W, (const bf16_t*)X, ldx, xrow, nullptr, (bf16_t*)act, M, ffn, K,
-                             plan_stripe(M, ffn, K, true));
+  if (ssq && (ssq_n < 1 || ssq_n > 256 || d_in < 1)) return hipErrorInvalidValue;
+  StripeEpi epi{};
+  epi.act = (bf16_t*)act;
+  epi.ssq_in = ssq;
+  epi.ssq_n = ssq_n;
+  epi.inv_d = ssq ? 1.0f / (float)d_in : 0.f;
+  epi.eps = eps;
+  return launch_stripe<EPI_SILU>(st, (const bf16_t*)W, (const bf16_t*)X, ldx, xrow, nullptr, epi, M, ffn, K,
+                                 plan_stripe(M, ffn, K, true));
+}
+
+int gemm_resid_groups(int dtype, int M, int N, int K) {
+  if (dtype != DT_BF16) return 0;
+  const StripePlan sp = plan_stripe(M, N, K);
+  return sp.S == 1 ? sp.G : 0;
+}
+
+hipError_t launch_gemm_resid(hipStream_t st, int dtype, const void* W, const void* X, int ldx, const int* xrow,
+                             float* x, const void* gain, void* xg, float* ssq, int M, int N, int K) {
+  if (!W || !X || !x || !gain || !xg || !ssq || ldx < K || ldx % 8 != 0 || gemm_resid_groups(dtype, M, N, K) < 1)
+    return hipErrorInvalidValue;
+  if ((reinterpret_cast<uintptr_t>(W) | reinterpret_cast<uintptr_t>(X)) & 15) return hipErrorInvalidValue;
+  StripeEpi epi{};
+  epi.act = (bf16_t*)xg;
+  epi.x = x;
+  epi.gain = (const bf16_t*)gain;
+  epi.ssq_out = ssq;
+  return launch_stripe<EPI_RESID>(st, (const bf16_t*)W, (const bf16_t*)X, ldx, xrow, nullptr, epi, M, N, K,
+                                  plan_stripe(M, N, K));
 }
 
 }  // namespace sd

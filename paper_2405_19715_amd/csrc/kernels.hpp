@@ -30,9 +30,22 @@ hipError_t launch_gemm(hipStream_t st, int dtype, const void* W, const void* X, 
 // Possible where gemm_silu_fused says so: bf16, up to 8 rows, K a multiple of 2048 up to 8192 (all stripes of
 // a row range in one workgroup, and room for a gate and an up range in it); launch_gemm_silu returns
 // hipErrorInvalidValue elsewhere.  Same sums, same rounding as launch_gemm + launch_silu_mul on such a shape.
+// With `ssq` (device, [M][ssq_n]: per-workgroup sums of squares of the UNSCALED input rows, as launch_gemm_resid
+// leaves them) both sums are multiplied by r_m = rsqrt(sum_i ssq[m][i] / d_in + eps) first: the RMSNorm factor the
+// producer of X left out.
 bool gemm_silu_fused(int dtype, int M, int ffn, int K);
 hipError_t launch_gemm_silu(hipStream_t st, int dtype, const void* W, const void* X, int ldx, const int* xrow,
-                            void* act, int M, int ffn, int K);
+                            void* act, int M, int ffn, int K, const float* ssq = nullptr, int ssq_n = 0, int d_in = 0,
+                            float eps = 0.f);
+
+// x[m, n] += X[m, :] . W[n, :] (the residual stream, fp32); xg[m, n] = bf16(x[m, n] * gain[n]); ssq[m][g] = sum of
+// x[m, n]^2 over the columns of workgroup g, g < gemm_resid_groups(...): the residual add and the RMSNorm that
+// follows a projection, minus the per-row factor rsqrt(mean(x^2) + eps), which the consumer of xg applies to
+// its own sums (launch_gemm_silu with `ssq`).  Row-stripe kernel with one slice only: gemm_resid_groups returns
+// 0 where that does not apply, and launch_gemm_resid hipErrorInvalidValue.
+int gemm_resid_groups(int dtype, int M, int N, int K);
+hipError_t launch_gemm_resid(hipStream_t st, int dtype, const void* W, const void* X, int ldx, const int* xrow,
+                             float* x, const void* gain, void* xg, float* ssq, int M, int N, int K);
 
 // ---------------------------------------------------------------- tiled GEMM (prompt pass, wide target passes)
 // C[s, m, n] = sum over the s-th K-slice of X[m, k] * W[n, k], bf16 in, fp32 out [S][M][N] with
