@@ -250,11 +250,20 @@ sd_status forward(sd_ctx* c, ModelRt& rt, int M, int RS, int max_kv_len, const i
   auto slices = [&](int N, int K) { return gemm_splits(dt, M, N, K); };
   const bool fuse_act = gemm_silu_fused(dt, M, m.d_ffn, d);     // gate|up GEMM writes silu(gate) * up itself
   const int res_groups = fuse_act ? gemm_resid_groups(dt, M, d, nq) : 0;   // > 0: residual + norm ride on the o projection
+  const int down_groups = gemm_scaled_ok(dt, M, nq + 2 * nkv, d) ? gemm_resid_groups(dt, M, d, m.d_ffn) : 0;   // and on down
+  int in_groups = 0;            // > 0: xn = x * gain without the rows' norm factors; their sums of squares sit in c->ssq
   SD_HIP(launch_embed_norm(st, dt, m.tok_emb, rt.na[0], m.rms_eps, c->rows.tok, c->x, c->xn, c->ssq, M, d, m.vocab));
   for (int l = 0; l < m.n_layers; ++l) {
     const bool pr = profile && c->prof_every > 0 && (l % c->prof_every) == 0;
     sd_status s;
-    if ((s = mm(rt.wqkv[l], c->xn, d, nq + 2 * nkv, d, pr ? 0 : -1)) != SD_OK) return s;
+    if (in_groups > 0) {          // the rows of xn still lack their RMSNorm factor (previous layer's down projection)
+      ProfSample* ps = pr ? prof_begin(c, 0, (double)(nq + 2 * nkv) * d * rt.esz) : nullptr;
+      SD_HIP(launch_gemm_scaled(st, dt, rt.wqkv[l], c->xn, d, nullptr, c->part, M, nq + 2 * nkv, d, c->ssq, in_groups, d,
+                                m.rms_eps));
+      if (ps) (void)hipEventRecord(ps->b, st);
+    } else if ((s = mm(rt.wqkv[l], c->xn, d, nq + 2 * nkv, d, pr ? 0 : -1)) != SD_OK) {
+      return s;
+    }
     void* kc = rt.kcache + (size_t)l * rt.layer_bytes;
     void* vc = rt.vcache + (size_t)l * rt.layer_bytes;
     SD_HIP(launch_rope_kv(st, dt, c->part, slices(nq + 2 * nkv, d), c->rows, rt.cos_sin, c->qbuf, kc, vc,
@@ -280,9 +289,20 @@ sd_status forward(sd_ctx* c, ModelRt& rt, int M, int RS, int max_kv_len, const i
       if ((s = mm(rt.wgu[l], c->xn, d, 2 * m.d_ffn, d, pr ? 2 : -1)) != SD_OK) return s;
       SD_HIP(launch_silu_mul(st, dt, c->part, slices(2 * m.d_ffn, d), c->act, M, m.d_ffn));
     }
-    if ((s = mm(rt.wdown[l], c->act, m.d_ffn, d, m.d_ffn, pr ? 3 : -1)) != SD_OK) return s;
     const void* g_next = (l + 1 < m.n_layers) ? rt.na[l + 1] : m.final_norm;
-    SD_HIP(launch_add_norm(st, dt, c->part, slices(d, m.d_ffn), g_next, m.rms_eps, c->x, c->xn, c->ssq, M, d));
+    if (down_groups > 0 && l + 1 < m.n_layers) {
+      // same for the MLP's output: the down projection adds itself to the residual rows, the next layer's q|k|v
+      // product applies the norm factors (the last layer keeps the separate kernel: its rows feed the LM head)
+      ProfSample* ps = pr ? prof_begin(c, 3, (double)d * m.d_ffn * rt.esz) : nullptr;
+      SD_HIP(launch_gemm_resid(st, dt, rt.wdown[l], c->act, m.d_ffn, nullptr, c->x, g_next, c->xn, c->ssq, M, d,
+                               m.d_ffn));
+      if (ps) (void)hipEventRecord(ps->b, st);
+      in_groups = down_groups;
+    } else {
+      if ((s = mm(rt.wdown[l], c->act, m.d_ffn, d, m.d_ffn, pr ? 3 : -1)) != SD_OK) return s;
+      SD_HIP(launch_add_norm(st, dt, c->part, slices(d, m.d_ffn), g_next, m.rms_eps, c->x, c->xn, c->ssq, M, d));
+      in_groups = 0;
+    }
   }
   if (logits_out) {
     sd_status s;

@@ -368,39 +368,40 @@ __device__ __forceinline__ float reduce_lanes(float* acc, int lane) {
   return v;
 }
 
-// cs stripes of the same rows sit in one workgroup and are added there, so part[] gets S = (K / 2048) / cs slices:
-// one for K up to 16384, two for the 70B down projection (14 stripes, 7 per workgroup).
-struct StripePlan { int S, cs, rpg, G, ranges, rpw; };   // rpg row ranges per workgroup (cs * rpg wavefronts); G workgroups per slice
+// The stripes of a row range all sit in one workgroup and are added there: cs wavefronts, each taking npass stripes
+// one after the other (the 70B down projection: 14 stripes = 7 wavefronts x 2), so part[] always gets ONE slice.
+struct StripePlan { int S, cs, rpg, G, ranges, rpw, npass; };   // rpg row ranges per workgroup (cs * rpg wavefronts); G workgroups
 
 // paired: N is the row count of each half of a [gate; up] matrix, and a workgroup takes its ranges in pairs
 // (needs one slice and an even number of ranges per workgroup)
 StripePlan plan_stripe(int M, int N, int K, bool paired = false) {
-  StripePlan sp{0, 0, 0, 0, 0, 0};
+  StripePlan sp{0, 0, 0, 0, 0, 0, 0};
   if (M < 1 || M > STRIPE_MAX_M || N < 1 || K < RSTEP || K % RSTEP != 0) return sp;
   const int stripes = K / RSTEP;
   int cs = 1;
   for (int d = 2; d <= GEMM_WAVES; ++d)
     if (stripes % d == 0) cs = d;
-  const int S = stripes / cs;
-  if (S > 4) return sp;                              // more slices than the consumers should have to walk
+  const int npass = stripes / cs;                    // stripes a wavefront takes one after the other
+  if (npass > 8) return sp;
   const int rpg = GEMM_WAVES / cs;
-  if (paired && (S != 1 || (rpg & 1))) return sp;
+  if (paired && (rpg & 1)) return sp;
   const int units = paired ? rpg / 2 : rpg;          // ranges of N a workgroup covers
-  int ranges = 256 * units / S;                      // one workgroup per CU
+  int ranges = 256 * units;                          // one workgroup per CU
   if (ranges > N) ranges = N;
   const int rpw = (N + ranges - 1) / ranges;
   ranges = (N + rpw - 1) / rpw;
   const int G = (ranges + units - 1) / units;
   if ((size_t)cs * rpg * M * rpw * sizeof(float) > STRIPE_LDS_MAX) return sp;         // the wavefronts' output tiles
-  return StripePlan{S, cs, rpg, G, ranges, rpw};
+  return StripePlan{1, cs, rpg, G, ranges, rpw, npass};
 }
 
 // What the final sweep of the stripe kernel does with the sums (EPI):
-//   EPI_PART  part[slice][m][n] = sum                                   (any number of slices)
+//   EPI_PART  part[m][n] = r_m sum
 //   EPI_SILU  W = [gate; up] with N rows each (2 N in all), one slice, rpg even: the workgroup's local ranges come
 //             in pairs, range g of gate and range g of up, and act[m, n] = silu(r_m gate) * (r_m up) in bf16: the
-//             MLP's activation without a launch of its own.  r_m = 1 unless the input rows were left unscaled by an
-//             EPI_RESID launch, whose sums of squares then give r_m = rsqrt(mean(x_m^2) + eps).
+//             MLP's activation without a launch of its own.
+//             (both: r_m = 1 unless the input rows were left unscaled by an EPI_RESID launch, whose sums of squares
+//             then give r_m = rsqrt(mean(x_m^2) + eps))
 //   EPI_RESID one slice: x[m, n] += sum (the residual stream, fp32); act[m, n] = bf16(x[m, n] * gain[n]), the next
 //             product's input WITHOUT the RMSNorm factor of its row (a per-row scalar commutes with the product, so
 //             the consumer applies it to its sums); ssq_out[m][workgroup] = sum of x[m, n]^2 over the workgroup's
@@ -411,9 +412,9 @@ struct StripeEpi {
   float* x;                // RESID: residual rows [M][N], updated in place
   const bf16_t* gain;      // RESID: [N]
   float* ssq_out;          // RESID: [M][gridDim.x]
-  const float* ssq_in;     // SILU: [M][ssq_n] or null
+  const float* ssq_in;     // PART / SILU: [M][ssq_n] or null
   int ssq_n;
-  float inv_d, eps;        // SILU: 1 / (length of the input rows whose squares ssq_in sums), RMSNorm epsilon
+  float inv_d, eps;        // 1 / (length of the input rows whose squares ssq_in sums), RMSNorm epsilon
 };
 
 template <int MM, int EPI>
@@ -421,23 +422,18 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_stripe(const bf16_t* _
                                                                  const bf16_t* __restrict__ X, int ldx,
                                                                  const int* __restrict__ xrow,
                                                                  float* __restrict__ part, StripeEpi epi, int M, int N,
-                                                                 int K, int cs, int rpg, int ranges, int rpw) {
+                                                                 int K, int cs, int rpg, int ranges, int rpw,
+                                                                 int npass) {
   constexpr bool SILU = EPI == EPI_SILU;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int lr = wave / cs, ls = wave - lr * cs;     // local row range, local stripe
   const int rg = SILU ? blockIdx.x * (rpg >> 1) + (lr >> 1) : blockIdx.x * rpg + lr;
-  // stripe of K.  SILU: gate and up are a multiple of 2^26 bytes apart for the 70B shape (the same DRAM channel and
-  // bank at equal k), and a pair's wavefronts run side by side: the up wavefronts take their stripes one further
-  const int c = blockIdx.y * cs + (SILU && (lr & 1) ? (ls + 1 == cs ? 0 : ls + 1) : ls);
+  // first stripe of K.  SILU: gate and up are a multiple of 2^26 bytes apart for the 70B shape (the same DRAM channel
+  // and bank at equal k), and a pair's wavefronts run side by side: the up wavefronts take their stripes one further
+  const int c0 = SILU && (lr & 1) ? (ls + 1 == cs ? 0 : ls + 1) : ls;
   const int r0 = rg * rpw + (SILU && (lr & 1) ? N : 0);          // SILU: odd local ranges are the rows of `up`
   const int rows = rg < ranges ? min(rpw, N - rg * rpw) : 0;     // a wavefront without rows still meets the barrier
-  const int rot = rows > 0 ? ((rg * (K / RSTEP) + c) * 5) % rows : 0;
-  const bf16_t* base = W + (size_t)(rows > 0 ? r0 : 0) * K + c * RSTEP + lane * 8;
-  auto at = [&](int t) -> const bf16_t* {
-    int r = t + rot;
-    if (r >= rows) r -= rows;
-    return base + (size_t)r * K;
-  };
+  const bf16_t* const idle = W + lane * 8;
 
   __shared__ float s_scale[STRIPE_MAX_M];            // SILU: r_m;  RESID: scratch of the sums of squares
   __shared__ float s_red[GEMM_WAVES][STRIPE_MAX_M];
@@ -445,7 +441,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_stripe(const bf16_t* _
   // per row).  Wavefront w takes rows w and w + (wavefronts in the workgroup): the loads go out first of all and
   // are added after the stream, in a fixed order (four per lane, then the butterfly).
   float sq[2][4] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
-  if constexpr (SILU) {
+  if constexpr (EPI != EPI_RESID) {
     if (epi.ssq_in) {
       const int nw = blockDim.x >> 6;
 #pragma unroll
@@ -460,26 +456,6 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_stripe(const bf16_t* _
     }
   }
 
-  // X first: its loads are then older than every weight load, and waiting for a weight step never waits for them
-  uint4 x[MM][4];                                    // M == MM (the launcher picks the instantiation)
-#pragma unroll
-  for (int m = 0; m < MM; ++m) {
-    const bf16_t* xp = X + (size_t)(xrow ? xrow[m] : m) * ldx + c * RSTEP + lane * 8;
-#pragma unroll
-    for (int j = 0; j < 4; ++j) x[m][j] = ldg128(xp + j * PIECE);
-  }
-
-  // Every step issues its four loads without a branch around them, so that the compiler can count the loads in
-  // flight and wait for the oldest step only; past the wave's last row the address is the start of W (a
-  // line every wave shares: served by L2) and the data is not used.
-  uint4 a[PREFETCH][4];
-#pragma unroll
-  for (int p = 0; p < PREFETCH; ++p) {
-    const bf16_t* q = p < rows ? at(p) : W + lane * 8;
-#pragma unroll
-    for (int j = 0; j < 4; ++j) a[p][j] = ldg128_stream(q + j * PIECE);
-  }
-
   // after the butterfly lane l holds the sum of activation row l / (64 / P2); its lanes with the low bits
   // clear put it into the wave's LDS tile [MM][rpw]; the tiles of the cs stripes are added and go to part[] in
   // one coalesced sweep at the end (no global store inside the loop: stores count like loads, and a store
@@ -491,31 +467,66 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_stripe(const bf16_t* _
   const bool writer = (lane % LPM) == 0 && my_m < MM;
   float* otile = obuf + (size_t)wave * MM * rpw;
 
-  for (int i0 = 0; i0 < rows; i0 += PREFETCH) {
+  for (int ps = 0; ps < npass; ++ps) {
+    const int c = ps * cs + c0;                        // this pass's stripe of K
+    const int rot = rows > 0 ? ((rg * npass * cs + c) * 5) % rows : 0;
+    const bf16_t* base = W + (size_t)(rows > 0 ? r0 : 0) * K + c * RSTEP + lane * 8;
+    auto at = [&](int t) -> const bf16_t* {
+      int r = t + rot;
+      if (r >= rows) r -= rows;
+      return base + (size_t)r * K;
+    };
+
+    // X first: its loads are then older than every weight load, and waiting for a weight step never waits for them
+    uint4 x[MM][4];                                    // M == MM (the launcher picks the instantiation)
+#pragma unroll
+    for (int m = 0; m < MM; ++m) {
+      const bf16_t* xp = X + (size_t)(xrow ? xrow[m] : m) * ldx + c * RSTEP + lane * 8;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) x[m][j] = ldg128(xp + j * PIECE);
+    }
+
+    // Every step issues its four loads without a branch around them, so that the compiler can count the loads in
+    // flight and wait for the oldest step only; past the wave's last row the address is the start of W (a
+    // line every wave shares: served by L2) and the data is not used.
+    uint4 a[PREFETCH][4];
 #pragma unroll
     for (int p = 0; p < PREFETCH; ++p) {
-      const int i = i0 + p;
-      __builtin_amdgcn_sched_barrier(0);             // steps stay in order: the next step's data is still in flight
-      float acc[P2];
+      const bf16_t* q = p < rows ? at(p) : idle;
 #pragma unroll
-      for (int m = 0; m < P2; ++m) acc[m] = 0.f;
-      // the sums of one activation row form a dependent chain: the chains of the MM rows interleave
+      for (int j = 0; j < 4; ++j) a[p][j] = ldg128_stream(q + j * PIECE);
+    }
+
+    for (int i0 = 0; i0 < rows; i0 += PREFETCH) {
 #pragma unroll
-      for (int j = 0; j < 4; ++j)
+      for (int p = 0; p < PREFETCH; ++p) {
+        const int i = i0 + p;
+        __builtin_amdgcn_sched_barrier(0);           // steps stay in order: the next step's data is still in flight
+        float acc[P2];
 #pragma unroll
-        for (int m = 0; m < MM; ++m) acc[m] = dot8(a[p][j], x[m][j], acc[m]);
-      {
-        const bf16_t* q = i + PREFETCH < rows ? at(i + PREFETCH) : W + lane * 8;
+        for (int m = 0; m < P2; ++m) acc[m] = 0.f;
+        // the sums of one activation row form a dependent chain: the chains of the MM rows interleave
 #pragma unroll
-        for (int j = 0; j < 4; ++j) a[p][j] = ldg128_stream(q + j * PIECE);
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+          for (int m = 0; m < MM; ++m) acc[m] = dot8(a[p][j], x[m][j], acc[m]);
+        {
+          const bool more = i + PREFETCH < rows;
+          const bf16_t* q = more ? at(i + PREFETCH) : idle;
+#pragma unroll
+          for (int j = 0; j < 4; ++j) a[p][j] = ldg128_stream(q + j * PIECE);
+        }
+        const float v = reduce_lanes<P2>(acc, lane);
+        int r = i + rot;
+        if (r >= rows) r -= rows;
+        if (writer && i < rows) {
+          if (ps == 0) otile[my_m * rpw + r] = v;
+          else otile[my_m * rpw + r] += v;             // later stripes of the same wavefront, in stripe order
+        }
       }
-      const float v = reduce_lanes<P2>(acc, lane);
-      int r = i + rot;
-      if (r >= rows) r -= rows;
-      if (writer && i < rows) otile[my_m * rpw + r] = v;
     }
   }
-  if constexpr (SILU) {
+  if constexpr (EPI != EPI_RESID) {
     const int nw = blockDim.x >> 6;
 #pragma unroll
     for (int u = 0; u < 2; ++u) {
@@ -547,12 +558,11 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_stripe(const bf16_t* _
       epi.act[(size_t)m * N + g * rpw + r] = f2bf(gate / (1.0f + expf(-gate)) * up);
     }
   } else if constexpr (EPI == EPI_RESID) {
-    float ssq[MM <= 1 ? 1 : MM <= 2 ? 2 : MM <= 4 ? 4 : 8];
-#pragma unroll
-    for (int m = 0; m < (int)(sizeof(ssq) / sizeof(float)); ++m) ssq[m] = 0.f;
-#pragma unroll
-    for (int m = 0; m < MM; ++m)
-      for (int e = threadIdx.x; e < rpg * rpw; e += blockDim.x) {
+    // wavefront w takes activation rows w, w + (wavefronts), ...: a row's sum of squares stays inside one wavefront
+    const int nw = blockDim.x >> 6;
+    for (int m = wave; m < MM; m += nw) {
+      float ssq = 0.f;
+      for (int e = lane; e < rpg * rpw; e += WAVE) {
         const int l = e / rpw, r = e - l * rpw;
         const int g = blockIdx.x * rpg + l;
         const int n = g * rpw + r;
@@ -563,16 +573,10 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_stripe(const bf16_t* _
         const float xv = epi.x[(size_t)m * N + n] + sum;
         epi.x[(size_t)m * N + n] = xv;
         epi.act[(size_t)m * N + n] = f2bf(xv * bf2f(epi.gain[n]));
-        ssq[m] += xv * xv;
+        ssq += xv * xv;
       }
-    // per-row sums of squares of this workgroup's columns: lanes, then wavefronts in order
-    const float v = reduce_lanes<sizeof(ssq) / sizeof(float)>(ssq, lane);
-    if (writer) s_red[wave][my_m] = v;
-    __syncthreads();
-    if (threadIdx.x < MM) {
-      float t = 0.f;
-      for (int w = 0; w < (int)(blockDim.x >> 6); ++w) t += s_red[w][threadIdx.x];
-      epi.ssq_out[threadIdx.x * gridDim.x + blockIdx.x] = t;
+      ssq = wave_sum(ssq);
+      if (lane == 0) epi.ssq_out[m * gridDim.x + blockIdx.x] = ssq;
     }
   } else {
     for (int idx = threadIdx.x; idx < rpg * tile; idx += blockDim.x) {
@@ -583,7 +587,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_stripe(const bf16_t* _
       const float* src = obuf + (size_t)l * cs * tile + rem;
       float sum = src[0];
       for (int t = 1; t < cs; ++t) sum += src[(size_t)t * tile];
-      part[((size_t)blockIdx.y * M + m) * N + g * rpw + r] = sum;
+      part[(size_t)m * N + g * rpw + r] = sum * s_scale[m];      // s_scale = 1 unless the input rows lack their norm factor
     }
   }
 }
@@ -593,8 +597,9 @@ hipError_t launch_stripe_mm(hipStream_t st, const bf16_t* W, const bf16_t* X, in
                             const StripeEpi& epi, int M, int N, int K, StripePlan sp) {
   const size_t lds = (size_t)sp.cs * sp.rpg * MM * sp.rpw * sizeof(float);
   if (lds > STRIPE_LDS_MAX) return hipErrorInvalidValue;
-  hipLaunchKernelGGL((gemm_bf16_stripe<MM, EPI>), dim3(sp.G, sp.S), dim3(sp.cs * sp.rpg * WAVE), lds, st, W, X, ldx,
-                     xrow, part, epi, M, N, K, sp.cs, sp.rpg, sp.ranges, sp.rpw);
+  const dim3 grid(sp.G), block(sp.cs * sp.rpg * WAVE);
+  hipLaunchKernelGGL((gemm_bf16_stripe<MM, EPI>), grid, block, lds, st, W, X, ldx, xrow, part, epi, M, N, K, sp.cs,
+                     sp.rpg, sp.ranges, sp.rpw, sp.npass);
   return hipGetLastError();
 }
 
@@ -614,9 +619,10 @@ hipError_t launch_stripe(hipStream_t st, const bf16_t* W, const bf16_t* X, int l
   }
 }
 
-// Up to 8 activation rows and K a multiple of 2048 up to 16384: measured equal or faster than the MFMA kernel on
-// every such matrix of the 70B / 7B shapes, alone and inside the forward pass (70B target pass, 1 .. 8 rows:
-// 2 - 6 % shorter).
+// Up to 8 activation rows and K a multiple of 2048 (up to 8 stripes per wavefront): measured equal or faster than
+// the MFMA kernel on every such matrix of the 70B / 7B shapes, alone and inside the forward pass (70B target pass,
+// 1 .. 8 rows: 2 - 6 % shorter).  A short last stripe (K % 2048 != 0, the 7B down projection) was built too, its
+// lanes beyond K reading the idle line against zeros: 22.4 us against the MFMA kernel's 20, so such K stay there.
 bool use_stripe(int M, int N, int K) { return plan_stripe(M, N, K).S > 0; }
 
 // ----------------------------------------------------------------------------- fp32 path
@@ -732,6 +738,24 @@ hipError_t launch_gemm_silu(hipStream_t st, int dtype, const void* W, const void
   epi.eps = eps;
   return launch_stripe<EPI_SILU>(st, (const bf16_t*)W, (const bf16_t*)X, ldx, xrow, nullptr, epi, M, ffn, K,
                                  plan_stripe(M, ffn, K, true));
+}
+
+bool gemm_scaled_ok(int dtype, int M, int N, int K) { return dtype == DT_BF16 && use_stripe(M, N, K); }
+
+hipError_t launch_gemm_scaled(hipStream_t st, int dtype, const void* W, const void* X, int ldx, const int* xrow,
+                              float* part, int M, int N, int K, const float* ssq, int ssq_n, int d_in, float eps) {
+  if (!W || !X || !part || !ssq || ldx < K || ldx % 8 != 0 || !gemm_scaled_ok(dtype, M, N, K) || ssq_n < 1 ||
+      ssq_n > 256 || d_in < 1)
+    return hipErrorInvalidValue;
+  if ((reinterpret_cast<uintptr_t>(W) | reinterpret_cast<uintptr_t>(X) | reinterpret_cast<uintptr_t>(part)) & 15)
+    return hipErrorInvalidValue;
+  StripeEpi epi{};
+  epi.ssq_in = ssq;
+  epi.ssq_n = ssq_n;
+  epi.inv_d = 1.0f / (float)d_in;
+  epi.eps = eps;
+  return launch_stripe<EPI_PART>(st, (const bf16_t*)W, (const bf16_t*)X, ldx, xrow, part, epi, M, N, K,
+                                 plan_stripe(M, N, K));
 }
 
 int gemm_resid_groups(int dtype, int M, int N, int K) {

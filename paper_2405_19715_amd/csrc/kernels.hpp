@@ -43,6 +43,11 @@ hipError_t launch_gemm_silu(hipStream_t st, int dtype, const void* W, const void
 // follows a projection, minus the per-row factor rsqrt(mean(x^2) + eps), which the consumer of xg applies to
 // its own sums (launch_gemm_silu with `ssq`).  Row-stripe kernel with one slice only: gemm_resid_groups returns
 // 0 where that does not apply, and launch_gemm_resid hipErrorInvalidValue.
+// launch_gemm with one slice whose sums are multiplied by the rows' RMSNorm factors from `ssq` (see
+// launch_gemm_silu): for the product that follows a launch_gemm_resid.  Row-stripe shapes only (gemm_scaled_ok).
+bool gemm_scaled_ok(int dtype, int M, int N, int K);
+hipError_t launch_gemm_scaled(hipStream_t st, int dtype, const void* W, const void* X, int ldx, const int* xrow,
+                              float* part, int M, int N, int K, const float* ssq, int ssq_n, int d_in, float eps);
 int gemm_resid_groups(int dtype, int M, int N, int K);
 hipError_t launch_gemm_resid(hipStream_t st, int dtype, const void* W, const void* X, int ldx, const int* xrow,
                              float* x, const void* gain, void* xg, float* ssq, int M, int N, int K);

@@ -42,8 +42,8 @@ def test_bf16_row_stripes(M):
     _check(M, 2560, 8192, torch.bfloat16, 60 + M, 3e-5)                 # four stripes (the 70B shape's K)
 
 
-# 16384: 8 stripes in one workgroup; 28672 (the 70B down projection): 14 stripes, 7 per workgroup (448 threads), two
-# partial-sum slices; 18432: 9 stripes, 3 per workgroup, three slices; tiny N: row ranges of one row, idle wavefronts
+# 16384: 8 stripes in one workgroup; 28672 (the 70B down projection): 14 stripes, 7 wavefronts (448 threads) taking
+# two each; 18432: 9 stripes, 3 wavefronts x 3; tiny N: row ranges of one row, idle wavefronts
 @pytest.mark.parametrize("shape", [(8, 640, 16384), (3, 5, 2048), (1, 1, 2048), (7, 32000, 2048), (2, 57344, 8192),
                                    (5, 1024 + 8, 28672), (8, 8192, 28672), (4, 2048, 2048 * 9), (6, 300, 2048 * 5)])
 def test_bf16_row_stripes_extremes(shape):
@@ -52,14 +52,16 @@ def test_bf16_row_stripes_extremes(shape):
 
 def test_bf16_rows_beyond_the_stripe_kernel_take_the_matrix_cores():
     from paper_2405_19715_amd import binding as B
-    # the stripes of a row range are added inside the workgroup: one slice up to K = 16384, two for K = 28672
+    # the stripes of a row range are added inside the workgroup (a wavefront takes several in turn when there are
+    # more than 8, or a number 8 wavefronts do not divide): always one slice
     assert B.lib.sd_gemm_workspace_bytes(B.SD_BF16, 8, 8192, 8192) == 8 * 8192 * 4
     assert B.lib.sd_gemm_workspace_bytes(B.SD_BF16, 2, 4096, 4096) == 2 * 4096 * 4
-    assert B.lib.sd_gemm_workspace_bytes(B.SD_BF16, 8, 8192, 28672) == 2 * 8 * 8192 * 4
-    # 9 rows, K not a multiple of 2048, or a stripe count that leaves more than 4 slices (11 stripes, prime): MFMA kernel
+    assert B.lib.sd_gemm_workspace_bytes(B.SD_BF16, 8, 8192, 28672) == 8 * 8192 * 4
+    _check(4, 4096, 2048 * 11, torch.bfloat16, 3, 3e-5)          # 11 stripes: one wavefront per row range takes them all
+    # 9 rows, or K not a multiple of 2048: MFMA kernel
     _check(9, 2560, 8192, torch.bfloat16, 3, 3e-5)
-    _check(4, 4096, 2048 * 11, torch.bfloat16, 3, 3e-5)
     _check(4, 4096, 2048 + 128, torch.bfloat16, 3, 3e-5)
+    assert B.lib.sd_gemm_workspace_bytes(B.SD_BF16, 4, 4096, 2048 + 128) > 4 * 4096 * 4
 
 
 @pytest.mark.parametrize("shape", [(1, 256, 256), (9, 1024, 256), (17, 688 * 2, 256), (32, 256, 688), (3, 7, 5)])
