@@ -69,6 +69,19 @@ def test_bf16_matches_oracle(shape):
     _forward_case(shape, torch.bfloat16, 150, [32, 32, 32, 17, 17, 1, 2, 17], std=0.04)
 
 
+# Widths that are multiples of 2048 send rows of up to 8 through the row-stripe GEMM, whose final sweep does the
+# SiLU * up, both residual adds and the RMSNorm preparation (the consumers apply the rows' norm factors): chunks of
+# every row count 1 .. 8 exercise each instantiation, 9 and 17 the MFMA / tiled kernels with the separate small
+# kernels, and the cache carries over between the two kinds of pass.
+@pytest.mark.parametrize("shape", [
+    synth.ModelShape(3, 2048, 16, 2, 128, 4096, 1024),       # q|k|v, o, gate|up, down all stripe-shaped (K = 2048 / 4096)
+    synth.ModelShape(2, 2048, 32, 32, 64, 5632, 1024),       # down K = 5632 stays on the MFMA kernel (1.1B-like MLP)
+    synth.ModelShape(2, 4096, 32, 4, 128, 2048 * 3, 512),    # 2 and 3 stripes per row
+])
+def test_bf16_fused_epilogues_match_oracle(shape):
+    _forward_case(shape, torch.bfloat16, 71, [9, 1, 2, 3, 4, 5, 6, 7, 8, 17, 1, 8], std=0.02)
+
+
 def test_bf16_long_context_many_key_splits():
     from paper_2405_19715_amd import binding as B
     shape = synth.ModelShape(1, 256, 4, 2, 64, 256, 512)

@@ -256,12 +256,20 @@ def test_cache_capacity_and_bad_arguments():
         ctx.close()
 
 
-def _bf16_pair():
-    ts = synth.ModelShape(2, 512, 8, 1, 64, 640, 2048)
-    ds = synth.ModelShape(1, 256, 2, 2, 128, 384, 2048)
-    t = synth.make_model(ts, 20, dtype=torch.bfloat16, std=0.04)
-    d = synth.make_model(ds, 21, dtype=torch.bfloat16, std=0.04)
-    h = synth.make_head([256, 256, 256, 256, 1], 22, dtype=torch.bfloat16, residual=True, std=0.04)
+def _bf16_pair(wide=False):
+    if wide:
+        # widths of 2048 / 4096: up to 8 rows go through the row-stripe GEMM and its fused epilogues (the models'
+        # matrices, the acceptance head's layers with their row gather, the LM head)
+        ts = synth.ModelShape(2, 2048, 16, 2, 128, 4096, 2048)
+        ds = synth.ModelShape(1, 2048, 16, 16, 128, 2048, 2048)
+        dims, std = [2048, 2048, 2048, 1], 0.02
+    else:
+        ts = synth.ModelShape(2, 512, 8, 1, 64, 640, 2048)
+        ds = synth.ModelShape(1, 256, 2, 2, 128, 384, 2048)
+        dims, std = [256, 256, 256, 256, 1], 0.04
+    t = synth.make_model(ts, 20, dtype=torch.bfloat16, std=std)
+    d = synth.make_model(ds, 21, dtype=torch.bfloat16, std=std)
+    h = synth.make_head(dims, 22, dtype=torch.bfloat16, residual=True, std=std)
     return t, d, h
 
 
@@ -408,7 +416,7 @@ def test_batch_of_sequences_matches_single_sequence_runs():
         ctx.close()
 
 
-def _ragged_batch_replay(Bn, k_max, hs, seed, max_exempt, check_rows=0):
+def _ragged_batch_replay(Bn, k_max, hs, seed, max_exempt, check_rows=0, wide=False):
     """Bn sequences with different prompt lengths decoded together on a bf16 pair, one round per
     threshold in `hs`: every sequence's K, candidates, n and y' replayed by the oracle on the HIP
     path's own rows, and the sequence state stays consistent; for the first `check_rows` sequences
@@ -416,7 +424,7 @@ def _ragged_batch_replay(Bn, k_max, hs, seed, max_exempt, check_rows=0):
     from paper_2405_19715_amd import binding as B
     from oracle import philox
     from oracle.model import forward_full
-    t, d, h = _bf16_pair()
+    t, d, h = _bf16_pair(wide)
     tw, dw = oracle_model(t), oracle_model(d)
     g0 = torch.Generator().manual_seed(123)
     lens = torch.randint(20, 90, (Bn,), generator=g0).tolist()
@@ -476,6 +484,15 @@ def test_ragged_batch_of_eight_bf16_decision_replay():
     """Eight sequences (136 activation rows in the target pass when all draft K_max, ragged K per
     sequence otherwise, per-sequence rollback)."""
     seen_K = _ragged_batch_replay(8, 16, [0.8] * 4, seed=9, max_exempt=3)
+    assert len(seen_K) > 1
+
+
+def test_ragged_batch_through_the_row_stripe_kernels():
+    """Three sequences on a pair 2048 wide: the draft steps carry 6 rows, the target passes 8 or fewer when the
+    sequences stop early and more when they do not, so the rounds alternate between the row-stripe GEMM with its
+    fused SiLU / residual / norm epilogues and the MFMA or tiled kernels with the separate small kernels, on the same
+    caches; rows against the oracle's teacher-forced forward, decisions replayed."""
+    seen_K = _ragged_batch_replay(3, 8, [0.3, 0.6, 0.9, 1.0, 0.5], seed=12, max_exempt=3, check_rows=3, wide=True)
     assert len(seen_K) > 1
 
 
