@@ -205,7 +205,7 @@ sd_status sd_profile_read(sd_ctx *ctx, int64_t *launches, double *seconds, doubl
  * scratch of sd_gemm_workspace_bytes(...) bytes (per-K-slice partial sums, added in
  * slice order).  1 <= M <= 160; for SD_BF16, K % 128 == 0 and N % 16 == 0, pointers
  * 16-byte aligned (more than 16 rows are handed to the tiled kernel below; up to 8 rows with
- * K % 2048 == 0 and K <= 16384 go through a kernel that streams whole 1 KB pieces of single weight
+ * K >= 2048 (K % 8 == 0) go through a kernel that streams whole 1 KB pieces of single weight
  * rows and takes any N >= 1).  Enqueued on `hip_stream`; does not synchronise. */
 sd_status sd_gemm_skinny(int32_t dtype, const void *W_dev, const void *X_dev, int32_t M, int32_t N, int32_t K,
                          float *Y_dev, void *ws_dev, void *hip_stream);
@@ -215,7 +215,9 @@ sd_status sd_gemm_skinny(int32_t dtype, const void *W_dev, const void *X_dev, in
  * W: DEVICE [2 ffn, K] = [gate; up] and X: DEVICE [M, K], both `dtype`; act: DEVICE [M, ffn] in `dtype`.
  * Two ways to the same result, both rounding once, to `dtype`, at the end:
  *   mode 1: ONE launch, the row-stripe GEMM with the activation in its final sweep; ws is not used.  Possible
- *           (sd_mlp_act_is_fused returns 1) for SD_BF16, M <= 8, K a multiple of 2048 up to 8192; SD_EINVAL elsewhere.
+ *           (sd_mlp_act_is_fused returns 1) for SD_BF16, M <= 8, K >= 2048, K % 8 == 0, when a workgroup can hold a
+ *           row range of gate and one of up (always for K <= 8192: up to four 2048-wide stripes per row);
+ *           SD_EINVAL elsewhere.
  *   mode 0: sd_gemm_skinny's product followed by an activation kernel; ws is DEVICE scratch of
  *           sd_gemm_workspace_bytes(dtype, M, 2 ffn, K) bytes.
  *   mode -1: what the forward passes do: mode 1 where it is possible, else mode 0.

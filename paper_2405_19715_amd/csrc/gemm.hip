@@ -376,8 +376,8 @@ struct StripePlan { int S, cs, rpg, G, ranges, rpw, npass; };   // rpg row range
 // (needs one slice and an even number of ranges per workgroup)
 StripePlan plan_stripe(int M, int N, int K, bool paired = false) {
   StripePlan sp{0, 0, 0, 0, 0, 0, 0};
-  if (M < 1 || M > STRIPE_MAX_M || N < 1 || K < RSTEP || K % RSTEP != 0) return sp;
-  const int stripes = K / RSTEP;
+  if (M < 1 || M > STRIPE_MAX_M || N < 1 || K < RSTEP || K % 8 != 0) return sp;
+  const int stripes = (K + RSTEP - 1) / RSTEP;       // the last one may be short (K % 2048 != 0)
   int cs = 1;
   for (int d = 2; d <= GEMM_WAVES; ++d)
     if (stripes % d == 0) cs = d;
@@ -417,7 +417,9 @@ struct StripeEpi {
   float inv_d, eps;        // 1 / (length of the input rows whose squares ssq_in sums), RMSNorm epsilon
 };
 
-template <int MM, int EPI>
+// RAGGED: K is not a multiple of 2048; a lane of the last stripe whose piece lies beyond K reads piece 0 of the
+// stripe again (a fixed per-lane offset: nothing changes in the loop) against zeros in X.
+template <int MM, int EPI, bool RAGGED>
 __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_stripe(const bf16_t* __restrict__ W,
                                                                  const bf16_t* __restrict__ X, int ldx,
                                                                  const int* __restrict__ xrow,
@@ -476,6 +478,13 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_stripe(const bf16_t* _
       if (r >= rows) r -= rows;
       return base + (size_t)r * K;
     };
+    int off[4];                                        // element offset of this lane's piece j from its piece 0
+    bool live[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      live[j] = !RAGGED || c * RSTEP + j * PIECE + lane * 8 < K;
+      off[j] = live[j] ? j * PIECE : 0;
+    }
 
     // X first: its loads are then older than every weight load, and waiting for a weight step never waits for them
     uint4 x[MM][4];                                    // M == MM (the launcher picks the instantiation)
@@ -483,7 +492,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_stripe(const bf16_t* _
     for (int m = 0; m < MM; ++m) {
       const bf16_t* xp = X + (size_t)(xrow ? xrow[m] : m) * ldx + c * RSTEP + lane * 8;
 #pragma unroll
-      for (int j = 0; j < 4; ++j) x[m][j] = ldg128(xp + j * PIECE);
+      for (int j = 0; j < 4; ++j) x[m][j] = ldg128(RAGGED ? xp + off[j] : xp + j * PIECE);
     }
 
     // Every step issues its four loads without a branch around them, so that the compiler can count the loads in
@@ -494,7 +503,15 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_stripe(const bf16_t* _
     for (int p = 0; p < PREFETCH; ++p) {
       const bf16_t* q = p < rows ? at(p) : idle;
 #pragma unroll
-      for (int j = 0; j < 4; ++j) a[p][j] = ldg128_stream(q + j * PIECE);
+      for (int j = 0; j < 4; ++j) a[p][j] = ldg128_stream(RAGGED ? q + off[j] : q + j * PIECE);
+    }
+    if constexpr (RAGGED) {                            // after the prefetch went out: pieces beyond K count as zeros
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int m = 0; m < MM; ++m)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+          if (!live[j]) x[m][j] = uint4{0u, 0u, 0u, 0u};
     }
 
     for (int i0 = 0; i0 < rows; i0 += PREFETCH) {
@@ -514,7 +531,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_stripe(const bf16_t* _
           const bool more = i + PREFETCH < rows;
           const bf16_t* q = more ? at(i + PREFETCH) : idle;
 #pragma unroll
-          for (int j = 0; j < 4; ++j) a[p][j] = ldg128_stream(q + j * PIECE);
+          for (int j = 0; j < 4; ++j) a[p][j] = ldg128_stream(RAGGED ? q + off[j] : q + j * PIECE);
         }
         const float v = reduce_lanes<P2>(acc, lane);
         int r = i + rot;
@@ -598,8 +615,12 @@ hipError_t launch_stripe_mm(hipStream_t st, const bf16_t* W, const bf16_t* X, in
   const size_t lds = (size_t)sp.cs * sp.rpg * MM * sp.rpw * sizeof(float);
   if (lds > STRIPE_LDS_MAX) return hipErrorInvalidValue;
   const dim3 grid(sp.G), block(sp.cs * sp.rpg * WAVE);
-  hipLaunchKernelGGL((gemm_bf16_stripe<MM, EPI>), grid, block, lds, st, W, X, ldx, xrow, part, epi, M, N, K, sp.cs,
-                     sp.rpg, sp.ranges, sp.rpw, sp.npass);
+  if (K % RSTEP)
+    hipLaunchKernelGGL((gemm_bf16_stripe<MM, EPI, true>), grid, block, lds, st, W, X, ldx, xrow, part, epi, M, N, K, sp.cs,
+                       sp.rpg, sp.ranges, sp.rpw, sp.npass);
+  else
+    hipLaunchKernelGGL((gemm_bf16_stripe<MM, EPI, false>), grid, block, lds, st, W, X, ldx, xrow, part, epi, M, N, K, sp.cs,
+                       sp.rpg, sp.ranges, sp.rpw, sp.npass);
   return hipGetLastError();
 }
 
@@ -619,10 +640,9 @@ hipError_t launch_stripe(hipStream_t st, const bf16_t* W, const bf16_t* X, int l
   }
 }
 
-// Up to 8 activation rows and K a multiple of 2048 (up to 8 stripes per wavefront): measured equal or faster than
-// the MFMA kernel on every such matrix of the 70B / 7B shapes, alone and inside the forward pass (70B target pass,
-// 1 .. 8 rows: 2 - 6 % shorter).  A short last stripe (K % 2048 != 0, the 7B down projection) was built too, its
-// lanes beyond K reading the idle line against zeros: 22.4 us against the MFMA kernel's 20, so such K stay there.
+// Up to 8 activation rows and K >= 2048 (up to 8 stripes per wavefront): measured equal or faster than the MFMA
+// kernel on every such matrix of the 70B / 7B / 1.1B shapes, alone and inside the forward pass (70B target pass,
+// 1 .. 8 rows: 2 - 6 % shorter before the fused epilogues, 8 - 12 % with them).
 bool use_stripe(int M, int N, int K) { return plan_stripe(M, N, K).S > 0; }
 
 // ----------------------------------------------------------------------------- fp32 path

@@ -58,10 +58,15 @@ def test_bf16_rows_beyond_the_stripe_kernel_take_the_matrix_cores():
     assert B.lib.sd_gemm_workspace_bytes(B.SD_BF16, 2, 4096, 4096) == 2 * 4096 * 4
     assert B.lib.sd_gemm_workspace_bytes(B.SD_BF16, 8, 8192, 28672) == 8 * 8192 * 4
     _check(4, 4096, 2048 * 11, torch.bfloat16, 3, 3e-5)          # 11 stripes: one wavefront per row range takes them all
-    # 9 rows, or K not a multiple of 2048: MFMA kernel
+    # K not a multiple of 2048: the last stripe is short (lanes beyond K multiply zeros): 11008 = the 7B down
+    # projection (6 stripes, 6 wavefronts), 5632 = the 1.1B one, 2048 + 8 = one 16-byte piece in the last stripe
+    for K in (11008, 5632, 2048 + 8, 4096 + 2040):
+        _check(5, 1000, K, torch.bfloat16, 3, 3e-5)
+        assert B.lib.sd_gemm_workspace_bytes(B.SD_BF16, 5, 1000, K) == 5 * 1000 * 4
+    # 9 rows, or K below 2048: MFMA kernel
     _check(9, 2560, 8192, torch.bfloat16, 3, 3e-5)
-    _check(4, 4096, 2048 + 128, torch.bfloat16, 3, 3e-5)
-    assert B.lib.sd_gemm_workspace_bytes(B.SD_BF16, 4, 4096, 2048 + 128) > 4 * 4096 * 4
+    _check(4, 4096, 1024, torch.bfloat16, 3, 3e-5)
+    assert B.lib.sd_gemm_workspace_bytes(B.SD_BF16, 4, 4096, 1024) > 4 * 4096 * 4
 
 
 @pytest.mark.parametrize("shape", [(1, 256, 256), (9, 1024, 256), (17, 688 * 2, 256), (32, 256, 688), (3, 7, 5)])
