@@ -1,12 +1,14 @@
-// Weight-streaming skinny GEMM: part[s, m, n] = sum_{k in slice s} X[m, k] * W[n, k].
+// Weight-streaming skinny GEMMs: part[s, m, n] = sum_{k in slice s} X[m, k] * W[n, k].
 //
-// This is the kernel the verify pass (M = K+1 rows, Algorithm 2's parallel target
+// These are the kernels the verify pass (M = K+1 rows, Algorithm 2's parallel target
 // forward) and the draft steps (M = 1 or 2 rows) spend their time in: every weight
 // is read from HBM exactly once per call and used for M multiply-adds, so the
-// kernel is bound by HBM bandwidth and its design is about how the weight stream
-// is laid over workgroups, wavefronts and time.
+// kernels are bound by HBM bandwidth and their design is about how the weight stream
+// is laid over workgroups, wavefronts and time.  Two of them: the row-stripe kernel
+// (up to 8 rows, vector-ALU dot products, described where it is defined below) and the
+// MFMA kernel described here (9 .. 16 rows, and K below 2048).
 //
-// bf16 layout of the work
+// bf16 layout of the work of the MFMA kernel
 //   grid       = G row groups x S K-slices.  A workgroup (8 wavefronts) belongs to one
 //                K-slice for its whole life: it stages that slice of X into LDS once
 //                (already in the order the multiply needs) and never synchronises again.
@@ -29,9 +31,9 @@
 //   multiply   = v_mfma_f32_16x16x32_bf16 for every M, weights as the A operand (16 rows
 //                x 32 k), X^T as the B operand (32 k x 16 activation rows), one MFMA per
 //                16-row tile of X; the last tile keeps only its live rows in LDS.  Per-lane
-//                fp32 dot products with a shuffle reduction were measured for M <= 4 and
-//                were slower (M = 1, 12288 x 4096: 29 us against 23 us): the matrix core
-//                costs the wavefront one issue slot per 64 B of weights where the dot
+//                fp32 dot products with a shuffle reduction ON THIS LAYOUT were measured for
+//                M <= 4 and were slower (M = 1, 12288 x 4096: 29 us against 23 us): the matrix
+//                core costs the wavefront one issue slot per 64 B of weights where the dot
 //                product costs sixteen.
 // Per-slice partial sums go to part[s] and are added by the consumer in slice order,
 // so results do not depend on scheduling.
@@ -286,13 +288,15 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_stream(const bf16_t* _
 // Few activation rows (M <= 8).  Every load instruction covers 1 KB of ONE weight row (lane l: k = 8 l .. 8 l + 7
 // of a 512-k piece); a step is four such pieces, 4 KB contiguous.  A wavefront owns one 2048-k stripe of a
 // contiguous range of rows and takes one row per step, so its stripe of X (4 x 16 bytes per lane and
-// activation row) lives in registers for the whole kernel: no LDS, no barrier.  This access pattern reads
+// activation row) lives in registers: no LDS and no barrier inside the stream.  This access pattern reads
 // HBM at 6.5-6.8 TB/s in a pure-read test (70B gate|up) where the MFMA kernel's 8 rows x 128 B per instruction
 // reach 6.4: rows are 16 KB apart, and addresses 16 KB apart meet in the same DRAM channel (the interleave is
 // 4 KB).  The matrix core cannot take operands laid out this way (it wants 16 rows x 32 k across the lanes), so
 // the products are v_dot2_f32_bf16 on the vector ALU, 4 per 16 bytes of weights and activation row, and each
 // row ends with a butterfly over the 64 lanes that reduces all MM sums at once (the lanes halve the set of
-// sums they carry at each of the first log2 MM exchanges).  The K / 2048 stripes are the K-slices of part[].
+// sums they carry at each of the first log2 MM exchanges).  The stripes of a row range all belong to one
+// workgroup, which adds them at the end: one slice of finished sums, on which the final sweep can also do the
+// elementwise work that follows the product in a decoder layer (see EPI below).
 constexpr int STRIPE_MAX_M = 8;
 constexpr size_t STRIPE_LDS_MAX = 64 * 1024;
 constexpr int PIECE = 512;               // k per 1 KB piece
