@@ -227,6 +227,31 @@ int32_t sd_mlp_act_is_fused(int32_t dtype, int32_t M, int32_t ffn, int32_t K);
 sd_status sd_mlp_act(int32_t dtype, const void *W_gate_up_dev, const void *X_dev, int32_t M, int32_t ffn, int32_t K,
                      void *act_dev, void *ws_dev, int32_t mode, void *hip_stream);
 
+/* The first step of a decoder layer's attention as both forward passes of Algorithm 2 compute it, on M rows:
+ *   [q; k; v][m] = W X[m],  W: DEVICE [(n_heads + 2 n_kv_heads) head_dim, K] = q rows, k rows, v rows;
+ *   q and k take the rotary embedding at row_pos[m]: the pair (v[i], v[i + head_dim/2]) of every head is turned by
+ *   the angle whose cosine and sine are cos_sin[row_pos[m]][i][0..1] (DEVICE fp32 [max_seq][head_dim/2][2]);
+ *   q -> q_out [M][n_heads head_dim], k -> k_cache[row_seq[m]][kv head][row_pos[m]][:] of a
+ *   [n_seq][n_kv_heads][max_seq][head_dim] array, v -> v_cache[row_seq[m]][kv head][:][row_pos[m]] of a
+ *   [n_seq][n_kv_heads][head_dim][max_seq] array (values are kept transposed), all in `dtype`.
+ * row_seq, row_pos: DEVICE int32 [M]; a row with row_seq[m] < 0 writes nothing; the caller guarantees
+ * 0 <= row_pos[m] < max_seq and that row_seq[m] indexes the caches.  X: DEVICE [M, K] in `dtype`.
+ *   mode 1: ONE launch: the row-stripe GEMM walks the rows of W so that both rows of a rotary pair land in one
+ *           wavefront, and its final sweep rotates and writes q and the cache entries; ws is not used.  Possible
+ *           (sd_qkv_rope_is_fused returns 1) for SD_BF16, M <= 8, K >= 2048, K % 8 == 0 and head_dim a power
+ *           of two; SD_EINVAL elsewhere.
+ *   mode 0: sd_gemm_skinny's product followed by a rotary + append kernel; ws is DEVICE scratch of
+ *           sd_gemm_workspace_bytes(dtype, M, N, K) bytes, N = (n_heads + 2 n_kv_heads) head_dim.
+ *   mode -1: what the forward passes do: mode 1 where it is possible, else mode 0.
+ * Both modes round once, to `dtype`, at the end, and give the same bits.  1 <= M <= 160 and sd_gemm_skinny's
+ * shape rules; SD_EINVAL / SD_EDEVICE otherwise.  Enqueued on `hip_stream`; does not synchronise. */
+int32_t sd_qkv_rope_is_fused(int32_t dtype, int32_t M, int32_t n_heads, int32_t n_kv_heads, int32_t head_dim,
+                             int32_t K);
+sd_status sd_qkv_rope(int32_t dtype, const void *W_qkv_dev, const void *X_dev, int32_t M, int32_t n_heads,
+                      int32_t n_kv_heads, int32_t head_dim, int32_t K, const int32_t *row_seq_dev,
+                      const int32_t *row_pos_dev, const float *cos_sin_dev, void *q_out_dev, void *k_cache_dev,
+                      void *v_cache_dev, int32_t max_seq, void *ws_dev, int32_t mode, void *hip_stream);
+
 /* ---- Training of the acceptance-prediction head (Sec. 4.4) ---------------------------
  *
  * sd_head_examples builds the training examples of one (prompt, response) pair with the

@@ -90,6 +90,10 @@ _PROTOS = {
     "sd_mlp_act": (C.c_int32, [C.c_int32, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p,
                                C.c_void_p, C.c_int32, C.c_void_p]),
     "sd_mlp_act_is_fused": (C.c_int32, [C.c_int32, C.c_int32, C.c_int32, C.c_int32]),
+    "sd_qkv_rope_is_fused": (C.c_int32, [C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32]),
+    "sd_qkv_rope": (C.c_int32, [C.c_int32, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
+                                C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                C.c_int32, C.c_void_p, C.c_int32, C.c_void_p]),
     "sd_gemm_tile": (C.c_int32, [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p,
                                  C.c_void_p]),
     "sd_gemm_tile_workspace_bytes": (C.c_int64, [C.c_int32, C.c_int32, C.c_int32]),
@@ -314,6 +318,36 @@ def sd_mlp_act(W_gate_up: torch.Tensor, X: torch.Tensor, mode: int = -1) -> torc
 
 def sd_mlp_act_is_fused(dtype: torch.dtype, M: int, ffn: int, K: int) -> bool:
     return bool(lib.sd_mlp_act_is_fused(_dtype_code(dtype), M, ffn, K))
+
+
+def sd_qkv_rope(W_qkv: torch.Tensor, X: torch.Tensor, n_heads: int, n_kv_heads: int, head_dim: int,
+                row_seq: torch.Tensor, row_pos: torch.Tensor, cos_sin: torch.Tensor, q_out: torch.Tensor,
+                k_cache: torch.Tensor, v_cache: torch.Tensor, mode: int = -1) -> None:
+    """q|k|v product of a decoder layer, rotary embedding, q -> q_out [M, Hq hd], k -> k_cache [n_seq, Hkv, max_seq, hd],
+    v -> v_cache [n_seq, Hkv, hd, max_seq] at (row_seq[m], row_pos[m]); rows with row_seq < 0 write nothing.
+    cos_sin: fp32 [max_seq, hd / 2, 2].  mode 1: one launch, 0: product + rotary kernel, -1: the forward passes' choice."""
+    W = W_qkv
+    for t in (W, X, row_seq, row_pos, cos_sin, q_out, k_cache, v_cache):
+        assert t.is_cuda and t.is_contiguous()
+    (N, K), (M, K2) = W.shape, X.shape
+    max_seq = k_cache.shape[2]
+    assert K == K2 and N == (n_heads + 2 * n_kv_heads) * head_dim and W.dtype == X.dtype == q_out.dtype
+    assert k_cache.dtype == W.dtype and v_cache.dtype == W.dtype
+    assert row_seq.dtype == torch.int32 and row_pos.dtype == torch.int32 and row_seq.numel() == M == row_pos.numel()
+    assert cos_sin.dtype == torch.float32 and tuple(cos_sin.shape) == (max_seq, head_dim // 2, 2)
+    assert tuple(q_out.shape) == (M, n_heads * head_dim)
+    assert tuple(k_cache.shape[1:]) == (n_kv_heads, max_seq, head_dim)
+    assert tuple(v_cache.shape) == (k_cache.shape[0], n_kv_heads, head_dim, max_seq)
+    dt = _dtype_code(W.dtype)
+    nbytes = lib.sd_gemm_workspace_bytes(dt, M, N, K)
+    ws = torch.empty(max(nbytes, 16), dtype=torch.uint8, device=W.device)
+    _check(lib.sd_qkv_rope(dt, W.data_ptr(), X.data_ptr(), M, n_heads, n_kv_heads, head_dim, K, row_seq.data_ptr(),
+                           row_pos.data_ptr(), cos_sin.data_ptr(), q_out.data_ptr(), k_cache.data_ptr(),
+                           v_cache.data_ptr(), max_seq, ws.data_ptr(), mode, _stream_ptr()), "sd_qkv_rope")
+
+
+def sd_qkv_rope_is_fused(dtype: torch.dtype, M: int, n_heads: int, n_kv_heads: int, head_dim: int, K: int) -> bool:
+    return bool(lib.sd_qkv_rope_is_fused(_dtype_code(dtype), M, n_heads, n_kv_heads, head_dim, K))
 
 
 def sd_gemm_tile(W: torch.Tensor, X: torch.Tensor, out: Optional[torch.Tensor] = None) -> torch.Tensor:

@@ -33,6 +33,13 @@ template <> struct Elem<bf16_t> {
   static __device__ __forceinline__ void st(bf16_t* p, float v) { *p = f2bf(v); }
 };
 
+// Rotary embedding of the pair (a, b) = (v[i], v[i + hd/2]) by the angle whose cosine and sine are c and s.  One
+// definition with its roundings spelled out, so that every kernel that rotates gives the same bits.
+__device__ __forceinline__ void rope_pair(float a, float b, float c, float s, float& ra, float& rb) {
+  ra = fmaf(a, c, -__fmul_rn(b, s));
+  rb = fmaf(b, c, __fmul_rn(a, s));
+}
+
 // Butterfly reductions over the 64 lanes of a wavefront (fixed order, so results
 // do not depend on scheduling).
 __device__ __forceinline__ float wave_sum(float v) {

@@ -162,7 +162,8 @@ __global__ __launch_bounds__(64) void rope_kv_k(const float* __restrict__ part, 
         b += p0[s * sstride + i + half];
       }
       const float c = cos_sin[((size_t)pos * half + i) * 2], sn = cos_sin[((size_t)pos * half + i) * 2 + 1];
-      const float ra = a * c - b * sn, rb = b * c + a * sn;
+      float ra, rb;
+      rope_pair(a, b, c, sn, ra, rb);
       if (slot < Hq) {
         T* q = qbuf + ((size_t)m * Hq + slot) * hd;
         Elem<T>::st(q + i, ra);

@@ -251,23 +251,32 @@ sd_status forward(sd_ctx* c, ModelRt& rt, int M, int RS, int max_kv_len, const i
   const bool fuse_act = gemm_silu_fused(dt, M, m.d_ffn, d);     // gate|up GEMM writes silu(gate) * up itself
   const int res_groups = fuse_act ? gemm_resid_groups(dt, M, d, nq) : 0;   // > 0: residual + norm ride on the o projection
   const int down_groups = gemm_scaled_ok(dt, M, nq + 2 * nkv, d) ? gemm_resid_groups(dt, M, d, m.d_ffn) : 0;   // and on down
+  const bool rope_fused = !tile && gemm_rope_fused(dt, M, m.n_heads, m.n_kv_heads, m.head_dim, d);
   int in_groups = 0;            // > 0: xn = x * gain without the rows' norm factors; their sums of squares sit in c->ssq
   SD_HIP(launch_embed_norm(st, dt, m.tok_emb, rt.na[0], m.rms_eps, c->rows.tok, c->x, c->xn, c->ssq, M, d, m.vocab));
   for (int l = 0; l < m.n_layers; ++l) {
     const bool pr = profile && c->prof_every > 0 && (l % c->prof_every) == 0;
     sd_status s;
-    if (in_groups > 0) {          // the rows of xn still lack their RMSNorm factor (previous layer's down projection)
-      ProfSample* ps = pr ? prof_begin(c, 0, (double)(nq + 2 * nkv) * d * rt.esz) : nullptr;
-      SD_HIP(launch_gemm_scaled(st, dt, rt.wqkv[l], c->xn, d, nullptr, c->part, M, nq + 2 * nkv, d, c->ssq, in_groups, d,
-                                m.rms_eps));
-      if (ps) (void)hipEventRecord(ps->b, st);
-    } else if ((s = mm(rt.wqkv[l], c->xn, d, nq + 2 * nkv, d, pr ? 0 : -1)) != SD_OK) {
-      return s;
-    }
     void* kc = rt.kcache + (size_t)l * rt.layer_bytes;
     void* vc = rt.vcache + (size_t)l * rt.layer_bytes;
-    SD_HIP(launch_rope_kv(st, dt, c->part, slices(nq + 2 * nkv, d), c->rows, rt.cos_sin, c->qbuf, kc, vc,
-                          M, m.n_heads, m.n_kv_heads, m.head_dim, c->cfg.max_seq));
+    if (rope_fused) {             // q|k|v product, rotary embedding and KV append in one launch
+      ProfSample* ps = pr ? prof_begin(c, 0, (double)(nq + 2 * nkv) * d * rt.esz) : nullptr;
+      SD_HIP(launch_gemm_rope(st, dt, rt.wqkv[l], c->xn, d, M, m.n_heads, m.n_kv_heads, m.head_dim, d, c->rows.seq,
+                              c->rows.pos, rt.cos_sin, c->qbuf, kc, vc, c->cfg.max_seq,
+                              in_groups > 0 ? c->ssq : nullptr, in_groups, d, m.rms_eps));
+      if (ps) (void)hipEventRecord(ps->b, st);
+    } else {
+      if (in_groups > 0) {        // the rows of xn still lack their RMSNorm factor (previous layer's down projection)
+        ProfSample* ps = pr ? prof_begin(c, 0, (double)(nq + 2 * nkv) * d * rt.esz) : nullptr;
+        SD_HIP(launch_gemm_scaled(st, dt, rt.wqkv[l], c->xn, d, nullptr, c->part, M, nq + 2 * nkv, d, c->ssq, in_groups,
+                                  d, m.rms_eps));
+        if (ps) (void)hipEventRecord(ps->b, st);
+      } else if ((s = mm(rt.wqkv[l], c->xn, d, nq + 2 * nkv, d, pr ? 0 : -1)) != SD_OK) {
+        return s;
+      }
+      SD_HIP(launch_rope_kv(st, dt, c->part, slices(nq + 2 * nkv, d), c->rows, rt.cos_sin, c->qbuf, kc, vc,
+                            M, m.n_heads, m.n_kv_heads, m.head_dim, c->cfg.max_seq));
+    }
     SD_HIP(launch_attention(st, dt, c->qbuf, kc, vc, c->rows, c->attn, c->attn_scratch, M, RS, m.n_heads,
                             m.n_kv_heads, m.head_dim, c->cfg.max_seq, max_kv_len, tile));
     if (res_groups > 0) {
@@ -923,6 +932,41 @@ sd_status sd_mlp_act(int32_t dtype, const void* W_gate_up, const void* X, int32_
   if (!ws) return SD_EINVAL;
   SD_HIP(launch_gemm(st, dtype, W_gate_up, X, K, nullptr, (float*)ws, M, 2 * ffn, K));
   SD_HIP(launch_silu_mul(st, dtype, (const float*)ws, gemm_splits(dtype, M, 2 * ffn, K), act, M, ffn));
+  return SD_OK;
+}
+
+int32_t sd_qkv_rope_is_fused(int32_t dtype, int32_t M, int32_t n_heads, int32_t n_kv_heads, int32_t head_dim,
+                             int32_t K) {
+  if ((dtype != SD_F32 && dtype != SD_BF16) || M < 1 || M > MAX_ROWS || n_heads < 1 || n_kv_heads < 1 ||
+      head_dim < 2 || K < 1)
+    return 0;
+  return gemm_rope_fused(dtype, M, n_heads, n_kv_heads, head_dim, K) ? 1 : 0;
+}
+
+sd_status sd_qkv_rope(int32_t dtype, const void* W_qkv, const void* X, int32_t M, int32_t n_heads, int32_t n_kv_heads,
+                      int32_t head_dim, int32_t K, const int32_t* row_seq, const int32_t* row_pos,
+                      const float* cos_sin, void* q_out, void* k_cache, void* v_cache, int32_t max_seq, void* ws,
+                      int32_t mode, void* hip_stream) {
+  if (!W_qkv || !X || !row_seq || !row_pos || !cos_sin || !q_out || !k_cache || !v_cache ||
+      (dtype != SD_F32 && dtype != SD_BF16) || M < 1 || M > MAX_ROWS || n_heads < 1 || n_kv_heads < 1 ||
+      head_dim < 2 || (head_dim & 1) || K < 1 || max_seq < 1 || mode < -1 || mode > 1)
+    return SD_EINVAL;
+  hipStream_t st = (hipStream_t)hip_stream;
+  const bool can = gemm_rope_fused(dtype, M, n_heads, n_kv_heads, head_dim, K);
+  if (mode == 1 && !can) return SD_EINVAL;
+  if (mode != 0 && can) {
+    SD_HIP(launch_gemm_rope(st, dtype, W_qkv, X, K, M, n_heads, n_kv_heads, head_dim, K, row_seq, row_pos, cos_sin,
+                            q_out, k_cache, v_cache, max_seq, nullptr, 0, 0, 0.f));
+    return SD_OK;
+  }
+  if (!ws) return SD_EINVAL;
+  const int N = (n_heads + 2 * n_kv_heads) * head_dim;
+  SD_HIP(launch_gemm(st, dtype, W_qkv, X, K, nullptr, (float*)ws, M, N, K));
+  RowPlan rows{};
+  rows.seq = const_cast<int32_t*>(row_seq);
+  rows.pos = const_cast<int32_t*>(row_pos);
+  SD_HIP(launch_rope_kv(st, dtype, (const float*)ws, gemm_splits(dtype, M, N, K), rows, cos_sin, q_out, k_cache,
+                        v_cache, M, n_heads, n_kv_heads, head_dim, max_seq));
   return SD_OK;
 }
 

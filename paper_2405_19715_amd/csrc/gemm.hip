@@ -378,7 +378,8 @@ struct StripePlan { int S, cs, rpg, G, ranges, rpw, npass; };   // rpg row range
 
 // paired: N is the row count of each half of a [gate; up] matrix, and a workgroup takes its ranges in pairs
 // (needs one slice and an even number of ranges per workgroup)
-StripePlan plan_stripe(int M, int N, int K, bool paired = false) {
+// even_rows: every range holds an even number of rows (the rotary pairs of EPI_ROPE stay inside one wavefront)
+StripePlan plan_stripe(int M, int N, int K, bool paired = false, bool even_rows = false) {
   StripePlan sp{0, 0, 0, 0, 0, 0, 0};
   if (M < 1 || M > STRIPE_MAX_M || N < 1 || K < RSTEP || K % 8 != 0) return sp;
   const int stripes = (K + RSTEP - 1) / RSTEP;       // the last one may be short (K % 2048 != 0)
@@ -392,7 +393,11 @@ StripePlan plan_stripe(int M, int N, int K, bool paired = false) {
   const int units = paired ? rpg / 2 : rpg;          // ranges of N a workgroup covers
   int ranges = 256 * units;                          // one workgroup per CU
   if (ranges > N) ranges = N;
-  const int rpw = (N + ranges - 1) / ranges;
+  int rpw = (N + ranges - 1) / ranges;
+  if (even_rows) {
+    if (N & 1) return sp;
+    rpw += rpw & 1;
+  }
   ranges = (N + rpw - 1) / rpw;
   const int G = (ranges + units - 1) / units;
   if ((size_t)cs * rpg * M * rpw * sizeof(float) > STRIPE_LDS_MAX) return sp;         // the wavefronts' output tiles
@@ -410,7 +415,12 @@ StripePlan plan_stripe(int M, int N, int K, bool paired = false) {
 //             product's input WITHOUT the RMSNorm factor of its row (a per-row scalar commutes with the product, so
 //             the consumer applies it to its sums); ssq_out[m][workgroup] = sum of x[m, n]^2 over the workgroup's
 //             columns, added by the consumer in workgroup order.  Residual + RMSNorm without a launch of their own.
-enum { EPI_PART = 0, EPI_SILU = 1, EPI_RESID = 2 };
+//   EPI_ROPE  W = [q; k; v] rows of a decoder layer, head dimension 2^(hshift+1).  The row ranges walk the rows in
+//             the order (head, i, half): local index j stands for row (j/2 / half) hd + (j/2 % half) + (j%2) half,
+//             so the two sums of a rotary pair (i, i + hd/2) sit side by side in one wavefront's tile, and the sweep
+//             rotates them at the row's position and writes q (bf16 [M, Hq hd]), the key cache row and the
+//             (transposed) value cache column itself: no launch of its own for the rotary embedding and the KV append.
+enum { EPI_PART = 0, EPI_SILU = 1, EPI_RESID = 2, EPI_ROPE = 3 };
 struct StripeEpi {
   bf16_t* act;             // SILU / RESID output [M][N]
   float* x;                // RESID: residual rows [M][N], updated in place
@@ -419,6 +429,14 @@ struct StripeEpi {
   const float* ssq_in;     // PART / SILU: [M][ssq_n] or null
   int ssq_n;
   float inv_d, eps;        // 1 / (length of the input rows whose squares ssq_in sums), RMSNorm epsilon
+  // ROPE
+  const int32_t* row_seq;  // [M] sequence of the row, < 0 = padding row (nothing written)
+  const int32_t* row_pos;  // [M] position of the row's token
+  const float* cos_sin;    // [max_seq][hd / 2][2]
+  bf16_t* qbuf;            // [M][Hq * hd]
+  bf16_t* kcache;          // [seq][Hkv][max_seq][hd]
+  bf16_t* vcache;          // [seq][Hkv][hd][max_seq]
+  int Hq, Hkv, hshift, max_seq;
 };
 
 // RAGGED: K is not a multiple of 2048; a lane of the last stripe whose piece lies beyond K reads piece 0 of the
@@ -480,6 +498,12 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_stripe(const bf16_t* _
     auto at = [&](int t) -> const bf16_t* {
       int r = t + rot;
       if (r >= rows) r -= rows;
+      if constexpr (EPI == EPI_ROPE) {                 // local index -> row of W: (head, i, half) order
+        const int hs = epi.hshift;
+        const int j = r0 + r, p = j >> 1;
+        const int row = ((p >> hs) << (hs + 1)) + (p & ((1 << hs) - 1)) + ((j & 1) << hs);
+        return W + (size_t)row * K + c * RSTEP + lane * 8;
+      }
       return base + (size_t)r * K;
     };
     int off[4];                                        // element offset of this lane's piece j from its piece 0
@@ -577,6 +601,41 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_stripe(const bf16_t* _
       gate *= rm;
       up *= rm;
       epi.act[(size_t)m * N + g * rpw + r] = f2bf(gate / (1.0f + expf(-gate)) * up);
+    }
+  } else if constexpr (EPI == EPI_ROPE) {
+    const int hw = rpw >> 1, hs = epi.hshift, half = 1 << hs, hd = 2 << hs;
+    for (int idx = threadIdx.x; idx < rpg * MM * hw; idx += blockDim.x) {
+      const int l = idx / (MM * hw), rem = idx - l * (MM * hw);
+      const int m = rem / hw, q = rem - m * hw;
+      const int g = blockIdx.x * rpg + l;
+      const int j = g * rpw + 2 * q;                   // local index of the pair's first row
+      if (g >= ranges || j >= N) continue;
+      const int seq = epi.row_seq[m];
+      if (seq < 0) continue;
+      const int pos = epi.row_pos[m];
+      const float* src = obuf + (size_t)l * cs * tile + m * rpw + 2 * q;
+      float a = src[0], b = src[1];
+      for (int t = 1; t < cs; ++t) {
+        a += src[(size_t)t * tile];
+        b += src[(size_t)t * tile + 1];
+      }
+      a *= s_scale[m];
+      b *= s_scale[m];
+      const int p = j >> 1, slot = p >> hs, i = p & (half - 1);
+      if (slot < epi.Hq + epi.Hkv) {
+        const float* cs2 = epi.cos_sin + ((size_t)pos * half + i) * 2;
+        float ra, rb;
+        rope_pair(a, b, cs2[0], cs2[1], ra, rb);
+        bf16_t* dst = slot < epi.Hq
+                          ? epi.qbuf + ((size_t)m * epi.Hq + slot) * hd + i
+                          : epi.kcache + (((size_t)seq * epi.Hkv + (slot - epi.Hq)) * epi.max_seq + pos) * hd + i;
+        dst[0] = f2bf(ra);
+        dst[half] = f2bf(rb);
+      } else {
+        bf16_t* v = epi.vcache + ((size_t)seq * epi.Hkv + (slot - epi.Hq - epi.Hkv)) * hd * (size_t)epi.max_seq + pos;
+        v[(size_t)i * epi.max_seq] = f2bf(a);
+        v[(size_t)(i + half) * epi.max_seq] = f2bf(b);
+      }
     }
   } else if constexpr (EPI == EPI_RESID) {
     // wavefront w takes activation rows w, w + (wavefronts), ...: a row's sum of squares stays inside one wavefront
@@ -780,6 +839,49 @@ hipError_t launch_gemm_scaled(hipStream_t st, int dtype, const void* W, const vo
   epi.eps = eps;
   return launch_stripe<EPI_PART>(st, (const bf16_t*)W, (const bf16_t*)X, ldx, xrow, part, epi, M, N, K,
                                  plan_stripe(M, N, K));
+}
+
+namespace {
+int log2_exact(int v) {                 // -1 unless v is a power of two
+  if (v < 1 || (v & (v - 1))) return -1;
+  int s = 0;
+  while ((1 << s) < v) ++s;
+  return s;
+}
+}  // namespace
+
+bool gemm_rope_fused(int dtype, int M, int Hq, int Hkv, int hd, int K) {
+  if (dtype != DT_BF16 || Hq < 1 || Hkv < 1 || hd < 2 || log2_exact(hd) < 1) return false;
+  return plan_stripe(M, (Hq + 2 * Hkv) * hd, K, false, true).S == 1;
+}
+
+hipError_t launch_gemm_rope(hipStream_t st, int dtype, const void* W, const void* X, int ldx, int M, int Hq, int Hkv,
+                            int hd, int K, const int32_t* row_seq, const int32_t* row_pos, const float* cos_sin,
+                            void* qbuf, void* kcache, void* vcache, int max_seq, const float* ssq, int ssq_n, int d_in,
+                            float eps) {
+  if (!W || !X || !row_seq || !row_pos || !cos_sin || !qbuf || !kcache || !vcache || max_seq < 1 || ldx < K ||
+      ldx % 8 != 0 || !gemm_rope_fused(dtype, M, Hq, Hkv, hd, K))
+    return hipErrorInvalidValue;
+  if (ssq && (ssq_n < 1 || ssq_n > 256 || d_in < 1)) return hipErrorInvalidValue;
+  if ((reinterpret_cast<uintptr_t>(W) | reinterpret_cast<uintptr_t>(X)) & 15) return hipErrorInvalidValue;
+  StripeEpi epi{};
+  epi.ssq_in = ssq;
+  epi.ssq_n = ssq ? ssq_n : 0;
+  epi.inv_d = ssq ? 1.0f / (float)d_in : 0.f;
+  epi.eps = eps;
+  epi.row_seq = row_seq;
+  epi.row_pos = row_pos;
+  epi.cos_sin = cos_sin;
+  epi.qbuf = (bf16_t*)qbuf;
+  epi.kcache = (bf16_t*)kcache;
+  epi.vcache = (bf16_t*)vcache;
+  epi.Hq = Hq;
+  epi.Hkv = Hkv;
+  epi.hshift = log2_exact(hd) - 1;
+  epi.max_seq = max_seq;
+  const int N = (Hq + 2 * Hkv) * hd;
+  return launch_stripe<EPI_ROPE>(st, (const bf16_t*)W, (const bf16_t*)X, ldx, nullptr, nullptr, epi, M, N, K,
+                                 plan_stripe(M, N, K, false, true));
 }
 
 int gemm_resid_groups(int dtype, int M, int N, int K) {

@@ -49,6 +49,16 @@ bool gemm_scaled_ok(int dtype, int M, int N, int K);
 hipError_t launch_gemm_scaled(hipStream_t st, int dtype, const void* W, const void* X, int ldx, const int* xrow,
                               float* part, int M, int N, int K, const float* ssq, int ssq_n, int d_in, float eps);
 int gemm_resid_groups(int dtype, int M, int N, int K);
+// The q|k|v product of a decoder layer (W = [q rows; k rows; v rows], (Hq + 2 Hkv) hd rows of K) that also does
+// what follows it: rotary embedding of q and k at row_pos[m], q -> qbuf [M, Hq hd], k -> kcache[seq, kvh, pos, :],
+// v -> vcache[seq, kvh, :, pos]; rows with row_seq[m] < 0 write nothing.  With `ssq` the sums first take the rows'
+// RMSNorm factors as in launch_gemm_scaled.  Row-stripe shapes with a power-of-two head dimension only
+// (gemm_rope_fused); elsewhere launch_gemm + launch_rope_kv do the same in two launches.
+bool gemm_rope_fused(int dtype, int M, int Hq, int Hkv, int hd, int K);
+hipError_t launch_gemm_rope(hipStream_t st, int dtype, const void* W, const void* X, int ldx, int M, int Hq, int Hkv,
+                            int hd, int K, const int32_t* row_seq, const int32_t* row_pos, const float* cos_sin,
+                            void* qbuf, void* kcache, void* vcache, int max_seq, const float* ssq, int ssq_n, int d_in,
+                            float eps);
 hipError_t launch_gemm_resid(hipStream_t st, int dtype, const void* W, const void* X, int ldx, const int* xrow,
                              float* x, const void* gain, void* xg, float* ssq, int M, int N, int K);
 

@@ -49,4 +49,13 @@ def test_host_side_argument_checks_need_no_gpu():
     assert B.lib.sd_mlp_act_is_fused(B.SD_BF16, 4, 512, 16384) == 0
     assert B.lib.sd_mlp_act_is_fused(B.SD_F32, 1, 688, 256) == 0
     assert B.lib.sd_mlp_act(B.SD_BF16, None, None, 1, 8, 128, None, None, -1, None) == B.SD_EINVAL
+    # the q|k|v product that rotates and appends: the same row limits, head dimension a power of two
+    assert B.lib.sd_qkv_rope_is_fused(B.SD_BF16, 8, 64, 8, 128, 8192) == 1
+    assert B.lib.sd_qkv_rope_is_fused(B.SD_BF16, 1, 32, 32, 128, 4096) == 1
+    assert B.lib.sd_qkv_rope_is_fused(B.SD_BF16, 9, 64, 8, 128, 8192) == 0
+    assert B.lib.sd_qkv_rope_is_fused(B.SD_BF16, 2, 8, 2, 96, 2048) == 0
+    assert B.lib.sd_qkv_rope_is_fused(B.SD_BF16, 2, 8, 2, 64, 1024) == 0
+    assert B.lib.sd_qkv_rope_is_fused(B.SD_F32, 2, 8, 2, 64, 2048) == 0
+    assert B.lib.sd_qkv_rope(B.SD_BF16, None, None, 1, 8, 2, 64, 2048, None, None, None, None, None, None, 64, None,
+                             -1, None) == B.SD_EINVAL
     assert B.lib.sd_version().decode().startswith("specdec")

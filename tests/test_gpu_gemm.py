@@ -162,3 +162,91 @@ def test_mlp_activation_where_the_one_launch_kernel_does_not_apply(M, ffn, K, dt
     W, X = _mlp_case(M, ffn, K, dtype, 5)
     with pytest.raises(B.SpecDecError):
         B.sd_mlp_act(W.cuda(), X.cuda(), mode=1)
+
+
+# ---------------------------------------------------------------- q|k|v product + rotary embedding + KV append
+def _qkv_case(M, Hq, Hkv, hd, K, dtype, seed, n_seq=3, max_seq=64):
+    g = torch.Generator().manual_seed(seed)
+    N = (Hq + 2 * Hkv) * hd
+    W = (torch.randn((N, K), generator=g) * (1.0 / K ** 0.5)).to(dtype)
+    X = torch.randn((M, K), generator=g).to(dtype)
+    seq = torch.randint(0, n_seq, (M,), generator=g, dtype=torch.int32)
+    pos = torch.randperm(max_seq, generator=g)[:M].to(torch.int32)        # distinct cache slots
+    if M >= 3:
+        seq[M // 2] = -1                                                  # a padding row writes nothing
+    return W, X, seq, pos
+
+
+def _qkv_run(M, Hq, Hkv, hd, K, dtype, seed, mode, n_seq=3, max_seq=64, theta=10000.0):
+    """Runs sd_qkv_rope and checks q, the key rows and the value columns it wrote against the oracle's rotary
+    embedding of the fp64 product; everything it must not touch keeps its fill value."""
+    from oracle import model as OM
+    from paper_2405_19715_amd import binding as B
+    W, X, seq, pos = _qkv_case(M, Hq, Hkv, hd, K, dtype, seed, n_seq, max_seq)
+    half = hd // 2
+    ang = np.arange(max_seq, dtype=np.float64)[:, None] * theta ** (-np.arange(half, dtype=np.float64) * 2 / hd)
+    cos_sin = torch.from_numpy(np.stack([np.cos(ang), np.sin(ang)], axis=-1).astype(np.float32))
+    fill = 7.0
+    q = torch.full((M, Hq * hd), fill, dtype=dtype).cuda()
+    kc = torch.full((n_seq, Hkv, max_seq, hd), fill, dtype=dtype).cuda()
+    vc = torch.full((n_seq, Hkv, hd, max_seq), fill, dtype=dtype).cuda()
+    B.sd_qkv_rope(W.cuda(), X.cuda(), Hq, Hkv, hd, seq.cuda(), pos.cuda(), cos_sin.cuda(), q, kc, vc, mode=mode)
+    torch.cuda.synchronize()
+    q_t, kc_t, vc_t = q.cpu(), kc.cpu(), vc.cpu()
+
+    y = X.double().numpy() @ W.double().numpy().T
+    p = pos.numpy().astype(np.int64)
+    want_q = OM.rope(y[:, : Hq * hd].reshape(M, Hq, hd), p, theta).reshape(M, Hq * hd)
+    want_k = OM.rope(y[:, Hq * hd: (Hq + Hkv) * hd].reshape(M, Hkv, hd), p, theta)
+    want_v = y[:, (Hq + Hkv) * hd:].reshape(M, Hkv, hd)
+    rel = 2.0 ** -8 if dtype == torch.bfloat16 else 1e-5
+    floor = 3e-5 * np.abs(X.double().numpy()).max() * np.abs(W.double().numpy()).max() * K ** 0.5
+
+    def close(got, want, what):
+        bad = np.abs(got - want) > rel * np.abs(want) + floor
+        assert not bad.any(), (what, M, Hq, Hkv, hd, K, mode, int(bad.sum()), float(np.abs(got - want).max()))
+
+    exp_k = torch.full_like(kc_t, fill).double().numpy()
+    exp_v = torch.full_like(vc_t, fill).double().numpy()
+    live = seq.numpy() >= 0
+    for m in range(M):
+        if not live[m]:
+            assert (q_t[m].float() == fill).all()
+            continue
+        close(q_t[m].double().numpy(), want_q[m], "q")
+        exp_k[seq[m], :, p[m], :] = want_k[m]
+        exp_v[seq[m], :, :, p[m]] = want_v[m]
+    close(kc_t.double().numpy(), exp_k, "k cache")       # untouched entries must equal the fill exactly:
+    close(vc_t.double().numpy(), exp_v, "v cache")       # |7 - want| is far outside the tolerance
+    written_k = np.zeros(exp_k.shape, bool)
+    written_v = np.zeros(exp_v.shape, bool)
+    for m in range(M):
+        if live[m]:
+            written_k[seq[m], :, p[m], :] = True
+            written_v[seq[m], :, :, p[m]] = True
+    assert (kc_t.float().numpy()[~written_k] == fill).all() and (vc_t.float().numpy()[~written_v] == fill).all()
+    return q_t, kc_t, vc_t
+
+
+# head dimensions 128 and 64, grouped and plain heads, one to four stripes and a ragged last stripe, every row count
+@pytest.mark.parametrize("M,Hq,Hkv,hd,K", [(1, 16, 2, 128, 2048), (2, 32, 32, 128, 4096), (3, 8, 1, 128, 8192),
+                                           (4, 12, 4, 64, 2048), (5, 5, 5, 64, 6144), (6, 64, 8, 128, 8192),
+                                           (7, 3, 1, 32, 4096), (8, 16, 4, 128, 5120), (8, 1, 1, 16, 2048),
+                                           (2, 20, 4, 128, 2560)])
+def test_qkv_rotary_append_one_launch_kernel(M, Hq, Hkv, hd, K):
+    from paper_2405_19715_amd import binding as B
+    assert B.sd_qkv_rope_is_fused(torch.bfloat16, M, Hq, Hkv, hd, K)
+    fused = _qkv_run(M, Hq, Hkv, hd, K, torch.bfloat16, 77 + M, mode=1)
+    split = _qkv_run(M, Hq, Hkv, hd, K, torch.bfloat16, 77 + M, mode=0)
+    for a, b in zip(fused, split):
+        assert torch.equal(a.view(torch.int16), b.view(torch.int16))
+
+
+@pytest.mark.parametrize("M,Hq,Hkv,hd,K,dtype", [(9, 16, 2, 128, 2048, torch.bfloat16), (4, 8, 2, 96, 2048, torch.bfloat16),
+                                                 (17, 8, 2, 64, 512, torch.bfloat16), (3, 4, 2, 16, 64, torch.float32)])
+def test_qkv_rotary_append_where_the_one_launch_kernel_does_not_apply(M, Hq, Hkv, hd, K, dtype):
+    from paper_2405_19715_amd import binding as B
+    assert not B.sd_qkv_rope_is_fused(dtype, M, Hq, Hkv, hd, K)
+    _qkv_run(M, Hq, Hkv, hd, K, dtype, 9, mode=-1)
+    with pytest.raises(B.SpecDecError):
+        _qkv_run(M, Hq, Hkv, hd, K, dtype, 9, mode=1)
