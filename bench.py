@@ -413,8 +413,9 @@ def main():
     ap.add_argument("--train-epochs", type=int, default=3)
     ap.add_argument("--w-rej", type=float, default=3.0)
     ap.add_argument("--lr", type=float, default=5e-5)
-    ap.add_argument("--profile-every", type=int, default=8,
-                    help="bracket the target GEMMs of every n-th layer with HIP events (0 = off)")
+    ap.add_argument("--profile-every", type=int, default=20,
+                    help="bracket the target GEMMs of every n-th layer with HIP events, one layer further with each "
+                         "pass (0 = off)")
     args = ap.parse_args()
     if args.gpus != 1:
         raise SystemExit("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)")

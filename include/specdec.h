@@ -191,8 +191,11 @@ sd_status sd_last_round_rows(sd_ctx *ctx, int32_t seq, float *q_logits_host, flo
 
 /* Per-launch timing of the weight-streaming GEMM kernels of the target pass.
  * sd_profile_enable(ctx, every) brackets the GEMM launches of every `every`-th
- * target layer (and the LM head) with HIP events from then on (0 = off).
- * sd_profile_read sums, since the last read, the sampled launches' streamed weight
+ * target layer (and the LM head) with HIP events from then on (0 = off); the sampled
+ * layers move on by one with every pass (pass p samples the layers l with
+ * (l + p) % every == 0), so a run of passes covers all of them.
+ * sd_profile_read waits for the context's stream, then sums, since the last read, the
+ * sampled launches' streamed weight
  * bytes and durations per matrix kind (0 qkv, 1 o, 2 gate_up, 3 down, 4 lm_head):
  * HOST arrays of 5. */
 sd_status sd_profile_enable(sd_ctx *ctx, int32_t every);

@@ -83,6 +83,7 @@ struct sd_ctx {
 
   hipEvent_t ev[4]{};
   int prof_every = 0;
+  int prof_pass = 0;              // profiled target passes since sd_profile_enable: rotates the sampled layers
   std::vector<ProfSample> prof_pool;
   size_t prof_used = 0;
   int64_t prof_launches[5]{};
@@ -207,6 +208,9 @@ ProfSample* prof_begin(sd_ctx* c, int kind, double bytes) {
   return ps;
 }
 
+// Reading the timers is kept out of the rounds (an elapsed-time query costs the host microseconds, 40 of them
+// a good part of a millisecond): samples pile up in the pool until sd_profile_read, or until the pool is large.
+constexpr size_t PROF_POOL_SOFT_MAX = 8192;
 void prof_collect(sd_ctx* c) {      // stream must be idle
   for (size_t i = 0; i < c->prof_used; ++i) {
     ProfSample& ps = c->prof_pool[i];
@@ -255,7 +259,7 @@ sd_status forward(sd_ctx* c, ModelRt& rt, int M, int RS, int max_kv_len, const i
   int in_groups = 0;            // > 0: xn = x * gain without the rows' norm factors; their sums of squares sit in c->ssq
   SD_HIP(launch_embed_norm(st, dt, m.tok_emb, rt.na[0], m.rms_eps, c->rows.tok, c->x, c->xn, c->ssq, M, d, m.vocab));
   for (int l = 0; l < m.n_layers; ++l) {
-    const bool pr = profile && c->prof_every > 0 && (l % c->prof_every) == 0;
+    const bool pr = profile && c->prof_every > 0 && ((l + c->prof_pass) % c->prof_every) == 0;
     sd_status s;
     void* kc = rt.kcache + (size_t)l * rt.layer_bytes;
     void* vc = rt.vcache + (size_t)l * rt.layer_bytes;
@@ -321,6 +325,7 @@ sd_status forward(sd_ctx* c, ModelRt& rt, int M, int RS, int max_kv_len, const i
     SD_HIP(launch_reduce_rows(st, c->part, gemm_splits(dt, n_lm, m.vocab, d), logits_out, lm_rs, ld_group, ld_row, n_lm,
                               m.vocab, lm_dst));
   }
+  if (profile && c->prof_every > 0) ++c->prof_pass;        // the next pass samples the layers one further
   return SD_OK;
 }
 
@@ -652,7 +657,7 @@ static sd_status round_impl(sd_ctx* c, const sd_params* params, sd_round_out* ou
   SD_HIP(hipEventRecord(c->ev[3], st));
   SD_HIP(hipMemcpyAsync(c->pinned, c->result, (size_t)B * RESULT_INTS * sizeof(int32_t), hipMemcpyDeviceToHost, st));
   SD_HIP(hipStreamSynchronize(st));
-  prof_collect(c);
+  if (c->prof_used > PROF_POOL_SOFT_MAX) prof_collect(c);
 
   bool nonfinite = false;
   for (int b = 0; b < B; ++b) {
@@ -882,11 +887,14 @@ sd_status sd_last_round_rows(sd_ctx* c, int32_t seq, float* q_host, float* p_hos
 sd_status sd_profile_enable(sd_ctx* c, int32_t every) {
   if (!c || every < 0) return SD_EINVAL;
   c->prof_every = every;
+  c->prof_pass = 0;
   return SD_OK;
 }
 
 sd_status sd_profile_read(sd_ctx* c, int64_t* launches, double* seconds, double* bytes) {
   if (!c || !launches || !seconds || !bytes) return SD_EINVAL;
+  SD_HIP(hipStreamSynchronize(c->st));
+  prof_collect(c);
   for (int k = 0; k < 5; ++k) {
     launches[k] = c->prof_launches[k];
     seconds[k] = c->prof_seconds[k];

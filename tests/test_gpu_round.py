@@ -618,3 +618,40 @@ def test_rounds_on_a_stream_of_the_callers():
         finally:
             ctx.close()
     side.synchronize()
+
+
+def test_gemm_timers_rotate_over_the_layers_and_change_nothing():
+    """sd_profile_enable(every) brackets the target pass's GEMM launches of every `every`-th layer, one layer
+    further with each pass; sd_profile_read returns what piled up since the last read.  The counts and bytes
+    are fixed by that rule, and the rounds must give the same tokens with the timers on."""
+    from paper_2405_19715_amd import binding as B
+    t, d, h = _bf16_pair()
+    prompt = synth.make_prompt(40, 2048, 3)
+    gp = B.make_params(h=0.8, temperature=1.0, greedy=False, seed=11)
+    n_rounds, every = 7, 2
+    runs = []
+    for prof in (0, every):
+        ctx = _context(t, d, h, k_max=8, max_seq=256)
+        try:
+            ctx.sd_prefill(0, prompt)
+            ctx.sd_profile_enable(prof)
+            ctx.sd_profile_read()
+            out = []
+            for _ in range(n_rounds):
+                out += [(r["K"], r["n"], tuple(r["tokens"])) for r in ctx.specdec_round(gp)]
+            stats = ctx.sd_profile_read()
+            again = ctx.sd_profile_read()
+            runs.append((out, stats, again))
+        finally:
+            ctx.close()
+    (out0, st0, _), (out1, st1, again1) = runs
+    assert out0 == out1
+    assert all(v["launches"] == 0 for v in st0.values())
+    assert all(v["launches"] == 0 and v["seconds"] == 0 for v in again1.values())      # a read empties the sums
+    # two target layers, every = 2: pass p samples layer l with (l + p) % 2 == 0, i.e. exactly one layer per pass
+    dm, nq, nkv, ffn, V = 512, 8 * 64, 1 * 64, 640, 2048          # the target of _bf16_pair()
+    per = {"qkv": (nq + 2 * nkv) * dm, "o": dm * nq, "gate_up": 2 * ffn * dm, "down": dm * ffn, "lm_head": V * dm}
+    for k, v in st1.items():
+        assert v["launches"] == n_rounds, (k, v)
+        assert v["weight_bytes"] == n_rounds * per[k] * 2
+        assert 0 < v["seconds"] < 1.0
