@@ -116,6 +116,30 @@ def attention(q: np.ndarray, k: np.ndarray, v: np.ndarray, q_pos: np.ndarray) ->
     return out.reshape(tq, hq * hd)
 
 
+def decoder_layer(w: ModelWeights, lw: LayerWeights, x: np.ndarray) -> np.ndarray:
+    """One decoder layer over a whole sequence with no cache: x [T, d] holds the residual
+    stream of positions 0..T-1 and the result is the residual stream after the layer."""
+    t = x.shape[0]
+    pos = np.arange(t)
+    hq, hkv, hd = w.n_heads, w.n_kv_heads, w.head_dim
+    a = rmsnorm(x, lw.norm_attn, w.rms_eps)
+    q = (a @ _f64(lw.wq).T).reshape(t, hq, hd)
+    k = (a @ _f64(lw.wk).T).reshape(t, hkv, hd)
+    v = (a @ _f64(lw.wv).T).reshape(t, hkv, hd)
+    q = rope(q, pos, w.rope_theta)
+    k = rope(k, pos, w.rope_theta)
+    o = attention(q, k, v, pos)
+    x = x + o @ _f64(lw.wo).T
+    m = rmsnorm(x, lw.norm_mlp, w.rms_eps)
+    return x + (silu(m @ _f64(lw.w_gate).T) * (m @ _f64(lw.w_up).T)) @ _f64(lw.w_down).T
+
+
+def final_logits(w: ModelWeights, x: np.ndarray) -> tuple[np.ndarray, np.ndarray]:
+    """(logits, e) of the residual rows x: e = final RMSNorm, logits = e W_lm^T."""
+    e = rmsnorm(x, w.final_norm, w.rms_eps)
+    return e @ _f64(w.lm_head).T, e
+
+
 def forward_full(w: ModelWeights, tokens) -> tuple[np.ndarray, np.ndarray]:
     """Forward over the whole sequence with no cache.
 
@@ -123,23 +147,10 @@ def forward_full(w: ModelWeights, tokens) -> tuple[np.ndarray, np.ndarray]:
     tokens[0..t].
     """
     tokens = np.asarray(tokens, dtype=np.int64)
-    t = tokens.shape[0]
-    pos = np.arange(t)
-    hq, hkv, hd = w.n_heads, w.n_kv_heads, w.head_dim
     x = _f64(w.tok_emb)[tokens]
     for lw in w.layers:
-        a = rmsnorm(x, lw.norm_attn, w.rms_eps)
-        q = (a @ _f64(lw.wq).T).reshape(t, hq, hd)
-        k = (a @ _f64(lw.wk).T).reshape(t, hkv, hd)
-        v = (a @ _f64(lw.wv).T).reshape(t, hkv, hd)
-        q = rope(q, pos, w.rope_theta)
-        k = rope(k, pos, w.rope_theta)
-        o = attention(q, k, v, pos)
-        x = x + o @ _f64(lw.wo).T
-        m = rmsnorm(x, lw.norm_mlp, w.rms_eps)
-        x = x + (silu(m @ _f64(lw.w_gate).T) * (m @ _f64(lw.w_up).T)) @ _f64(lw.w_down).T
-    e = rmsnorm(x, w.final_norm, w.rms_eps)
-    return e @ _f64(w.lm_head).T, e
+        x = decoder_layer(w, lw, x)
+    return final_logits(w, x)
 
 
 class CachedForward:

@@ -159,14 +159,18 @@ hipError_t launch_sample_stop(hipStream_t st, int dtype, const SeqState& s, cons
 // is live when j <= K[b]) and the draft logits [B, Kmax, V] (live when j < K[b]), in one launch:
 // stats[row] = {max, sum exp((l-max)/T), argmax, top-k threshold}.  With top_k > 0 only logits >=
 // the row's k-th largest enter the sum and the threshold is that value (else -inf).
+// K[b] outside [0, Kmax] is clamped, a candidate id outside [0, V) counts as rejected; `bad` (device int32,
+// may be null) is set to 0 by launch_row_stats and gets bit 0 (a clamped K) / bit 1 (a candidate id out of
+// range) from launch_accept, which must follow it on the same stream.
 hipError_t launch_row_stats(hipStream_t st, const float* p_logits, const float* q_logits, int Kmax,
                             const int32_t* K, int B, int V, float temperature, int top_k, float* p_stats,
-                            float* q_stats, int32_t* err);
+                            float* q_stats, int32_t* err, int32_t* bad = nullptr);
 // accept tests, n, and the residual / bonus sample y' for every sequence
 hipError_t launch_accept(hipStream_t st, const float* p_logits, const float* q_logits, const float* p_stats,
                          const float* q_stats, const int32_t* cand, int cand_ld, const int32_t* K,
                          const int32_t* round, int round_const, const DecodeParams& p, int B, int Kmax,
-                         int V, int32_t* n_out, int32_t* tok_out, uint8_t* flags, int flags_ld);
+                         int V, int32_t* n_out, int32_t* tok_out, uint8_t* flags, int flags_ld,
+                         int32_t* bad = nullptr);
 // training targets of the acceptance head (Sec. 4.4): for row i of p / q [n, V], Y_i ~ q_i with the
 // uniform of (slot0 + i, example, 0, stream 3) and P_i = min(1, p_i(Y_i) / q_i(Y_i))
 hipError_t launch_labels(hipStream_t st, const float* p_logits, const float* q_logits, int n, int V,

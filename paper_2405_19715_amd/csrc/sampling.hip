@@ -383,14 +383,16 @@ __global__ __launch_bounds__(SB) void sample_stop_k(SeqState s, const float* __r
 struct RowSet { const float* logits; float* stats; int rows, extra; };
 
 __global__ __launch_bounds__(SB) void row_stats_k(RowSet A, RowSet Bq, const int32_t* __restrict__ K, int V, float inv_t,
-                                                  int top_k, int32_t* __restrict__ err) {
+                                                  int top_k, int32_t* __restrict__ err, int32_t* __restrict__ oob) {
   __shared__ float sh_w[SB / 64];
   __shared__ int sh_i[SB / 64];
   const int b = blockIdx.y;
   const bool first = (int)blockIdx.x < A.rows;
   const RowSet& R = first ? A : Bq;
   const int j = first ? blockIdx.x : blockIdx.x - A.rows;
-  if (j >= K[b] + R.extra) return;
+  // the caller's "inputs out of range" word starts every call at 0; accept_k, next on the stream, sets its bits
+  if (oob && blockIdx.x == 0 && b == 0 && threadIdx.x == 0) *oob = 0;
+  if (j >= min(K[b], Bq.rows) + R.extra) return;       // K_b beyond Kmax counts as Kmax (accept_k reports it)
   const size_t row = (size_t)b * R.rows + j;
   const float* l = R.logits + row * V;
   const bool warp = top_k > 0 && top_k < V;
@@ -539,12 +541,16 @@ __global__ __launch_bounds__(SB) void accept_k(const float* __restrict__ p_logit
                                                const int32_t* __restrict__ Karr, const int32_t* __restrict__ round_arr,
                                                int round_const, DecodeParams p, int Kmax, int V,
                                                int32_t* __restrict__ n_out, int32_t* __restrict__ tok_out,
-                                               uint8_t* __restrict__ flags, int flags_ld) {
+                                               uint8_t* __restrict__ flags, int flags_ld, int32_t* __restrict__ oob) {
   __shared__ float sh_w[SB / 64];
   __shared__ int sh_res;
   __shared__ int sh_n;
   const int b = blockIdx.x;
-  const int K = Karr[b];
+  // K_b and the candidate ids come from the caller (isolated entry point): a count outside [0, Kmax] is clamped
+  // and a candidate id outside [0, V) counts as rejected, so that no index below leaves its array; `oob` (may
+  // be null) gets bit 0 / bit 1 when that happened
+  const int K = min(max(Karr[b], 0), Kmax);
+  if (oob && threadIdx.x == 0 && K != Karr[b]) atomicOr(oob, 1);
   const int rnd = round_arr ? round_arr[b] : round_const;
   const float inv_t = 1.0f / p.temperature;
   const float* pl = p_logits + (size_t)b * (Kmax + 1) * V;
@@ -558,7 +564,9 @@ __global__ __launch_bounds__(SB) void accept_k(const float* __restrict__ p_logit
     uint8_t ok = 0;
     if (i <= K) {
       const int y = cand[b * cand_ld + i - 1];
-      if (p.greedy) {
+      if (y < 0 || y >= V) {
+        if (oob) atomicOr(oob, 2);
+      } else if (p.greedy) {
         ok = (y == __float_as_int(ps[(i - 1) * 4 + 2])) ? 1 : 0;
       } else {
         const float lp = pl[(size_t)(i - 1) * V + y], lq = ql[(size_t)(i - 1) * V + y];
@@ -689,12 +697,14 @@ hipError_t launch_sample_stop(hipStream_t st, int dtype, const SeqState& s, cons
 }
 
 hipError_t launch_row_stats(hipStream_t st, const float* p_logits, const float* q_logits, int Kmax, const int32_t* K,
-                            int B, int V, float temperature, int top_k, float* p_stats, float* q_stats, int32_t* err) {
+                            int B, int V, float temperature, int top_k, float* p_stats, float* q_stats, int32_t* err,
+                            int32_t* bad) {
   if (B < 1 || Kmax < 1 || V < 1 || top_k < 0 || !p_logits || !q_logits || !K || !p_stats || !q_stats ||
       !(temperature > 0.f))
     return hipErrorInvalidValue;
   const RowSet A{p_logits, p_stats, Kmax + 1, 1}, Bq{q_logits, q_stats, Kmax, 0};
-  hipLaunchKernelGGL(row_stats_k, dim3(2 * Kmax + 1, B), dim3(SB), 0, st, A, Bq, K, V, 1.0f / temperature, top_k, err);
+  hipLaunchKernelGGL(row_stats_k, dim3(2 * Kmax + 1, B), dim3(SB), 0, st, A, Bq, K, V, 1.0f / temperature, top_k, err,
+                     bad);
   return hipGetLastError();
 }
 
@@ -717,12 +727,12 @@ hipError_t launch_mix(hipStream_t st, const int32_t* X, const int32_t* Y, int n,
 hipError_t launch_accept(hipStream_t st, const float* p_logits, const float* q_logits, const float* p_stats,
                          const float* q_stats, const int32_t* cand, int cand_ld, const int32_t* K,
                          const int32_t* round, int round_const, const DecodeParams& p, int B, int Kmax, int V,
-                         int32_t* n_out, int32_t* tok_out, uint8_t* flags, int flags_ld) {
+                         int32_t* n_out, int32_t* tok_out, uint8_t* flags, int flags_ld, int32_t* bad) {
   if (B < 1 || Kmax < 1 || Kmax > CAND_LD || V < 1 || cand_ld < Kmax || flags_ld < Kmax || !p_logits || !q_logits ||
       !p_stats || !q_stats || !cand || !K || !n_out || !tok_out || !flags || !(p.temperature > 0.f))
     return hipErrorInvalidValue;
   hipLaunchKernelGGL(accept_k, dim3(B), dim3(SB), 0, st, p_logits, q_logits, p_stats, q_stats, cand, cand_ld, K, round,
-                     round_const, p, Kmax, V, n_out, tok_out, flags, flags_ld);
+                     round_const, p, Kmax, V, n_out, tok_out, flags, flags_ld, bad);
   return hipGetLastError();
 }
 

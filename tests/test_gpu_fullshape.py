@@ -5,8 +5,6 @@ GEMM, attention and sampling launch has the grid bench.py times) but only 2 laye
 each, so that the oracle can recompute sampled rows in fp64 within seconds; and the pair at
 full depth, where the oracle recomputes every decision from the HIP path's rows and the rows
 are checked for independence of the launch shape."""
-import os
-
 import numpy as np
 import pytest
 import torch
@@ -222,31 +220,83 @@ def test_full_depth_pair_rounds_decisions_and_launch_shape_invariance():
         ref.close()
 
 
-_SLOW = pytest.mark.skipif(not os.environ.get("SD_RUN_SLOW"),
-                           reason="about 3 minutes of fp64 host work: set SD_RUN_SLOW=1 (and -s to see its progress)")
-
-
-@pytest.mark.parametrize("n_layers", [2, pytest.param(80, marks=_SLOW)])
-def test_target_logits_against_the_streamed_fp64_oracle(n_layers):
-    """The 70B-shaped target against the fp64 oracle with the oracle streaming one layer of weights
-    at a time from the device: 24 prompt tokens through the prompt pass, 6 teacher-forced rows.
-    At 2 layers the bf16 bound (2e-2) applies; at 80 layers the five bf16 roundings per layer
-    have added up (measured 13.5 %, argmax agreement 43 % on random-init logits), so the bound
-    there only separates rounding noise from a wrong row, position or cache entry (error ~ 1)."""
+def test_target_logits_at_depth_against_fp64_and_bf16_rounded_oracle(capsys):
+    """The 70B-shaped target at 2, 8, 24 and all 80 layers against three forwards of the oracle's
+    functions, all streaming one layer of weights at a time from the device:
+      fp64      the definition (oracle.model.decoder_layer);
+      rounded   the same in fp64 with the activations rounded to bf16 at the points where a bf16 model
+                stores them (tests/_bf16_rounding.py: RMSNorm outputs, q / k / v, softmax weights of the
+                value product, attention output, SiLU * up);
+      rounded32 `rounded` once more with every intermediate held in fp32 and numpy's fp32 products: a
+                second plain implementation of the same roundings.
+    24 prompt tokens go through the prompt pass, 7 teacher-forced rows through one launch of the
+    round's kernels.  What the figures say (errors are row-wise max-norm, as everywhere):
+      * at 2 layers the HIP path is within the bf16 tolerance (2e-2) of the definition itself;
+      * deeper, its distance from the definition is the distance of `rounded` from the definition
+        (about 1.5 % / 3 % / 6 % / 14 % at 2 / 8 / 24 / 80 layers, growing like the square root of the
+        depth): storing activations in bf16 costs that much on random-init layers, whoever computes;
+      * what separates it from `rounded` is not the bf16 tolerance either beyond about 8 layers,
+        and that is not the kernels: `rounded32`, which shares every rounding point with `rounded`
+        and differs in nothing but fp32 arithmetic, lands as far from `rounded` as the HIP path does
+        (a value one fp32 ulp away before a bf16 rounding can take the other neighbour; a random-init
+        layer amplifies such a flip about tenfold).  So the bound at depth is relative: the HIP path
+        may be no further from `rounded` than 1.5 x a plain fp32 implementation of the same roundings
+        is, and no further from the definition than 1.5 x `rounded` is."""
     from dataclasses import replace
-    from oracle.model import forward_full
+    from oracle.model import decoder_layer, final_logits
     from paper_2405_19715_amd import binding as B
+    from tests._bf16_rounding import RoundedDecoder
+    from tests._util import StreamedLayers
     dev = "cuda:0"
-    t = synth.make_model(replace(synth.LLAMA_70B, n_layers=n_layers), 1, device=dev, dtype=torch.bfloat16)
+    depths = (2, 8, 24, 80)
+    t = synth.make_model(synth.LLAMA_70B, 1, device=dev, dtype=torch.bfloat16)
     d = synth.make_model(replace(synth.LLAMA_7B, n_layers=1), 2, device=dev, dtype=torch.bfloat16)
     n, tail = 24, 6
     toks = synth.make_prompt(n + tail, 32000, 6)
-    ctx = B.Context(t, d, None, batch=1, max_seq=64, k_max=8)
-    try:
-        ctx.sd_prefill(0, toks[:n])
-        got = ctx.sd_forward(0, 0, n - 1, toks[n - 1:]).numpy()
-    finally:
-        ctx.close()
-    want = forward_full(oracle_model_streamed(t), toks)[0][n - 1:]
-    err = (np.abs(got - want).max(-1) / np.abs(want).max(-1)).max()
-    assert err < (2e-2 if n_layers == 2 else 0.25), err
+    sh = t["shape"]
+    got = {}
+    for L in depths:                     # the first L layers of the same model, its LM head and final norm
+        sub = dict(t, shape=replace(sh, n_layers=L), layers=t["layers"][:L])
+        ctx = B.Context(sub, d, None, batch=1, max_seq=64, k_max=8)
+        try:
+            ctx.sd_prefill(0, toks[:n])
+            got[L] = ctx.sd_forward(0, 0, n - 1, toks[n - 1:]).numpy().astype(np.float64)
+        finally:
+            ctx.close()
+    # launch modes of the two chunks: the 23 prompt rows take the unfused kernels (row factor applied
+    # before the product), the 7 rows the fused ones where the library says it fuses that row count
+    fused_tail = bool(B.lib.sd_mlp_act_is_fused(B.SD_BF16, tail + 1, sh.d_ffn, sh.d_model))
+
+    def progress(i, total):
+        if i % 8 == 0:
+            with capsys.disabled():
+                print(f"[depth oracle] layer {i} of {total}", flush=True)
+
+    w = oracle_model_streamed(t, progress)
+    x64 = np.asarray(w.tok_emb)[np.asarray(toks)]
+    chunks = ((n - 1, tail + 1), (False, fused_tail), (False, False))
+    dec = RoundedDecoder(w, toks, *chunks)
+    dec32 = RoundedDecoder(w, toks, *chunks, dtype=np.float32)
+    rel = lambda a, b: float((np.abs(a - b).max(-1) / np.abs(b).max(-1)).max())
+    same = lambda a, b: float((a.argmax(-1) == b.argmax(-1)).mean())
+    table = []
+    for i, (lw, lw32) in enumerate(zip(w.layers, StreamedLayers(t, dtype=torch.float32))):
+        x64 = decoder_layer(w, lw, x64)
+        dec.layer(lw)
+        dec32.layer(lw32)
+        L = i + 1
+        if L in depths:
+            fp64, rnd, rnd32 = final_logits(w, x64)[0][n - 1:], dec.logits(), dec32.logits()
+            table.append(dict(L=L, hip_rnd=rel(got[L], rnd), r32_rnd=rel(rnd32, rnd), hip_fp64=rel(got[L], fp64),
+                              rnd_fp64=rel(rnd, fp64), am_rnd=same(got[L], rnd), am_fp64=same(got[L], fp64)))
+    with capsys.disabled():
+        print("\nlayers  HIP-vs-rounded  rounded32-vs-rounded  HIP-vs-fp64  rounded-vs-fp64  argmax=rounded  argmax=fp64")
+        for r in table:
+            print("%5d   %.5f         %.5f               %.5f      %.5f          %.2f            %.2f"
+                  % (r["L"], r["hip_rnd"], r["r32_rnd"], r["hip_fp64"], r["rnd_fp64"], r["am_rnd"], r["am_fp64"]), flush=True)
+    assert [r["L"] for r in table] == list(depths)
+    assert table[0]["hip_fp64"] < 2e-2 and table[0]["hip_rnd"] < 2e-2, table[0]
+    for r in table:
+        assert r["hip_rnd"] < 1.5 * r["r32_rnd"] + 1e-3, r
+        assert r["hip_fp64"] < 1.5 * r["rnd_fp64"] + 1e-3, r
+        assert r["hip_fp64"] < 0.25, r
