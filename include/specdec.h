@@ -16,11 +16,11 @@
  *   - Every function returns an sd_status; 0 is success, negative is an error.
  *     Nothing throws or aborts.  Host out-parameters are written only on SD_OK.
  *     On an error the sequences' committed state (tokens, lengths) is unchanged.
- *   - Calls on one context must not overlap.  The library keeps a little per-process
- *     state that is set on a kernel's first launch (the permission to use more than
- *     64 KB of LDS): make the first calls from one thread, and use one GPU per
- *     process (the device that is current when sd_create runs must be current in
- *     every later call on that context).
+ *   - Calls on one context must not overlap; calls on different contexts may come
+ *     from different threads.  Use one GPU per process (the device that is current
+ *     when sd_create runs must be current in every later call on that context; the
+ *     permission to use more than 64 KB of LDS is set once per process, by a
+ *     kernel's first launch).
  */
 #ifndef SPECDEC_H
 #define SPECDEC_H
@@ -160,8 +160,16 @@ sd_status specdec_generate(sd_ctx *ctx, const sd_params *params, int32_t max_new
  * p_logits_dev: DEVICE fp32 [B, Kmax+1, V]; q_logits_dev: DEVICE fp32 [B, Kmax, V];
  * cand_dev: DEVICE int32 [B, Kmax]; K_per_seq_dev: DEVICE int32 [B];
  * outputs DEVICE int32 [B], int32 [B], uint8 [B, Kmax].  `stats_ws_dev` is DEVICE
- * scratch of sd_accept_workspace_bytes(B, Kmax) bytes.  Enqueued on `hip_stream`;
- * does not synchronise. */
+ * scratch of sd_accept_workspace_bytes(B, Kmax) bytes, 16-byte aligned.  Enqueued on
+ * `hip_stream`; does not synchronise.
+ * The device arrays are the caller's and cannot be checked on the host without a
+ * synchronisation, so the kernels make them safe instead: a K_b outside [0, Kmax]
+ * is clamped into it, and a candidate id outside [0, V) counts as rejected (its flag
+ * is 0, n_out stops before it, y' is the residual sample of that position).  The
+ * int32 at byte offset B * (2 * Kmax + 1) * 16 of the workspace is the call's status
+ * word: 0 when every input was in range, bit 0 set when a K_b was clamped, bit 1 when
+ * a candidate id was out of range (valid once the stream has reached the end of the
+ * call). */
 sd_status sd_accept_resample(const float *p_logits_dev, const float *q_logits_dev,
                              const int32_t *cand_dev, const int32_t *K_per_seq_dev,
                              int32_t B, int32_t Kmax, int32_t V, const sd_params *params,

@@ -26,7 +26,9 @@ p_hat at i = 1 because e_0 is never computed.
 
 Pins: greedy generation equals target-only greedy decoding token for token
 (Sec. 4.1); N_draft + N_target = N + N_discarded (Sec. 3.2); h >= 1 gives the
-fixed-K algorithm; full-recompute and cached forwards give the same rounds.
+fixed-K algorithm; full-recompute and cached forwards give the same rounds; the
+hindsight policy of Theorem 1 played through the rounds discards nothing and is
+optimal among all stopping policies (brute force over every policy on tiny inputs).
 """
 from __future__ import annotations
 
@@ -103,7 +105,11 @@ def oracle_round(target, draft, head: Optional[HeadWeights], x: List[int], rho: 
     Returns dict(K, n, cand, tokens (= y_1..y_n, y'), q_logits, p_logits, s (head
     outputs used), p_hat, trace) where trace lists every decision with its margin
     so a parity harness can tell a near-tie from an error.  `forced` maps
-    ("draft", i) / ("stop", i) / ("accept", i) / "token" to a decision to impose.
+    ("draft", i) / ("stop", i) / ("accept", i) / "token" to a decision to impose;
+    forced["K"] = k makes the round draw exactly k candidates whatever the stop rule
+    says (0 <= k <= K_cap; k = 0 is a plain target step: Algorithm 1's tail with no
+    candidate, y' ~ p_1), which is how a stopping policy other than the head's is
+    played, e.g. the hindsight policy of Sec. 4.1.
     """
     forced = forced or {}
     P = len(x)
@@ -115,7 +121,12 @@ def oracle_round(target, draft, head: Optional[HeadWeights], x: List[int], rho: 
     q_rows = []
     s_used = []
     p_hat = 1.0
+    k_forced = forced.get("K")
+    if k_forced is not None and not 0 <= k_forced <= k_cap:
+        raise ValueError("forced K outside [0, K_cap]")
     for i in range(1, k_cap + 1):
+        if k_forced is not None and i > k_forced:
+            break
         logits, hid = draft.tail(x + cand, 1)
         q_rows.append(logits[0])
         if params.greedy:
@@ -135,13 +146,16 @@ def oracle_round(target, draft, head: Optional[HeadWeights], x: List[int], rho: 
         stop = should_stop(p_hat, params.h)
         trace.append(("stop", i, int(stop), abs(1.0 - p_hat - params.h)))
         stop = bool(forced.get(("stop", i), stop))
+        if k_forced is not None:
+            continue                                     # the imposed count decides, not the rule
         if stop:
             break
         if params.eos_id >= 0 and y == params.eos_id:
             break
     K = len(cand)
     p_logits, _ = target.tail(x + cand, K + 1)
-    res = accept_resample(p_logits, np.stack(q_rows), cand, K, temperature=params.temperature,
+    q_logits = np.stack(q_rows) if q_rows else np.zeros((0, p_logits.shape[-1]))
+    res = accept_resample(p_logits, q_logits, cand, K, temperature=params.temperature,
                           greedy=params.greedy, seed=params.seed, rnd=rho, seq=seq, forced=forced,
                           top_k=params.top_k)
     for i in range(1, K + 1):
@@ -149,7 +163,7 @@ def oracle_round(target, draft, head: Optional[HeadWeights], x: List[int], rho: 
                       res["ratio"][i - 1] if params.greedy else abs(res["r"][i - 1] - res["ratio"][i - 1])))
     trace.append(("token", res["n"] + 1, res["token"], res["margin"]))
     n = res["n"]
-    return dict(K=K, n=n, cand=cand, tokens=cand[:n] + [res["token"]], q_logits=np.stack(q_rows),
+    return dict(K=K, n=n, cand=cand, tokens=cand[:n] + [res["token"]], q_logits=q_logits,
                 p_logits=p_logits, s=s_used, p_hat=p_hat, flags=res["flags"], trace=trace)
 
 
@@ -203,3 +217,34 @@ def target_greedy_generate(target_w: ModelWeights, prompt, max_new: int, eos_id:
         if eos_id >= 0 and t == eos_id:
             break
     return out
+
+
+def hindsight_counts(target_w: ModelWeights, draft_w: ModelWeights, prompt, N: int) -> dict:
+    """The hindsight-optimal stopping policy of greedy speculative decoding (Sec. 4.1, Theorem 1).
+
+    X_1..X_N are the target's own greedy tokens; Y_i = argmax q(. | prompt, X_1..X_{i-1}) is the
+    draft's greedy token given the target's partial generation; S = {i : Y_i != X_i}.  Stopping
+    right before every i in S discards nothing and calls the target once per element of S (that
+    call emits X_i) plus once for the tokens behind the last disagreement.
+
+    Returns dict(X, Y, S (1-based), plan, N_draft, N_target, N_discarded = 0), where plan[r] is the
+    number of candidates the policy drafts in round r (0 when two disagreements are adjacent: the
+    target simply takes a step).  N_target is the theorem's |S| + 1, except that when X_N itself is
+    a disagreement nothing is left for a last round and the count is |S|.
+    """
+    prompt = [int(t) for t in prompt]
+    X = target_greedy_generate(target_w, prompt, N)
+    # row P-1+j of the draft's forward over (prompt, X_1..X_{N-1}) is conditioned on prompt, X_1..X_j
+    logits, _ = forward_full(draft_w, prompt + X[:-1])
+    P = len(prompt)
+    Y = [argmax_lowest(logits[P - 1 + j]) for j in range(N)]
+    S = [i for i in range(1, N + 1) if Y[i - 1] != X[i - 1]]
+    plan, pos = [], 0                    # pos = tokens emitted so far
+    for i in S + ([] if S and S[-1] == N else [N + 1]):
+        # candidates Y_{pos+1}..Y_{i-1} all agree; the target's call emits X_i (or, in the last
+        # round, the bonus token X_N after N - pos - 1 accepted candidates)
+        k = min(i, N) - pos - 1
+        plan.append(k)
+        pos += k + 1
+    assert pos == N
+    return dict(X=X, Y=Y, S=S, plan=plan, N_draft=sum(plan), N_target=len(plan), N_discarded=0)

@@ -264,7 +264,8 @@ def sd_accept_resample(p_logits: torch.Tensor, q_logits: torch.Tensor, cand: tor
     """p_logits [B, Kmax+1, V] fp32, q_logits [B, Kmax, V] fp32, cand [B, Kmax] int32,
     K_per_seq [B] int32, all CUDA.  Returns (n [B], token [B], flags [B, Kmax]) CUDA tensors;
     enqueued on the current stream, not synchronised.  `out` may carry preallocated
-    (n, token, flags, workspace) tensors."""
+    (n, token, flags, workspace) tensors; the call's status word (see the header) is
+    workspace[B * (2 * Kmax + 1) * 16:][:4] as int32."""
     B, Kp1, V = p_logits.shape
     Kmax = Kp1 - 1
     assert q_logits.shape == (B, Kmax, V) and cand.shape == (B, Kmax) and K_per_seq.shape == (B,)

@@ -27,8 +27,6 @@
 #include "common.hpp"
 #include "kernels.hpp"
 
-#include <cstdlib>
-
 namespace sd {
 
 namespace {
@@ -269,9 +267,9 @@ __global__ __launch_bounds__(HD) void attn_merge_k(const float* __restrict__ scr
   *dst = f2bf(den > 0.f ? num / den : 0.f);
 }
 
-// ------------------------------------------------------------------ plain kernel (any dtype)
+// ------------------------------------------------------------------ plain kernel (fp32 models)
 // One workgroup per (query head, row group); rows one after another; scores of the
-// whole prefix in LDS.  Used for fp32 models, where sizes are tiny.
+// whole prefix in LDS.  Sizes are tiny there.
 template <typename T>
 __global__ __launch_bounds__(256) void attn_plain_k(const T* __restrict__ qbuf, const T* __restrict__ kcache,
                                                     const T* __restrict__ vcache, const int32_t* __restrict__ row_seq,
@@ -342,10 +340,7 @@ MfmaShape mfma_shape(int RS, int G) {
   return s;
 }
 
-bool use_plain(int dtype) {
-  static const bool forced = std::getenv("SD_ATTN_PLAIN") != nullptr;
-  return dtype == DT_F32 || forced;
-}
+bool use_plain(int dtype) { return dtype == DT_F32; }
 
 }  // namespace
 
@@ -362,20 +357,15 @@ hipError_t launch_attention(hipStream_t st, int dtype, const void* qbuf, const v
     return hipErrorInvalidValue;
   const int ngroups = M / RS;
   if (use_plain(dtype)) {
+    if (full) return hipErrorInvalidValue;
     if (hd != 32 && hd != 64 && hd != 128) return hipErrorInvalidValue;
     const size_t lds = ((size_t)max_seq + hd + 256) * sizeof(float);
     if (lds > 64 * 1024) return hipErrorInvalidValue;
-    if (dtype == DT_F32)
-      hipLaunchKernelGGL(attn_plain_k<float>, dim3(Hq, ngroups), dim3(256), lds, st, (const float*)qbuf,
-                         (const float*)kcache, (const float*)vcache, rows.seq, rows.pos, (float*)out, RS, Hq, Hkv, hd,
-                         max_seq);
-    else
-      hipLaunchKernelGGL(attn_plain_k<bf16_t>, dim3(Hq, ngroups), dim3(256), lds, st, (const bf16_t*)qbuf,
-                         (const bf16_t*)kcache, (const bf16_t*)vcache, rows.seq, rows.pos, (bf16_t*)out, RS, Hq, Hkv,
-                         hd, max_seq);
+    hipLaunchKernelGGL(attn_plain_k<float>, dim3(Hq, ngroups), dim3(256), lds, st, (const float*)qbuf,
+                       (const float*)kcache, (const float*)vcache, rows.seq, rows.pos, (float*)out, RS, Hq, Hkv, hd,
+                       max_seq);
     return hipGetLastError();
   }
-  if (full && use_plain(dtype)) return hipErrorInvalidValue;
   if (dtype != DT_BF16 || (hd != 64 && hd != 128) || max_seq % KB != 0 || max_seq > 512 * KB || (!scratch && !full))
     return hipErrorInvalidValue;
   const MfmaShape sh = mfma_shape(RS, Hq / Hkv);

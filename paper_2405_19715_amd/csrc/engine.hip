@@ -10,6 +10,7 @@
 #include <cmath>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -756,20 +757,29 @@ int64_t sd_accept_workspace_bytes(int32_t B, int32_t Kmax) {
   return (int64_t)B * (2 * Kmax + 1) * 16 + 16;
 }
 
+static sd_status accept_resample_on(const float* p_logits, const float* q_logits, const int32_t* cand,
+                                    const int32_t* K, int32_t B, int32_t Kmax, int32_t V, const sd_params* params,
+                                    int32_t round_idx, void* ws, hipStream_t st, int32_t* n_out, int32_t* tok_out,
+                                    uint8_t* flags) {
+  const DecodeParams dp = to_dp(params);
+  float* p_stats = (float*)ws;
+  float* q_stats = p_stats + (size_t)B * (Kmax + 1) * 4;
+  int32_t* oob = (int32_t*)(p_stats + (size_t)B * (2 * Kmax + 1) * 4);      // the status word behind the statistics
+  SD_HIP(launch_row_stats(st, p_logits, q_logits, Kmax, K, B, V, dp.temperature, dp.top_k, p_stats, q_stats, nullptr, oob));
+  SD_HIP(launch_accept(st, p_logits, q_logits, p_stats, q_stats, cand, Kmax, K, nullptr, round_idx, dp, B, Kmax, V,
+                       n_out, tok_out, flags, Kmax, oob));
+  return SD_OK;
+}
+
 sd_status sd_accept_resample(const float* p_logits, const float* q_logits, const int32_t* cand, const int32_t* K,
                              int32_t B, int32_t Kmax, int32_t V, const sd_params* params, int32_t round_idx,
                              void* ws, void* hip_stream, int32_t* n_out, int32_t* tok_out, uint8_t* flags) {
   if (!p_logits || !q_logits || !cand || !K || !ws || !n_out || !tok_out || !flags || !params_ok(params))
     return SD_EINVAL;
   if (B < 1 || Kmax < 1 || Kmax > SD_MAX_K || V < 1) return SD_EINVAL;
-  hipStream_t st = (hipStream_t)hip_stream;
-  const DecodeParams dp = to_dp(params);
-  float* p_stats = (float*)ws;
-  float* q_stats = p_stats + (size_t)B * (Kmax + 1) * 4;
-  SD_HIP(launch_row_stats(st, p_logits, q_logits, Kmax, K, B, V, dp.temperature, dp.top_k, p_stats, q_stats, nullptr));
-  SD_HIP(launch_accept(st, p_logits, q_logits, p_stats, q_stats, cand, Kmax, K, nullptr, round_idx, dp, B, Kmax, V,
-                       n_out, tok_out, flags, Kmax));
-  return SD_OK;
+  if (reinterpret_cast<uintptr_t>(ws) & 15) return SD_EINVAL;
+  return accept_resample_on(p_logits, q_logits, cand, K, B, Kmax, V, params, round_idx, ws, (hipStream_t)hip_stream,
+                            n_out, tok_out, flags);
 }
 
 sd_status sd_forward(sd_ctx* c, int32_t which, int32_t seq, int32_t start, const int32_t* tokens, int32_t n,

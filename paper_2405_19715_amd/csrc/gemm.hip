@@ -42,6 +42,7 @@
 #include "kernels.hpp"
 
 #include <cstdlib>
+#include <mutex>
 #include <vector>
 
 namespace sd {
@@ -439,8 +440,9 @@ struct StripeEpi {
   int Hq, Hkv, hshift, max_seq;
 };
 
-// RAGGED: K is not a multiple of 2048; a lane of the last stripe whose piece lies beyond K reads piece 0 of the
-// stripe again (a fixed per-lane offset: nothing changes in the loop) against zeros in X.
+// RAGGED: K is not a multiple of 2048; a lane of the last stripe whose piece lies beyond K reads the first 16 bytes
+// of the stripe instead (lane 0's piece 0, which every stripe has: a fixed per-lane offset, nothing changes in the
+// loop) against zeros in X.
 template <int MM, int EPI, bool RAGGED>
 __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_stripe(const bf16_t* __restrict__ W,
                                                                  const bf16_t* __restrict__ X, int ldx,
@@ -511,7 +513,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_stripe(const bf16_t* _
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       live[j] = !RAGGED || c * RSTEP + j * PIECE + lane * 8 < K;
-      off[j] = live[j] ? j * PIECE : 0;
+      off[j] = live[j] ? j * PIECE : -lane * 8;        // dead: the stripe's first 16 bytes (k = c * RSTEP < K)
     }
 
     // X first: its loads are then older than every weight load, and waiting for a weight step never waits for them
@@ -745,13 +747,14 @@ hipError_t launch_stream(hipStream_t st, const bf16_t* W, const bf16_t* X, int l
                          int N, int K, Split sp) {
   const dim3 grid(sp.G, sp.S);
   const size_t lds = (size_t)M * sp.steps_per * KSTEP * 2;
-  static bool attr_set = false;          // dynamic LDS above 64 KB has to be allowed once per kernel
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_bf16_stream<NT>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, LDS_MAX + 8 * 1024);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  // dynamic LDS above 64 KB has to be allowed once per kernel: the first caller does it, whichever thread that is
+  static std::once_flag once;
+  static hipError_t attr_err = hipSuccess;
+  std::call_once(once, [] {
+    attr_err = hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_bf16_stream<NT>),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, LDS_MAX + 8 * 1024);
+  });
+  if (attr_err != hipSuccess) return attr_err;
   hipLaunchKernelGGL(gemm_bf16_stream<NT>, grid, dim3(GEMM_THREADS), lds, st, W, X, ldx, xrow, part, M, N, K,
                      sp.steps_per, sp.G);
   return hipGetLastError();

@@ -31,6 +31,8 @@
 #include "common.hpp"
 #include "kernels.hpp"
 
+#include <mutex>
+
 namespace sd {
 
 namespace {
@@ -202,13 +204,15 @@ hipError_t launch_tile(hipStream_t st, const bf16_t* W, const bf16_t* X, int ldx
   constexpr int BN = 32 * TN * WN, BM = 32 * TM * WM;
   constexpr size_t lds = (size_t)NS * (BK / 8) * (BN + BM) * 16;
   auto kern = gemm_bf16_tile<TN, TM, WN, WM, BK, NS>;
-  static bool attr_set = false;          // dynamic LDS above 64 KB has to be allowed once per kernel
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  // dynamic LDS above 64 KB has to be allowed once per kernel (instantiation): the first caller does it, whichever
+  // thread that is
+  static std::once_flag once;
+  static hipError_t attr_err = hipSuccess;
+  std::call_once(once, [&] {
+    attr_err = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                   (int)lds);
+  });
+  if (attr_err != hipSuccess) return attr_err;
   const int n_tiles = (N + BN - 1) / BN, m_tiles = (M + BM - 1) / BM;
   const int n_tiles_pad = (n_tiles + NXCD - 1) / NXCD * NXCD;
   const int nk = K / BK, steps_per = (nk + S - 1) / S;

@@ -392,7 +392,7 @@ __global__ __launch_bounds__(SB) void row_stats_k(RowSet A, RowSet Bq, const int
   const int j = first ? blockIdx.x : blockIdx.x - A.rows;
   // the caller's "inputs out of range" word starts every call at 0; accept_k, next on the stream, sets its bits
   if (oob && blockIdx.x == 0 && b == 0 && threadIdx.x == 0) *oob = 0;
-  if (j >= min(K[b], Bq.rows) + R.extra) return;       // K_b beyond Kmax counts as Kmax (accept_k reports it)
+  if (j >= min(max(K[b], 0), Bq.rows) + R.extra) return;       // K_b is clamped into [0, Kmax] (accept_k reports it)
   const size_t row = (size_t)b * R.rows + j;
   const float* l = R.logits + row * V;
   const bool warp = top_k > 0 && top_k < V;

@@ -228,3 +228,47 @@ def test_sequences_without_candidates():
                 assert tok[b] == o["token"] or (not greedy and o["margin"] < CDF_TOL)
             elif (flags[b, : Ks[b]] == o["flags"]).all():
                 assert n[b] == o["n"] and (tok[b] == o["token"] or (not greedy and o["margin"] < CDF_TOL))
+
+
+def test_counts_and_ids_out_of_range_are_made_safe_and_reported():
+    """The isolated entry point cannot check the caller's device arrays on the host: a K_b outside
+    [0, Kmax] is clamped and a candidate id outside [0, V) counts as rejected, and the status word
+    behind the statistics says so.  Placed in the last sequence and the last slots, where an
+    unclamped index would leave the arrays."""
+    from paper_2405_19715_amd import binding as Bd
+    B, Kmax, V, seed = 3, 4, 32000, 23
+    p, q = synth.make_accept_logits(B, Kmax, V, seed)
+    good = np.stack([np.pad(_candidates(q[b], Kmax, seed, 0, b), (0, 0)) for b in range(B)]).astype(np.int32)
+
+    def run(Ks, cand):
+        ws = torch.zeros(Bd.lib.sd_accept_workspace_bytes(B, Kmax), dtype=torch.uint8, device="cuda")
+        out = (torch.empty(B, dtype=torch.int32, device="cuda"), torch.empty(B, dtype=torch.int32, device="cuda"),
+               torch.empty((B, Kmax), dtype=torch.uint8, device="cuda"), ws)
+        n, tok, flags = Bd.sd_accept_resample(p.cuda(), q.cuda(), torch.from_numpy(cand).cuda(),
+                                              torch.from_numpy(np.asarray(Ks, dtype=np.int32)).cuda(),
+                                              Bd.make_params(seed=seed), 0, out=out)
+        torch.cuda.synchronize()
+        word = int(ws[B * (2 * Kmax + 1) * 16:][:4].view(torch.int32).item())
+        return n.cpu().numpy(), tok.cpu().numpy(), flags.cpu().numpy(), word
+
+    base = run([Kmax] * B, good)
+    assert base[3] == 0
+    # counts: too large -> Kmax, negative -> 0 (same results as the clamped call, bit 0 set)
+    got = run([2, -5, 1000], good)
+    want = run([2, 0, Kmax], good)
+    assert got[3] == 1 and want[3] == 0
+    for a, b in zip(got[:3], want[:3]):
+        assert np.array_equal(a, b)
+    # ids: the bad candidate is rejected, everything before it is judged as usual
+    bad = good.copy()
+    bad[B - 1, Kmax - 1] = V + 7
+    bad[0, 1] = -1
+    n, tok, flags, word = run([Kmax] * B, bad)
+    assert word == 2
+    assert flags[B - 1, Kmax - 1] == 0 and flags[0, 1] == 0
+    assert n[0] <= 1 and n[B - 1] <= Kmax - 1
+    assert np.array_equal(flags[1], base[2][1]) and n[1] == base[0][1] and tok[1] == base[1][1]
+    assert (0 <= tok).all() and (tok < V).all()
+    for b in (0, B - 1):          # slots before the bad one are unchanged
+        stop = 1 if b == 0 else Kmax - 1
+        assert np.array_equal(flags[b, :stop], base[2][b, :stop])

@@ -194,6 +194,41 @@ def test_greedy_generate_equals_target_only_greedy_and_counters():
             ctx.close()
 
 
+def test_hindsight_disagreement_set_from_hip_greedy_tokens_matches_oracle():
+    """Sec. 4.1, Theorem 1 on the HIP path: X = the greedy tokens the rounds emit, Y_i = argmax of
+    the draft's teacher-forced row conditioned on (prompt, X_<i) (sd_forward on the draft), S where
+    they differ; S and the counts it implies must be the oracle's.  Any actual run calls the target
+    at least that often."""
+    from paper_2405_19715_amd import binding as B
+    t, d, h = tiny_pair(seed=3)
+    for perturb_seed, n_prompt, N, std in ((4, 20, 72, 0.002), (9, 33, 64, 0.003)):
+        # all of the target's layers plus a little noise: agrees with the target on part of the tokens
+        d = synth.make_perturbed_draft(t, 2, perturb_seed, std=std)
+        prompt = synth.make_prompt(n_prompt, 1024, perturb_seed)
+        hs = R.hindsight_counts(oracle_model(t), oracle_model(d), prompt, N)
+        assert 2 < len(hs["S"]) < N - 2 and max(hs["plan"]) >= 2, hs["S"]
+        ctx = _context(t, d, h, k_max=8, max_seq=192)
+        try:
+            ctx.sd_prefill(0, prompt)
+            seqs, st = ctx.specdec_generate(B.make_params(h=0.7, greedy=True), N)
+            X = seqs[0]
+            assert X == hs["X"]
+            # teacher-forced draft rows: feeding prompt[-1], X_1 .. X_{N-1} from cache position n_prompt - 1
+            ctx.sd_prefill(0, prompt)
+            fed = [prompt[-1]] + X[:-1]
+            Y = []
+            for s0 in range(0, N, 32):
+                rows = ctx.sd_forward(1, 0, n_prompt - 1 + s0, fed[s0:s0 + 32]).numpy()
+                Y += [int(np.argmax(r)) for r in rows]
+            S = [i + 1 for i in range(N) if Y[i] != X[i]]
+            assert S == hs["S"]
+            n_target = len(S) + (0 if S and S[-1] == N else 1)
+            assert n_target == hs["N_target"] and N - n_target == hs["N_draft"]
+            assert st["N_target"] >= n_target and st["N_discarded"] >= 0
+        finally:
+            ctx.close()
+
+
 def test_sampled_generate_matches_oracle_generate_and_resumes():
     """specdec_generate(N) equals the oracle's stream, and equals generate(N1) followed
     by generate(N - N1) when N1 ends on a round boundary (counter-based uniforms)."""

@@ -118,3 +118,96 @@ def test_first_sampled_token_follows_target_distribution():
     obs = np.append(counts[keep], counts[~keep].sum())
     exp = np.append(p[keep], p[~keep].sum()) * trials
     assert stats.chisquare(obs, exp).pvalue > 1e-3
+
+
+def _aligned_pair(seed, perturb):
+    """A draft with all of the target's layers plus noise: agrees with the target on part of the tokens."""
+    t = synth.make_model(SHAPE, seed, dtype=torch.float64, std=0.25)
+    d = synth.make_perturbed_draft(t, SHAPE.n_layers, seed + 1, std=perturb)
+    h = synth.make_head([SHAPE.d_model, 8, 1], seed + 2, dtype=torch.float64, std=0.3)
+    return oracle_model(t), oracle_model(d), oracle_head(h)
+
+
+def _play(tw, dw, hw, prompt, N, plan_of):
+    """Greedy rounds with the candidate count of every round imposed by plan_of(tokens so far)."""
+    target, draft = R.Recompute(tw), R.Recompute(dw)
+    x, out, st, rho = list(prompt), [], R.Stats(), 0
+    while len(out) < N:
+        k = plan_of(len(out))
+        r = R.oracle_round(target, draft, hw, x, rho, R.Params(greedy=True), 64, 512, forced={"K": k})
+        assert r["K"] == k
+        x += r["tokens"]
+        out += r["tokens"]
+        st.N_draft += k
+        st.N_target += 1
+        st.N_discarded += k - r["n"]
+        rho += 1
+    return out, st
+
+
+def test_hindsight_policy_discards_nothing_and_calls_the_target_once_per_disagreement():
+    """Sec. 4.1, Theorem 1, checked by playing the policy through the rounds: stopping right before
+    every disagreement yields the target's own tokens with N_discarded = 0 and N_target = |S| + 1
+    (|S| when the last token is itself a disagreement)."""
+    seen_adjacent = seen_last = seen_open = False
+    for seed, perturb in ((0, 0.02), (3, 0.08), (4, 0.03), (6, 0.05)):
+        tw, dw, hw = _aligned_pair(seed, perturb)
+        prompt = synth.make_prompt(6, SHAPE.vocab, seed)
+        N = 20
+        hs = R.hindsight_counts(tw, dw, prompt, N)
+        X, S = hs["X"], hs["S"]
+        assert X == R.target_greedy_generate(tw, prompt, N)
+        # S by its definition, one draft forward per position (the function uses a single forward)
+        for i in range(1, N + 1):
+            yi = sampling.argmax_lowest(forward_full(dw, list(prompt) + X[: i - 1])[0][-1])
+            assert (yi != X[i - 1]) == (i in S)
+        last = bool(S) and S[-1] == N
+        assert hs["N_target"] == len(S) + (0 if last else 1) and hs["N_discarded"] == 0
+        assert hs["N_draft"] + hs["N_target"] == N          # Sec. 3.2's identity with nothing discarded
+        seen_adjacent |= 0 in hs["plan"][:-1]
+        seen_last |= last
+        seen_open |= not last and hs["plan"][-1] > 0
+        it = iter(hs["plan"])
+        out, st = _play(tw, dw, hw, prompt, N, lambda pos: next(it))
+        assert out == X
+        assert (st.N_draft, st.N_target, st.N_discarded) == (hs["N_draft"], hs["N_target"], 0)
+    # the cases cover a target step without candidates, a last token that is a disagreement, and a last
+    # round that ends on the bonus token
+    assert seen_adjacent and seen_last and seen_open
+
+
+def test_no_stopping_policy_beats_hindsight_brute_force():
+    """Every stopping policy on a short generation (all candidate counts in every round, by
+    dynamic programming over the position with the rounds actually played): none discards less,
+    none calls the target less often, so by the time decomposition of Sec. 3.2
+    (T = T_0 + t_draft N_discarded + (t_target - t_draft) N_target) none is faster."""
+    tw, dw, hw = _aligned_pair(0, 0.02)
+    prompt = synth.make_prompt(6, SHAPE.vocab, 0)
+    N = 14
+    hs = R.hindsight_counts(tw, dw, prompt, N)
+    assert 0 < len(hs["S"]) < N
+    X = hs["X"]
+    target, draft = R.Recompute(tw), R.Recompute(dw)
+    gain = {}                                   # (pos, k) -> accepted candidates n of that round
+    for pos in range(N):
+        for k in range(0, N - pos):
+            r = R.oracle_round(target, draft, hw, list(prompt) + X[:pos], 0, R.Params(greedy=True), 64, 512,
+                               forced={"K": k})
+            assert r["tokens"] == X[pos: pos + r["n"] + 1]
+            gain[(pos, k)] = r["n"]
+    best = {N: (0, 0)}                          # pos -> set of (N_target, N_discarded) reachable to the end
+    frontier = {N: {(0, 0)}}
+    for pos in range(N - 1, -1, -1):
+        outs = set()
+        for k in range(0, N - pos):
+            n = gain[(pos, k)]
+            for (nt, nd) in frontier[min(N, pos + n + 1)]:
+                outs.add((nt + 1, nd + k - n))
+        frontier[pos] = outs
+    all_plans = frontier[0]
+    assert min(nt for nt, _ in all_plans) == hs["N_target"]
+    assert min(nd for _, nd in all_plans) == 0
+    assert (hs["N_target"], 0) in all_plans
+    t_d, t_t = 1.0, 4.8                          # the paper's ratio of forward times, about 0.0234 : 0.112
+    cost = lambda nt, nd: t_d * N + t_d * nd + (t_t - t_d) * nt
+    assert min(cost(nt, nd) for nt, nd in all_plans) == cost(hs["N_target"], 0)
