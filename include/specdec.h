@@ -177,6 +177,25 @@ sd_status sd_accept_resample(const float *p_logits_dev, const float *q_logits_de
                              int32_t *n_out_dev, int32_t *tok_out_dev, uint8_t *accept_flags_dev);
 int64_t sd_accept_workspace_bytes(int32_t B, int32_t Kmax);
 
+/* sd_accept_resample for callers that cannot allocate device memory (code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc): the same step
+ * with the row statistics kept in a device array that is part of the library image
+ * (SD_ACCEPT_STATIC_MAX_BATCH * (2 * SD_MAX_K + 1) * 16 + 16 bytes = 66 576 bytes per
+ * GPU, held until the process ends) instead of a caller's workspace.  Same arguments,
+ * same kernels and same results as sd_accept_resample; B > SD_ACCEPT_STATIC_MAX_BATCH
+ * is SD_ERANGE.  The call allocates nothing, frees nothing and does not synchronise.
+ * If status_word_dev_out is not NULL it receives the DEVICE address of the call's
+ * status word (see sd_accept_resample).  Every call on a GPU shares that GPU's array:
+ * calls that overlap on one GPU (different streams, different threads) race; calls on
+ * one stream are ordered and each overwrites what the last one left. */
+#define SD_ACCEPT_STATIC_MAX_BATCH 64
+sd_status sd_accept_resample_static(const float *p_logits_dev, const float *q_logits_dev,
+                                    const int32_t *cand_dev, const int32_t *K_per_seq_dev,
+                                    int32_t B, int32_t Kmax, int32_t V, const sd_params *params,
+                                    int32_t round_idx, void *hip_stream,
+                                    int32_t *n_out_dev, int32_t *tok_out_dev,
+                                    uint8_t *accept_flags_dev, int32_t **status_word_dev_out);
+
 /* Teacher-forced forward for parity checks and timing: ingest `n` tokens (HOST
  * ids) of sequence `seq` into model `which` (0 = target, 1 = draft) at cache
  * positions start .. start+n-1 (start <= that cache's current length; later

@@ -71,6 +71,9 @@ _PROTOS = {
                                        C.c_int32, C.POINTER(sd_params), C.c_int32, C.c_void_p, C.c_void_p,
                                        C.c_void_p, C.c_void_p, C.c_void_p]),
     "sd_accept_workspace_bytes": (C.c_int64, [C.c_int32, C.c_int32]),
+    "sd_accept_resample_static": (C.c_int32, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32,
+                                              C.c_int32, C.POINTER(sd_params), C.c_int32, C.c_void_p, C.c_void_p,
+                                              C.c_void_p, C.c_void_p, C.POINTER(C.c_void_p)]),
     "sd_forward": (C.c_int32, [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, _i32p, C.c_int32, _f32p, _f32p]),
     "sd_seq_state": (C.c_int32, [C.c_void_p, C.c_int32, _i32p, _i32p, _i32p, _i32p]),
     "sd_last_round_rows": (C.c_int32, [C.c_void_p, C.c_int32, _f32p, _f32p, _f32p]),
@@ -281,6 +284,31 @@ def sd_accept_resample(p_logits: torch.Tensor, q_logits: torch.Tensor, cand: tor
                                   B, Kmax, V, C.byref(params), round_idx, ws.data_ptr(), _stream_ptr(),
                                   n.data_ptr(), tok.data_ptr(), flags.data_ptr()), "sd_accept_resample")
     return n, tok, flags
+
+
+def lib_static_max_batch() -> int:
+    """SD_ACCEPT_STATIC_MAX_BATCH of the header."""
+    return 64
+
+
+def sd_accept_resample_static(p_logits: torch.Tensor, q_logits: torch.Tensor, cand: torch.Tensor,
+                              K_per_seq: torch.Tensor, params: sd_params, round_idx: int, out):
+    """sd_accept_resample with the library's static scratch: `out` = preallocated (n [B] int32,
+    token [B] int32, flags [B, Kmax] uint8) CUDA tensors (this wrapper allocates nothing on the
+    device either).  Returns the device address of the call's status word."""
+    B, Kp1, V = p_logits.shape
+    Kmax = Kp1 - 1
+    assert q_logits.shape == (B, Kmax, V) and cand.shape == (B, Kmax) and K_per_seq.shape == (B,)
+    for t, dt in ((p_logits, torch.float32), (q_logits, torch.float32), (cand, torch.int32), (K_per_seq, torch.int32)):
+        assert t.is_cuda and t.is_contiguous() and t.dtype == dt
+    n, tok, flags = out
+    assert n.shape == (B,) and tok.shape == (B,) and flags.shape == (B, Kmax)
+    word = C.c_void_p()
+    _check(lib.sd_accept_resample_static(p_logits.data_ptr(), q_logits.data_ptr(), cand.data_ptr(),
+                                         K_per_seq.data_ptr(), B, Kmax, V, C.byref(params), round_idx, _stream_ptr(),
+                                         n.data_ptr(), tok.data_ptr(), flags.data_ptr(), C.byref(word)),
+           "sd_accept_resample_static")
+    return word.value
 
 
 def sd_gemm_skinny(W: torch.Tensor, X: torch.Tensor, out=None) -> torch.Tensor:

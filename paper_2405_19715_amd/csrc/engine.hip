@@ -782,6 +782,49 @@ sd_status sd_accept_resample(const float* p_logits, const float* q_logits, const
                             n_out, tok_out, flags);
 }
 
+// ---- the same step for callers that cannot allocate: the row statistics live in a file-scope device array.
+// Every GPU holds its own copy of the array at its own address; the address is looked up once per device.
+namespace {
+constexpr int STATIC_ACCEPT_MAX_B = SD_ACCEPT_STATIC_MAX_BATCH;
+constexpr size_t STATIC_ACCEPT_BYTES = (size_t)STATIC_ACCEPT_MAX_B * (2 * SD_MAX_K + 1) * 16 + 16;
+constexpr int MAX_DEVICES = 64;
+}  // namespace
+static __device__ __align__(256) unsigned char scratch[STATIC_ACCEPT_BYTES];
+
+static sd_status static_scratch_ptr(void** out) {
+  static std::mutex mu;
+  static void* ptr_of_device[MAX_DEVICES] = {};
+  int dev = -1;
+  SD_HIP(hipGetDevice(&dev));
+  if (dev < 0 || dev >= MAX_DEVICES) return SD_EDEVICE;
+  std::lock_guard<std::mutex> lock(mu);
+  if (!ptr_of_device[dev]) {
+    void* p = nullptr;
+    SD_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    if (!p) return SD_EDEVICE;
+    ptr_of_device[dev] = p;
+  }
+  *out = ptr_of_device[dev];
+  return SD_OK;
+}
+
+sd_status sd_accept_resample_static(const float* p_logits, const float* q_logits, const int32_t* cand,
+                                    const int32_t* K, int32_t B, int32_t Kmax, int32_t V, const sd_params* params,
+                                    int32_t round_idx, void* hip_stream, int32_t* n_out, int32_t* tok_out,
+                                    uint8_t* flags, int32_t** status_word_dev) {
+  if (!p_logits || !q_logits || !cand || !K || !n_out || !tok_out || !flags || !params_ok(params)) return SD_EINVAL;
+  if (B < 1 || Kmax < 1 || Kmax > SD_MAX_K || V < 1) return SD_EINVAL;
+  if (B > STATIC_ACCEPT_MAX_B) return SD_ERANGE;            // beyond the static array: use sd_accept_resample
+  void* ws = nullptr;
+  sd_status s = static_scratch_ptr(&ws);
+  if (s != SD_OK) return s;
+  if (status_word_dev) *status_word_dev = (int32_t*)((float*)ws + (size_t)B * (2 * Kmax + 1) * 4);
+  // nothing in the array has to start at zero: every statistic a call reads it has written before, and the status
+  // word is cleared by the first kernel
+  return accept_resample_on(p_logits, q_logits, cand, K, B, Kmax, V, params, round_idx, ws, (hipStream_t)hip_stream,
+                            n_out, tok_out, flags);
+}
+
 sd_status sd_forward(sd_ctx* c, int32_t which, int32_t seq, int32_t start, const int32_t* tokens, int32_t n,
                      float* logits_host, float* hidden_host) {
   if (!c || !tokens || (which != 0 && which != 1) || seq < 0 || seq >= c->B || n < 1 || n > PREFILL_CHUNK || start < 0)
