@@ -16,7 +16,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libspecdec.so")
-SOURCES = ["gemm.hip", "gemm_tile.hip", "elementwise.hip", "attention.hip", "sampling.hip", "train.hip", "engine.hip"]
+SOURCES = ["gemm.hip", "gemm_mstripe.hip", "gemm_tile.hip", "elementwise.hip", "attention.hip", "sampling.hip", "train.hip", "engine.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden",
          # packed-fp32 VALU forms are kept out of the generated code on purpose
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

@@ -40,6 +40,7 @@
 // fp32 weights (tiny configuration) take a plain wave-per-output-row kernel.
 #include "common.hpp"
 #include "kernels.hpp"
+#include "stripe_epilogue.hpp"
 
 #include <cstdlib>
 #include <mutex>
@@ -405,41 +406,6 @@ StripePlan plan_stripe(int M, int N, int K, bool paired = false, bool even_rows 
   return StripePlan{1, cs, rpg, G, ranges, rpw, npass};
 }
 
-// What the final sweep of the stripe kernel does with the sums (EPI):
-//   EPI_PART  part[m][n] = r_m sum
-//   EPI_SILU  W = [gate; up] with N rows each (2 N in all), one slice, rpg even: the workgroup's local ranges come
-//             in pairs, range g of gate and range g of up, and act[m, n] = silu(r_m gate) * (r_m up) in bf16: the
-//             MLP's activation without a launch of its own.
-//             (both: r_m = 1 unless the input rows were left unscaled by an EPI_RESID launch, whose sums of squares
-//             then give r_m = rsqrt(mean(x_m^2) + eps))
-//   EPI_RESID one slice: x[m, n] += sum (the residual stream, fp32); act[m, n] = bf16(x[m, n] * gain[n]), the next
-//             product's input WITHOUT the RMSNorm factor of its row (a per-row scalar commutes with the product, so
-//             the consumer applies it to its sums); ssq_out[m][workgroup] = sum of x[m, n]^2 over the workgroup's
-//             columns, added by the consumer in workgroup order.  Residual + RMSNorm without a launch of their own.
-//   EPI_ROPE  W = [q; k; v] rows of a decoder layer, head dimension 2^(hshift+1).  The row ranges walk the rows in
-//             the order (head, i, half): local index j stands for row (j/2 / half) hd + (j/2 % half) + (j%2) half,
-//             so the two sums of a rotary pair (i, i + hd/2) sit side by side in one wavefront's tile, and the sweep
-//             rotates them at the row's position and writes q (bf16 [M, Hq hd]), the key cache row and the
-//             (transposed) value cache column itself: no launch of its own for the rotary embedding and the KV append.
-enum { EPI_PART = 0, EPI_SILU = 1, EPI_RESID = 2, EPI_ROPE = 3 };
-struct StripeEpi {
-  bf16_t* act;             // SILU / RESID output [M][N]
-  float* x;                // RESID: residual rows [M][N], updated in place
-  const bf16_t* gain;      // RESID: [N]
-  float* ssq_out;          // RESID: [M][gridDim.x]
-  const float* ssq_in;     // PART / SILU: [M][ssq_n] or null
-  int ssq_n;
-  float inv_d, eps;        // 1 / (length of the input rows whose squares ssq_in sums), RMSNorm epsilon
-  // ROPE
-  const int32_t* row_seq;  // [M] sequence of the row, < 0 = padding row (nothing written)
-  const int32_t* row_pos;  // [M] position of the row's token
-  const float* cos_sin;    // [max_seq][hd / 2][2]
-  bf16_t* qbuf;            // [M][Hq * hd]
-  bf16_t* kcache;          // [seq][Hkv][max_seq][hd]
-  bf16_t* vcache;          // [seq][Hkv][hd][max_seq]
-  int Hq, Hkv, hshift, max_seq;
-};
-
 // RAGGED: K is not a multiple of 2048; a lane of the last stripe whose piece lies beyond K reads the first 16 bytes
 // of the stripe instead (lane 0's piece 0, which every stripe has: a fixed per-lane offset, nothing changes in the
 // loop) against zeros in X.
@@ -461,26 +427,9 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_stripe(const bf16_t* _
   const int rows = rg < ranges ? min(rpw, N - rg * rpw) : 0;     // a wavefront without rows still meets the barrier
   const bf16_t* const idle = W + lane * 8;
 
-  __shared__ float s_scale[STRIPE_MAX_M];            // SILU: r_m;  RESID: scratch of the sums of squares
-  __shared__ float s_red[GEMM_WAVES][STRIPE_MAX_M];
-  // SILU: the RMSNorm factors of the input rows come from the producer's per-workgroup sums of squares (at most 256
-  // per row).  Wavefront w takes rows w and w + (wavefronts in the workgroup): the loads go out first of all and
-  // are added after the stream, in a fixed order (four per lane, then the butterfly).
-  float sq[2][4] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
-  if constexpr (EPI != EPI_RESID) {
-    if (epi.ssq_in) {
-      const int nw = blockDim.x >> 6;
-#pragma unroll
-      for (int u = 0; u < 2; ++u) {
-        const int m = min(wave + u * nw, MM - 1);
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          const int idx = lane + WAVE * i;
-          sq[u][i] = idx < epi.ssq_n ? epi.ssq_in[m * epi.ssq_n + idx] : 0.f;
-        }
-      }
-    }
-  }
+  __shared__ float s_scale[STRIPE_MAX_M];            // the rows' RMSNorm factors (1 unless the producer left them out)
+  float sq[2][STRIPE_SSQ_PER_LANE];                  // up to 2 * 7 wavefronts >= 8 rows
+  if constexpr (EPI != EPI_RESID) stripe_load_ssq<2>(epi, MM, sq);
 
   // after the butterfly lane l holds the sum of activation row l / (64 / P2); its lanes with the low bits
   // clear put it into the wave's LDS tile [MM][rpw]; the tiles of the cs stripes are added and go to part[] in
@@ -573,105 +522,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_stripe(const bf16_t* _
       }
     }
   }
-  if constexpr (EPI != EPI_RESID) {
-    const int nw = blockDim.x >> 6;
-#pragma unroll
-    for (int u = 0; u < 2; ++u) {
-      const int m = wave + u * nw;
-      const float t = wave_sum((sq[u][0] + sq[u][1]) + (sq[u][2] + sq[u][3]));
-      if (m < MM && lane == 0) s_scale[m] = epi.ssq_in ? 1.0f / sqrtf(t * epi.inv_d + epi.eps) : 1.0f;
-    }
-  }
-  __syncthreads();
-  // stripe tiles of one row range are added in stripe order
-  const int tile = MM * rpw;
-  if constexpr (EPI == EPI_SILU) {
-    for (int idx = threadIdx.x; idx < (rpg >> 1) * tile; idx += blockDim.x) {
-      const int l = idx / tile, rem = idx - l * tile;
-      const int m = rem / rpw, r = rem - m * rpw;
-      const int g = blockIdx.x * (rpg >> 1) + l;
-      if (g >= ranges || g * rpw + r >= N) continue;
-      const float* sg = obuf + (size_t)(2 * l) * cs * tile + rem;
-      const float* su = sg + (size_t)cs * tile;
-      // both in stripe order (stripe t of `up` sits in the tile of local wavefront t - 1)
-      float gate = sg[0], up = su[(size_t)(cs - 1) * tile];
-      for (int t = 1; t < cs; ++t) {
-        gate += sg[(size_t)t * tile];
-        up += su[(size_t)(t - 1) * tile];
-      }
-      const float rm = s_scale[m];
-      gate *= rm;
-      up *= rm;
-      epi.act[(size_t)m * N + g * rpw + r] = f2bf(gate / (1.0f + expf(-gate)) * up);
-    }
-  } else if constexpr (EPI == EPI_ROPE) {
-    const int hw = rpw >> 1, hs = epi.hshift, half = 1 << hs, hd = 2 << hs;
-    for (int idx = threadIdx.x; idx < rpg * MM * hw; idx += blockDim.x) {
-      const int l = idx / (MM * hw), rem = idx - l * (MM * hw);
-      const int m = rem / hw, q = rem - m * hw;
-      const int g = blockIdx.x * rpg + l;
-      const int j = g * rpw + 2 * q;                   // local index of the pair's first row
-      if (g >= ranges || j >= N) continue;
-      const int seq = epi.row_seq[m];
-      if (seq < 0) continue;
-      const int pos = epi.row_pos[m];
-      const float* src = obuf + (size_t)l * cs * tile + m * rpw + 2 * q;
-      float a = src[0], b = src[1];
-      for (int t = 1; t < cs; ++t) {
-        a += src[(size_t)t * tile];
-        b += src[(size_t)t * tile + 1];
-      }
-      a *= s_scale[m];
-      b *= s_scale[m];
-      const int p = j >> 1, slot = p >> hs, i = p & (half - 1);
-      if (slot < epi.Hq + epi.Hkv) {
-        const float* cs2 = epi.cos_sin + ((size_t)pos * half + i) * 2;
-        float ra, rb;
-        rope_pair(a, b, cs2[0], cs2[1], ra, rb);
-        bf16_t* dst = slot < epi.Hq
-                          ? epi.qbuf + ((size_t)m * epi.Hq + slot) * hd + i
-                          : epi.kcache + (((size_t)seq * epi.Hkv + (slot - epi.Hq)) * epi.max_seq + pos) * hd + i;
-        dst[0] = f2bf(ra);
-        dst[half] = f2bf(rb);
-      } else {
-        bf16_t* v = epi.vcache + ((size_t)seq * epi.Hkv + (slot - epi.Hq - epi.Hkv)) * hd * (size_t)epi.max_seq + pos;
-        v[(size_t)i * epi.max_seq] = f2bf(a);
-        v[(size_t)(i + half) * epi.max_seq] = f2bf(b);
-      }
-    }
-  } else if constexpr (EPI == EPI_RESID) {
-    // wavefront w takes activation rows w, w + (wavefronts), ...: a row's sum of squares stays inside one wavefront
-    const int nw = blockDim.x >> 6;
-    for (int m = wave; m < MM; m += nw) {
-      float ssq = 0.f;
-      for (int e = lane; e < rpg * rpw; e += WAVE) {
-        const int l = e / rpw, r = e - l * rpw;
-        const int g = blockIdx.x * rpg + l;
-        const int n = g * rpw + r;
-        if (g >= ranges || n >= N) continue;
-        const float* src = obuf + (size_t)l * cs * tile + m * rpw + r;
-        float sum = src[0];
-        for (int t = 1; t < cs; ++t) sum += src[(size_t)t * tile];
-        const float xv = epi.x[(size_t)m * N + n] + sum;
-        epi.x[(size_t)m * N + n] = xv;
-        epi.act[(size_t)m * N + n] = f2bf(xv * bf2f(epi.gain[n]));
-        ssq += xv * xv;
-      }
-      ssq = wave_sum(ssq);
-      if (lane == 0) epi.ssq_out[m * gridDim.x + blockIdx.x] = ssq;
-    }
-  } else {
-    for (int idx = threadIdx.x; idx < rpg * tile; idx += blockDim.x) {
-      const int l = idx / tile, rem = idx - l * tile;
-      const int m = rem / rpw, r = rem - m * rpw;
-      const int g = blockIdx.x * rpg + l;
-      if (g >= ranges || g * rpw + r >= N) continue;
-      const float* src = obuf + (size_t)l * cs * tile + rem;
-      float sum = src[0];
-      for (int t = 1; t < cs; ++t) sum += src[(size_t)t * tile];
-      part[(size_t)m * N + g * rpw + r] = sum * s_scale[m];      // s_scale = 1 unless the input rows lack their norm factor
-    }
-  }
+  stripe_finish<EPI, 2>(obuf, s_scale, sq, part, epi, MM, N, cs, rpg, ranges, rpw);
 }
 
 template <int MM, int EPI>
@@ -771,6 +622,7 @@ bool use_tile(int M, int N, int K) { return M > STREAM_MAX_ROWS && K % 32 == 0 &
 
 int gemm_splits(int dtype, int M, int N, int K) {
   if (dtype == DT_F32) return 1;
+  if (mstripe_ok(M, N, K, EPI_PART)) return 1;
   if (use_tile(M, N, K)) return gemm_tile_splits(M, N, K);
   if (use_stripe(M, N, K)) return plan_stripe(M, N, K).S;
   return plan_bf16(M, N, K).S;
@@ -786,6 +638,10 @@ hipError_t launch_gemm(hipStream_t st, int dtype, const void* W, const void* X, 
     return hipGetLastError();
   }
   if (dtype != DT_BF16) return hipErrorInvalidValue;
+  if (mstripe_ok(M, N, K, EPI_PART)) {
+    if (reinterpret_cast<uintptr_t>(part) & 15) return hipErrorInvalidValue;
+    return launch_mstripe(st, EPI_PART, W, X, ldx, xrow, part, StripeEpi{}, M, N, K);
+  }
   if (use_tile(M, N, K)) return launch_gemm_tile(st, W, X, ldx, xrow, part, M, N, K);
   if (use_stripe(M, N, K)) {
     if (ldx % 8 != 0 ||
@@ -808,7 +664,7 @@ hipError_t launch_gemm(hipStream_t st, int dtype, const void* W, const void* X, 
 }
 
 bool gemm_silu_fused(int dtype, int M, int ffn, int K) {
-  return dtype == DT_BF16 && plan_stripe(M, ffn, K, true).S == 1;
+  return dtype == DT_BF16 && (plan_stripe(M, ffn, K, true).S == 1 || mstripe_ok(M, ffn, K, EPI_SILU));
 }
 
 hipError_t launch_gemm_silu(hipStream_t st, int dtype, const void* W, const void* X, int ldx, const int* xrow,
@@ -822,11 +678,14 @@ hipError_t launch_gemm_silu(hipStream_t st, int dtype, const void* W, const void
   epi.ssq_n = ssq_n;
   epi.inv_d = ssq ? 1.0f / (float)d_in : 0.f;
   epi.eps = eps;
+  if (M > STRIPE_MAX_M) return launch_mstripe(st, EPI_SILU, W, X, ldx, xrow, nullptr, epi, M, ffn, K);
   return launch_stripe<EPI_SILU>(st, (const bf16_t*)W, (const bf16_t*)X, ldx, xrow, nullptr, epi, M, ffn, K,
                                  plan_stripe(M, ffn, K, true));
 }
 
-bool gemm_scaled_ok(int dtype, int M, int N, int K) { return dtype == DT_BF16 && use_stripe(M, N, K); }
+bool gemm_scaled_ok(int dtype, int M, int N, int K) {
+  return dtype == DT_BF16 && (use_stripe(M, N, K) || mstripe_ok(M, N, K, EPI_PART));
+}
 
 hipError_t launch_gemm_scaled(hipStream_t st, int dtype, const void* W, const void* X, int ldx, const int* xrow,
                               float* part, int M, int N, int K, const float* ssq, int ssq_n, int d_in, float eps) {
@@ -840,6 +699,7 @@ hipError_t launch_gemm_scaled(hipStream_t st, int dtype, const void* W, const vo
   epi.ssq_n = ssq_n;
   epi.inv_d = 1.0f / (float)d_in;
   epi.eps = eps;
+  if (M > STRIPE_MAX_M) return launch_mstripe(st, EPI_PART, W, X, ldx, xrow, part, epi, M, N, K);
   return launch_stripe<EPI_PART>(st, (const bf16_t*)W, (const bf16_t*)X, ldx, xrow, part, epi, M, N, K,
                                  plan_stripe(M, N, K));
 }
@@ -855,7 +715,7 @@ int log2_exact(int v) {                 // -1 unless v is a power of two
 
 bool gemm_rope_fused(int dtype, int M, int Hq, int Hkv, int hd, int K) {
   if (dtype != DT_BF16 || Hq < 1 || Hkv < 1 || hd < 2 || log2_exact(hd) < 1) return false;
-  return plan_stripe(M, (Hq + 2 * Hkv) * hd, K, false, true).S == 1;
+  return plan_stripe(M, (Hq + 2 * Hkv) * hd, K, false, true).S == 1 || mstripe_ok(M, (Hq + 2 * Hkv) * hd, K, EPI_ROPE);
 }
 
 hipError_t launch_gemm_rope(hipStream_t st, int dtype, const void* W, const void* X, int ldx, int M, int Hq, int Hkv,
@@ -883,12 +743,14 @@ hipError_t launch_gemm_rope(hipStream_t st, int dtype, const void* W, const void
   epi.hshift = log2_exact(hd) - 1;
   epi.max_seq = max_seq;
   const int N = (Hq + 2 * Hkv) * hd;
+  if (M > STRIPE_MAX_M) return launch_mstripe(st, EPI_ROPE, W, X, ldx, nullptr, nullptr, epi, M, N, K);
   return launch_stripe<EPI_ROPE>(st, (const bf16_t*)W, (const bf16_t*)X, ldx, nullptr, nullptr, epi, M, N, K,
                                  plan_stripe(M, N, K, false, true));
 }
 
 int gemm_resid_groups(int dtype, int M, int N, int K) {
   if (dtype != DT_BF16) return 0;
+  if (M > STRIPE_MAX_M) return mstripe_groups(M, N, K, EPI_RESID);
   const StripePlan sp = plan_stripe(M, N, K);
   return sp.S == 1 ? sp.G : 0;
 }
@@ -903,6 +765,7 @@ hipError_t launch_gemm_resid(hipStream_t st, int dtype, const void* W, const voi
   epi.x = x;
   epi.gain = (const bf16_t*)gain;
   epi.ssq_out = ssq;
+  if (M > STRIPE_MAX_M) return launch_mstripe(st, EPI_RESID, W, X, ldx, xrow, nullptr, epi, M, N, K);
   return launch_stripe<EPI_RESID>(st, (const bf16_t*)W, (const bf16_t*)X, ldx, xrow, nullptr, epi, M, N, K,
                                   plan_stripe(M, N, K));
 }

@@ -71,15 +71,17 @@ def test_bf16_matches_oracle(shape):
 
 # Widths that are multiples of 2048 send rows of up to 8 through the row-stripe GEMM, whose final sweep does the
 # SiLU * up, both residual adds and the RMSNorm preparation (the consumers apply the rows' norm factors): chunks of
-# every row count 1 .. 8 exercise each instantiation, 9 and 17 the MFMA / tiled kernels with the separate small
-# kernels, and the cache carries over between the two kinds of pass.
+# every row count 1 .. 8 exercise each instantiation of the vector-ALU kernel, 9 .. 17 the matrix-core member of the
+# family (same sweeps), 18 and more the tiled kernel with the separate small kernels, and the cache carries over
+# between the kinds of pass.
+@pytest.mark.parametrize("chunks", [[9, 1, 2, 3, 4, 5, 6, 7, 8, 17, 1, 8], [16, 15, 14, 13, 12, 11, 10, 9, 17, 18, 3]])
 @pytest.mark.parametrize("shape", [
     synth.ModelShape(3, 2048, 16, 2, 128, 4096, 1024),       # q|k|v, o, gate|up, down all stripe-shaped (K = 2048 / 4096)
     synth.ModelShape(2, 2048, 32, 32, 64, 5632, 1024),       # down K = 5632 stays on the MFMA kernel (1.1B-like MLP)
     synth.ModelShape(2, 4096, 32, 4, 128, 2048 * 3, 512),    # 2 and 3 stripes per row
 ])
-def test_bf16_fused_epilogues_match_oracle(shape):
-    _forward_case(shape, torch.bfloat16, 71, [9, 1, 2, 3, 4, 5, 6, 7, 8, 17, 1, 8], std=0.02)
+def test_bf16_fused_epilogues_match_oracle(shape, chunks):
+    _forward_case(shape, torch.bfloat16, sum(chunks), chunks, std=0.02)
 
 
 def test_bf16_long_context_many_key_splits():
