@@ -5,7 +5,7 @@
 // range of weight rows, every load instruction covers 1 KB of ONE row (the access pattern that reads HBM fastest),
 // its piece of X lives in registers for the whole pass, the K pieces of a row range all belong to one workgroup,
 // which adds them at the end, so there is ONE slice of finished sums and the final sweep does the elementwise work
-// of the decoder layer (SiLU * up, residual + norm, rotary embedding + KV append: stripe_epilogue.hpp).  What
+// of the decoder layer (SiLU * up, residual + norm, rotary embedding + KV append: stripe_common.hpp).  What
 // differs is the multiply: 16 * M dot products per 16 bytes of weights do not fit the vector ALU beyond 8 rows
 // (it is 54 % busy there), so the products run on the matrix cores, v_mfma_f32_16x16x32_bf16 with the weights
 // as the A operand (16 rows x 32 k) and X^T as the B operand.
@@ -14,19 +14,22 @@
 // of ONE row: the tile is transposed through a per-wavefront LDS buffer.  A wavefront takes 8 weight rows at a
 // time (rows 8 .. 15 of the A operand read a row of zeros: the matrix cores have time to spare, LDS space is what
 // is short): row r of the 8 goes to LDS as it arrives, 16-byte block b of the row at slot b ^ r of the row's 1 KB,
-// and lane (i, g) reads block t + 16 g of row i for MFMA t: both the 64-lane write and the read hit 16 distinct
+// and lane (i, g) reads block 4 t + g of row i for MFMA t: both the 64-lane write and the read hit 16 distinct
 // 16-byte bank groups per 16 lanes.  The 16 row registers of a wavefront are a ring over two such half tiles, each
 // reloaded as soon as it has been written to LDS, so 16 KB per wavefront are in flight all the time, as in the
 // vector-ALU kernel.  LDS operations of one wavefront execute in order, so the next half tile's writes cannot
 // overtake this one's reads.
 //
-// X: the B operand of MFMA t is X[m = lane % 16][k0 + 8 (t + 16 g) ..], 16 registers of 16 bytes for the first 16
-// activation rows.  A 17th row (K = 16 candidates) would need 16 more for one live lane in 16; its operands are
-// packed four to a register (lanes 0, 4, 8, 12 of each 16 hold the operands of four consecutive MFMAs) and moved
-// into lane 0 by a DPP row shift when used.
+// X: the B operand of MFMA t is X[m = lane % 16][k0 + 8 (4 t + g) ..], 16 registers of 16 bytes for the first 16
+// activation rows (a load instruction reads 64 contiguous bytes of each row: with block t + 16 g instead, 64 separate
+// 16-byte pieces per instruction, the X loads of a pass cost the CU's address path about 4 us, seven times per
+// launch on the 70B down projection).  A 17th row (K = 16 candidates) would need a second MFMA per step for one live
+// column in 16; it is multiplied on the vector ALU instead, where the weight rows pass through registers in row
+// order anyway: its piece of X is ONE register quad (lane l: the 8 k of block l, as the weights), four v_dot2 per
+// weight row before the row goes to LDS, and one transposing butterfly over the 8 sums of a half tile.
 #include "common.hpp"
 #include "kernels.hpp"
-#include "stripe_epilogue.hpp"
+#include "stripe_common.hpp"
 
 #include <mutex>
 
@@ -60,22 +63,6 @@ __device__ __forceinline__ uint4 ms_ld_stream(const bf16_t* p) {      // read on
   return v;
 }
 
-// lanes 0 .. 3 of every 16 take `src` from the lane SHL further up (lane 0 <- lane SHL), all other lanes 0
-template <int SHL>
-__device__ __forceinline__ uint32_t ms_take_lane(uint32_t src) {
-  constexpr int CTRL = SHL == 0 ? 0xE4 : 0x100 + SHL;        // quad_perm identity, or row_shl:SHL
-  return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)src, CTRL, 0xF, 0x1, false);
-}
-template <int SHL>
-__device__ __forceinline__ uint4 ms_take_lane4(const uint4& v) {
-  return uint4{ms_take_lane<SHL>(v.x), ms_take_lane<SHL>(v.y), ms_take_lane<SHL>(v.z), ms_take_lane<SHL>(v.w)};
-}
-// operand of MFMA t from the packed 17th-row registers (t = 4 q + jj sits in lanes 4 jj of register q)
-template <int T>
-__device__ __forceinline__ uint4 ms_row16_operand(const uint4 (&xp)[4]) {
-  return ms_take_lane4<4 * (T & 3)>(xp[T >> 2]);
-}
-
 // MT = 1: up to 16 activation rows; MT = 2: 17.
 template <int MT, int EPI>
 __global__ __launch_bounds__(MS_THREADS) void gemm_bf16_mstripe(const bf16_t* __restrict__ W,
@@ -85,7 +72,9 @@ __global__ __launch_bounds__(MS_THREADS) void gemm_bf16_mstripe(const bf16_t* __
                                                                 int K, int cs, int rpg, int ranges, int rpw,
                                                                 int npass) {
   constexpr bool SILU = EPI == EPI_SILU;
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  // the wavefront's index as a scalar: everything derived from it (row range, pieces, loop bounds) then lives in
+  // scalar registers and the address selection below costs no vector compares or exec-mask branches
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int li = lane & 15, g = lane >> 4;
   const int lr = wave / cs, ls = wave - lr * cs;     // local row range, local K slot
   const int rg = SILU ? blockIdx.x * (rpg >> 1) + (lr >> 1) : blockIdx.x * rpg + lr;
@@ -108,98 +97,126 @@ __global__ __launch_bounds__(MS_THREADS) void gemm_bf16_mstripe(const bf16_t* __
   float* const otile = obuf + (size_t)wave * M * rpw;
   // the row of zeros that lanes 8 .. 15 of every 16 read as their A operand
   *reinterpret_cast<uint4*>(buf + MS_HALF * 1024 + lane * 16) = uint4{0u, 0u, 0u, 0u};
-  // this lane's write slot for row r of a half tile is (lane ^ r); its read for MFMA t is block (t + 16 g) of row
+  // this lane's write slot for row r of a half tile is (lane ^ r); its read for MFMA t is block (4 t + g) of row
   // li (or of the zero row), at slot block ^ li
   const unsigned char* const rd_row = buf + (li < MS_HALF ? li : MS_HALF) * 1024;
 
+  // The weight stream runs across the passes: the ring is refilled from the next pass's piece while this pass's last
+  // half tiles are multiplied, so only the X operands change at a pass boundary.  NH = half tiles per pass rounded
+  // up to the ring's two halves (a padding half tile reads the idle line, goes through LDS unread, and is neither
+  // multiplied nor stored).
+  const int NH = (nh + 1) & ~1;
+  const int ps_off = rg % npass;
+  auto piece_of = [&](int ps) { int q = ps + ps_off; q = q >= npass ? q - npass : q; return q * cs + c0; };
+  // start row per pass: the same for the K slots of a row range, so that together they read 8 (4) KB contiguous
+  // pieces of a row at about the same time; different from range to range
+  auto rot_of = [&](int ps) { return nh > 0 ? ((rg * npass + ps) * 5) % nh : 0; };
+  // row r of half tile h of the pass whose piece is c (< 0: past the last pass) and whose walk starts at half tile
+  // rot -> address of this lane's 16 bytes (or the idle line past the range / the end)
+  auto at = [&](int c, int rot, int h, int r) -> const bf16_t* {
+    int hh = h + rot;
+    hh = hh >= nh ? hh - nh : hh;
+    const int j = hh * MS_HALF + r;
+    const bool dead = c < 0 || h >= nh || j >= rows;   // no branch: the address is formed either way, then selected
+    int row = dead ? 0 : r0 + j;
+    if constexpr (EPI == EPI_ROPE) {                   // local index -> row of W: (head, i, half) order
+      const int hs = epi.hshift;
+      const int p = row >> 1;
+      row = ((p >> hs) << (hs + 1)) + (p & ((1 << hs) - 1)) + ((row & 1) << hs);
+    }
+    const bf16_t* q = W + (size_t)row * K + (dead ? 0 : c) * MS_PIECE + lane * 8;
+    return dead ? idle : q;
+  };
+  // B operands of a pass: MFMA t, lane (m, g) takes the 8 k of 16-byte block 4 t + g of its row, so that one load
+  // instruction reads 64 contiguous bytes of each of its 16 rows
+  uint4 xb[16];
+  uint4 x16 = uint4{0u, 0u, 0u, 0u};                   // MT == 2: the 17th row's piece, lane l: block l
+  // with fewer than 16 rows the lanes beyond take the last row again: their columns of the product are finite and
+  // never stored.  The gather indices are read once, here: a dependent load inside a pass would make the pass wait
+  // for every weight load in flight.
+  const int xm = xrow ? xrow[min(li, M - 1)] : min(li, M - 1);
+  const int xm16 = MT == 2 ? (xrow ? xrow[16] : 16) : 0;
+  auto load_x = [&](int ps) {
+    const int c = piece_of(ps);
+    const bf16_t* xr = X + (size_t)xm * ldx + c * MS_PIECE + g * 8;
+#pragma unroll
+    for (int t = 0; t < 16; ++t) xb[t] = *reinterpret_cast<const uint4*>(xr + t * 32);
+    if constexpr (MT == 2)
+      x16 = *reinterpret_cast<const uint4*>(X + (size_t)xm16 * ldx + c * MS_PIECE + lane * 8);
+  };
+  // The weight ring first: HBM starts working at once.  X is not needed before the first MFMA, by when the ring's
+  // first half tile must have arrived anyway (and the second is needed right after).
+  uint4 a[2 * MS_HALF];
+  int roth = rot_of(0);
+#pragma unroll
+  for (int i = 0; i < 2 * MS_HALF; ++i) a[i] = ms_ld_stream(at(piece_of(0), roth, i / MS_HALF, i % MS_HALF));
+  __builtin_amdgcn_sched_barrier(0);
+  load_x(0);
+  __builtin_amdgcn_sched_barrier(0);
+
   for (int ps = 0; ps < npass; ++ps) {
-    const int c = ps * cs + c0;                        // this pass's piece of K
-    const int roth = nh > 0 ? ((rg * npass * cs + c) * 5) % nh : 0;      // the wavefronts start at different rows
-    // row r of half tile h -> address of this lane's 16 bytes (or the idle line past the range)
-    auto at = [&](int h, int r) -> const bf16_t* {
-      int hh = h + roth;
-      if (hh >= nh) hh -= nh;
-      const int j = hh * MS_HALF + r;
-      if (h >= nh || j >= rows) return idle;
-      int row = r0 + j;
-      if constexpr (EPI == EPI_ROPE) {                 // local index -> row of W: (head, i, half) order
-        const int hs = epi.hshift;
-        const int p = row >> 1;
-        row = ((p >> hs) << (hs + 1)) + (p & ((1 << hs) - 1)) + ((row & 1) << hs);
-      }
-      return W + (size_t)row * K + c * MS_PIECE + lane * 8;
-    };
-
-    // X first: its loads are then older than every weight load
-    uint4 xb[16];
-    uint4 xp[4];
-    {
-      const int m = min(li, M - 1);
-      const bf16_t* xr = X + (size_t)(xrow ? xrow[m] : m) * ldx + c * MS_PIECE + g * 128;
-#pragma unroll
-      for (int t = 0; t < 16; ++t) xb[t] = *reinterpret_cast<const uint4*>(xr + t * 8);
-      if constexpr (MT == 2) {
-        const bf16_t* x16 = X + (size_t)(xrow ? xrow[16] : 16) * ldx + c * MS_PIECE + g * 128 + (li >> 2) * 8;
-#pragma unroll
-        for (int q = 0; q < 4; ++q) xp[q] = *reinterpret_cast<const uint4*>(x16 + q * 32);
-      }
-    }
-    uint4 a[2 * MS_HALF];
-#pragma unroll
-    for (int i = 0; i < 2 * MS_HALF; ++i) a[i] = ms_ld_stream(at(i / MS_HALF, i % MS_HALF));
-    __builtin_amdgcn_sched_barrier(0);
-    if (li >= M) {                                     // fewer than 16 rows: the missing ones multiply zeros
-#pragma unroll
-      for (int t = 0; t < 16; ++t) xb[t] = uint4{0u, 0u, 0u, 0u};
-    }
-    if constexpr (MT == 2) {
-      if (li & 3) {                                    // only lanes 0, 4, 8, 12 of every 16 carry 17th-row operands
-#pragma unroll
-        for (int q = 0; q < 4; ++q) xp[q] = uint4{0u, 0u, 0u, 0u};
-      }
-    }
-
-    for (int h0 = 0; h0 < nh; h0 += 2) {
+    if (ps > 0) load_x(ps);                            // behind the ring's loads, which the pass needs first anyway
+    const int c = piece_of(ps);
+    const int c_next = ps + 1 < npass ? piece_of(ps + 1) : -1, rot_next = rot_of(ps + 1);
+    for (int h0 = 0; h0 < NH; h0 += 2) {
 #pragma unroll
       for (int p = 0; p < 2; ++p) {
         const int h = h0 + p;
         __builtin_amdgcn_sched_barrier(0);             // half tiles stay in order: the next one's data is still in flight
+        float s16[MS_HALF];                            // MT == 2: this lane's share of the 17th row's 8 sums
 #pragma unroll
         for (int r = 0; r < MS_HALF; ++r) {
           *reinterpret_cast<uint4*>(buf + r * 1024 + ((lane ^ r) << 4)) = a[p * MS_HALF + r];
-          a[p * MS_HALF + r] = ms_ld_stream(at(h + 2, r));
+          if constexpr (MT == 2) s16[r] = dot8(a[p * MS_HALF + r], x16, 0.f);
+          const bool nx = h + 2 >= NH;                 // the ring runs on into the next pass's piece
+          a[p * MS_HALF + r] = ms_ld_stream(at(nx ? c_next : c, nx ? rot_next : roth, nx ? h + 2 - NH : h + 2, r));
         }
-        floatx4 acc0 = floatx4{0.f, 0.f, 0.f, 0.f}, acc1 = floatx4{0.f, 0.f, 0.f, 0.f};
-#define SD_MS_STEP(T)                                                                                              \
-        {                                                                                                          \
-          const uint4 f = *reinterpret_cast<const uint4*>(rd_row + ((((T) + 16 * g) ^ li) << 4));                  \
-          acc0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ms_as_bf16x8(f), ms_as_bf16x8(xb[T]), acc0, 0, 0, 0);     \
-          if constexpr (MT == 2)                                                                                   \
-            acc1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ms_as_bf16x8(f), ms_as_bf16x8(ms_row16_operand<T>(xp)), \
-                                                           acc1, 0, 0, 0);                                         \
-        }
-        SD_MS_STEP(0) SD_MS_STEP(1) SD_MS_STEP(2) SD_MS_STEP(3) SD_MS_STEP(4) SD_MS_STEP(5) SD_MS_STEP(6) SD_MS_STEP(7)
-        SD_MS_STEP(8) SD_MS_STEP(9) SD_MS_STEP(10) SD_MS_STEP(11) SD_MS_STEP(12) SD_MS_STEP(13) SD_MS_STEP(14)
-        SD_MS_STEP(15)
-#undef SD_MS_STEP
-        // D[i][m]: lane (m = li, g) holds weight rows 4 g .. 4 g + 3 of the half tile (g < 2) for activation row m
-        if (h < nh && g < 2) {
+        __builtin_amdgcn_sched_barrier(0);
+        if (h < nh) {                                  // not the padding half tile of an odd count (no load in here)
           int hh = h + roth;
-          if (hh >= nh) hh -= nh;
-          const int r = hh * MS_HALF + 4 * g;          // rpw is a multiple of 8: the four rows stay inside the tile
-          if (li < M) {
-            floatx4* dst = reinterpret_cast<floatx4*>(otile + li * rpw + r);
-            *dst = ps == 0 ? acc0 : *dst + acc0;       // later pieces of the same wavefront, in piece order
-          }
+          hh = hh >= nh ? hh - nh : hh;                // this half tile's place in the range
           if constexpr (MT == 2) {
-            if (li == 0) {
-              floatx4* dst = reinterpret_cast<floatx4*>(otile + 16 * rpw + r);
-              *dst = ps == 0 ? acc1 : *dst + acc1;
+            // lane l ends with the whole-wavefront sum of weight row l / 8 of the half tile
+            const float v16 = reduce_lanes<MS_HALF>(s16, lane);
+            if ((lane & 7) == 0) {
+              float* dst = otile + 16 * rpw + hh * MS_HALF + (lane >> 3);
+              *dst = ps == 0 ? v16 : *dst + v16;
             }
+          }
+          // A operands: AHEAD LDS reads are requested before the first MFMA and one more with every MFMA, so that
+          // an MFMA never waits for the read issued just before it; two accumulators, so that consecutive MFMAs
+          // do not wait for each other's results either (even t, odd t; added at the end)
+          constexpr int AHEAD = 8;
+          floatx4 acc0[2] = {floatx4{0.f, 0.f, 0.f, 0.f}, floatx4{0.f, 0.f, 0.f, 0.f}};
+          uint4 f[16];
+#define SD_MS_READ(T) f[T] = *reinterpret_cast<const uint4*>(rd_row + (((4 * (T) + g) ^ li) << 4));
+#define SD_MS_MUL(T)                                                                                                 \
+          acc0[(T) & 1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ms_as_bf16x8(f[T]), ms_as_bf16x8(xb[T]), acc0[(T) & 1], \
+                                                                   0, 0, 0);
+#define SD_MS_STEP(T)                                             \
+          if constexpr ((T) + AHEAD < 16) { SD_MS_READ((T) + AHEAD) } \
+          SD_MS_MUL(T)                                            \
+          __builtin_amdgcn_sched_barrier(0);
+          SD_MS_READ(0) SD_MS_READ(1) SD_MS_READ(2) SD_MS_READ(3) SD_MS_READ(4) SD_MS_READ(5) SD_MS_READ(6)
+          SD_MS_READ(7)
+          __builtin_amdgcn_sched_barrier(0);
+          SD_MS_STEP(0) SD_MS_STEP(1) SD_MS_STEP(2) SD_MS_STEP(3) SD_MS_STEP(4) SD_MS_STEP(5) SD_MS_STEP(6)
+          SD_MS_STEP(7) SD_MS_STEP(8) SD_MS_STEP(9) SD_MS_STEP(10) SD_MS_STEP(11) SD_MS_STEP(12) SD_MS_STEP(13)
+          SD_MS_STEP(14) SD_MS_STEP(15)
+#undef SD_MS_STEP
+#undef SD_MS_MUL
+#undef SD_MS_READ
+          const floatx4 acc0s = acc0[0] + acc0[1];
+          // D[i][m]: lane (m = li, g) holds weight rows 4 g .. 4 g + 3 of the half tile (g < 2) for activation row m
+          if (g < 2 && li < M) {
+            // rpw is a multiple of 8: the four rows stay inside the wavefront's tile
+            floatx4* dst = reinterpret_cast<floatx4*>(otile + li * rpw + hh * MS_HALF + 4 * g);
+            *dst = ps == 0 ? acc0s : *dst + acc0s;     // later pieces of the same wavefront, in pass order
           }
         }
       }
     }
+    roth = rot_next;
   }
   stripe_finish<EPI, 3>(obuf, s_scale, sq, part, epi, M, N, cs, rpg, ranges, rpw);
 }

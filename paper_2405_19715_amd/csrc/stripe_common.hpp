@@ -1,4 +1,5 @@
-// The final sweep shared by the row-stripe GEMM kernels: every wavefront of a workgroup has left its partial sums
+// What the row-stripe GEMM kernels share: the vector-ALU dot product and the 64-lane butterfly of the few-row
+// kernel (the many-row kernel uses them for its 17th activation row), and the final sweep: every wavefront of a workgroup has left its partial sums
 // of one K stripe set in an LDS tile [M][rpw] (tile of wavefront w at obuf + w * M * rpw; the wavefronts of local
 // row range l are l * cs .. l * cs + cs - 1, in stripe order); the sweep adds the cs tiles of a range in that order
 // and does the elementwise work that follows the product in a decoder layer.
@@ -41,6 +42,76 @@ struct StripeEpi {
   bf16_t* vcache;          // [seq][Hkv][hd][max_seq]
   int Hq, Hkv, hshift, max_seq;
 };
+
+typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2;
+
+__device__ __forceinline__ float dot8(const uint4& w, const uint4& x, float c) {
+  union { uint32_t u; bf16x2 v; } a, b;
+  a.u = w.x; b.u = x.x; c = __builtin_amdgcn_fdot2_f32_bf16(a.v, b.v, c, false);
+  a.u = w.y; b.u = x.y; c = __builtin_amdgcn_fdot2_f32_bf16(a.v, b.v, c, false);
+  a.u = w.z; b.u = x.z; c = __builtin_amdgcn_fdot2_f32_bf16(a.v, b.v, c, false);
+  a.u = w.w; b.u = x.w; c = __builtin_amdgcn_fdot2_f32_bf16(a.v, b.v, c, false);
+  return c;
+}
+
+// Cross-lane sums without the LDS crossbar.  v_permlane32_swap (a, b) returns {a with its upper 32 lanes replaced
+// by b's lower 32, b with its lower 32 lanes replaced by a's upper 32}; v_permlane16_swap does the same with the
+// odd 16-lane rows of a and the even rows of b.  So for a pair of per-lane values (lo, hi), r = swap(lo, hi) and
+// r[0] + r[1] leaves, in the lanes whose OFF bit is clear, their own lo plus the partner's (lane ^ OFF) lo, and in
+// the lanes whose bit is set, their own hi plus the partner's hi: one exchange of a transposing butterfly.
+template <int OFF>
+__device__ __forceinline__ float swap_add(float lo, float hi) {
+  static_assert(OFF == 32 || OFF == 16, "row-crossing exchanges");
+  if constexpr (OFF == 32) {
+    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(lo), __float_as_uint(hi), false, false);
+    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+  } else {
+    const auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(lo), __float_as_uint(hi), false, false);
+    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+  }
+}
+
+template <int CTRL>
+__device__ __forceinline__ float dpp_move(float v) {
+  return __uint_as_float((uint32_t)__builtin_amdgcn_update_dpp(0, (int)__float_as_uint(v), CTRL, 0xF, 0xF, false));
+}
+constexpr int DPP_QUAD_XOR1 = 0xB1, DPP_QUAD_XOR2 = 0x4E, DPP_HALF_MIRROR = 0x141, DPP_ROR8 = 0x128;
+
+// N sums per lane become N / 2; lanes with bit OFF set keep the upper half.
+template <int N, int OFF>
+__device__ __forceinline__ void fold_stage(float* acc, int lane) {
+  constexpr int H = N / 2;
+  if constexpr (OFF >= 16) {
+#pragma unroll
+    for (int k = 0; k < H; ++k) acc[k] = swap_add<OFF>(acc[k], acc[k + H]);
+  } else {
+    static_assert(OFF == 8, "inside a 16-lane row only the 8-lane exchange is used");
+    const bool hi = (lane & 8) != 0;
+#pragma unroll
+    for (int k = 0; k < H; ++k) {
+      const float keep = hi ? acc[k + H] : acc[k];
+      const float send = hi ? acc[k] : acc[k + H];
+      acc[k] = keep + dpp_move<DPP_ROR8>(send);
+    }
+  }
+}
+
+// Sums P2 (a power of two <= 8) per-lane values over the 64 lanes; lane l ends with the total of value l / (64 / P2).
+template <int P2>
+__device__ __forceinline__ float reduce_lanes(float* acc, int lane) {
+  static_assert(P2 == 1 || P2 == 2 || P2 == 4 || P2 == 8, "power of two");
+  if constexpr (P2 == 8) { fold_stage<8, 32>(acc, lane); fold_stage<4, 16>(acc, lane); fold_stage<2, 8>(acc, lane); }
+  if constexpr (P2 == 4) { fold_stage<4, 32>(acc, lane); fold_stage<2, 16>(acc, lane); }
+  if constexpr (P2 == 2) { fold_stage<2, 32>(acc, lane); }
+  float v = acc[0];
+  if constexpr (P2 <= 1) v = swap_add<32>(v, v);
+  if constexpr (P2 <= 2) v = swap_add<16>(v, v);
+  if constexpr (P2 <= 4) v += dpp_move<DPP_ROR8>(v);
+  v += dpp_move<DPP_QUAD_XOR1>(v);
+  v += dpp_move<DPP_QUAD_XOR2>(v);
+  v += dpp_move<DPP_HALF_MIRROR>(v);
+  return v;
+}
 
 constexpr int STRIPE_SSQ_PER_LANE = 4;      // a consumer adds at most 4 * 64 = 256 per-workgroup sums of squares per row
 
