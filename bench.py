@@ -139,7 +139,7 @@ def _cpu_baseline(tgt, drf, k_mean, n_mean, P, k_max):
         toks = rng.integers(0, s.vocab, size=rows)
         # repeat the layer (rolling the cache back each time) until about `budget` seconds have gone by
         n_rep, t_all = 0, 0.0
-        while t_all < budget and n_rep < 200:
+        while n_rep == 0 or (t_all < budget and n_rep < 200):
             fw.truncate(P)
             t0 = time.perf_counter()
             logits, _ = fw.extend(toks)
@@ -156,16 +156,28 @@ def _cpu_baseline(tgt, drf, k_mean, n_mean, P, k_max):
     t_target, tl_t, lm_t = time_pass(tgt, k_max + 1, 6.0)
     t_draft, tl_d, lm_d = time_pass(drf, 1, 4.0)
     tps = (n_mean + 1.0) / (k_mean * t_draft + t_target)
+    # the same with ONE thread (the oracle's products are numpy's BLAS calls; the rest of it is single-threaded
+    # anyway): one repetition of each layer
+    one = None
+    try:
+        from threadpoolctl import threadpool_limits
+        with threadpool_limits(limits=1):
+            t1_target, _, _ = time_pass(tgt, k_max + 1, 0.0)
+            t1_draft, _, _ = time_pass(drf, 1, 0.0)
+        one = dict(value=(n_mean + 1.0) / (k_mean * t1_draft + t1_target), unit="tokens/s", cores=1,
+                   t_target_s=t1_target, t_draft_s=t1_draft, sample="one repetition of the same two layers")
+    except Exception as e:                                   # threadpoolctl missing: the all-thread figure stands alone
+        one = dict(error=str(e))
     return dict(value=tps, unit="tokens/s", cores=_blas_threads(), kind="oracle",
                 sample=(f"extrapolated (each layer repeated for ~6 s / ~4 s of CPU work, mean taken): 1 of {tgt['shape'].n_layers} target layers ({k_max + 1} rows, P={P}) "
                         f"{tl_t:.3f}s + LM head {lm_t:.3f}s -> t_target {t_target:.1f}s; 1 of "
                         f"{drf['shape'].n_layers} draft layers (1 row) {tl_d:.3f}s + LM head {lm_d:.3f}s -> "
                         f"t_draft {t_draft:.2f}s; tokens/s = (n+1)/(K*t_draft + t_target) with the GPU run's "
                         f"mean K={k_mean:.2f}, n={n_mean:.2f}"),
-                t_target_s=t_target, t_draft_s=t_draft)
+                t_target_s=t_target, t_draft_s=t_draft, one_thread=one)
 
 
-def _accept_bench(args):
+def _accept_bench(args, cases=None):
     """The isolated softmax + accept + residual-resample step (Algorithm 1's tail) on its own
     workload: vocab 32000, batch {1, 16, 64}, K in {1, 4, 8, 16}, target logits N(0, 2^2),
     draft = target + N(0, 0.5^2).  Algorithmic bytes per call: every live logits row once,
@@ -176,8 +188,8 @@ def _accept_bench(args):
     torch.cuda.set_device(0)
     V, rows = 32000, []
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    for nb in (1, 16, 64):
-        for K in (1, 4, 8, 16):
+    for nb, K in (cases or [(nb, K) for nb in (1, 16, 64) for K in (1, 4, 8, 16)]):
+        if True:
             # several input sets in rotation so that the 256 MB memory-side cache does not serve the rows
             n_sets = max(2, int(6e8 // (nb * (2 * K + 1) * V * 4)) + 1) if nb * K > 16 else 2
             n_sets = min(n_sets, 8)
@@ -204,16 +216,16 @@ def _accept_bench(args):
             print(f"accept B={nb:3d} K={K:2d}: {t * 1e6:8.1f} us  {nbytes / t / 1e9:8.1f} GB/s", file=sys.stderr, flush=True)
             del sets
     last = rows[-1]
-    print(json.dumps(dict(
+    return dict(
         metric="isolated accept / resample calls per second (vocab 32000, batch 64, K 16)", value=1e6 / last["us"],
         unit="calls/s", n_gpus=1, steps=args.steps, warmup=1, ms_per_step=last["us"] / 1e3, higher_is_better=True,
         scaling="weak", vs_baseline=None, dtype="f32", data="synthetic",
         config=dict(workload="isolated accept/resample: vocab 32000, target logits N(0,4), draft = target + N(0,0.25)",
                     top_k=args.top_k),
-        roofline=dict(bound="hbm", kernel="row_stats_k x2 + accept_k", achieved=last["GBs"], peak=HBM_PEAK_GBS,
+        roofline=dict(bound="hbm", kernel="row_stats_k + accept_k", achieved=last["GBs"], peak=HBM_PEAK_GBS,
                       unit="GB/s", frac=last["GBs"] / HBM_PEAK_GBS, traffic=None,
                       algorithmic_bytes_per_launch=last["bytes"]),
-        cpu_baseline=None, cases=rows)))
+        cpu_baseline=None, cases=rows)
 
 
 def _train_head(args, tgt, drf, head, shape, n_gen):
@@ -343,31 +355,36 @@ def _sweep(args):
         r = rows[-1]
         print(f"{mode:10s} K={K} h={h}: {r['tokens_per_s']:8.1f} tok/s  discard {r['discard_rate']:.3f}  "
               f"verify {r['verification_rate']:.3f}  mean K {r['mean_K']:.2f}", file=sys.stderr, flush=True)
-    # Sec. 4.1 (Theorem 1): in greedy mode a policy with hindsight stops right before every disagreement, so it
-    # discards nothing and calls the target once per disagreement (plus the calls the cap of 20 forces).  One
-    # greedy run with K = 20 reveals the run lengths n_i; the bound prices them with Eq. (1) and the measured
-    # per-call times of that same run.
+    # Sec. 4.1 (Theorem 1): with hindsight, greedy speculative decoding stops right before every position where the
+    # draft's greedy token, given the TARGET's own partial generation, differs from the target's: nothing is discarded
+    # and the target is called once per such position (plus once for what follows the last one).  X = the greedy
+    # tokens of a run of the rounds (they are the target's own), Y_i from teacher-forced draft rows (sd_forward on
+    # the draft over prompt, X_<i), S = {i : Y_i != X_i}; the bound prices N_draft = N - N_target draft steps and
+    # N_target target calls with Eq. (1) and the per-call times measured in that run.
     ctx = B.Context(tgt, drf, head, batch=1, max_seq=n_prompt + n_gen + 64, k_max=20)
     ctx.sd_prefill(0, prompt)
     gparams = B.make_params(h=1.0, greedy=True, seed=args.seed)
-    ctx.specdec_generate(gparams, 16)
-    n_acc, n_rounds, n_out = 0, 0, 0
-    t_d_sum = t_t_sum = 0.0
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    while n_out < n_gen:
-        r = ctx.specdec_round(gparams)[0]
-        n_acc += r["n"]
-        n_rounds += 1
-        n_out += r["n"] + 1
+    seqs, stg = ctx.specdec_generate(gparams, n_gen)
     torch.cuda.synchronize()
     dt_g = time.perf_counter() - t0
-    _, stg = ctx.specdec_generate(gparams, 32)
+    X = seqs[0]
+    ctx.sd_prefill(0, prompt)                                            # the draft cache back to the prompt
+    fed, Y = [prompt[-1]] + X[:-1], []
+    for s0 in range(0, len(X), 32):
+        Y += ctx.sd_forward(1, 0, n_prompt - 1 + s0, fed[s0:s0 + 32]).argmax(-1).tolist()
     ctx.close()
+    S = [i + 1 for i in range(len(X)) if Y[i] != X[i]]
+    n_target = len(S) + (0 if S and S[-1] == len(X) else 1)
+    n_draft = len(X) - n_target
     t_d, t_t = stg["t_draft_s"] / max(stg["N_draft"], 1), stg["t_target_s"] / stg["rounds"]
-    hindsight = dict(tokens=n_out, disagreements_plus_caps=n_rounds, N_draft=n_acc, N_target=n_rounds, N_discarded=0,
-                     measured_greedy_K20_tokens_per_s=n_out / dt_g,
-                     bound_tokens_per_s=n_out / (t_d * n_acc + t_t * n_rounds), t_draft_ms=t_d * 1e3, t_target_ms=t_t * 1e3)
+    hindsight = dict(tokens=len(X), disagreements=len(S), N_draft=n_draft, N_target=n_target, N_discarded=0,
+                     verification_rate=n_target / len(X),
+                     measured_greedy_K20=dict(tokens_per_s=len(X) / dt_g, N_target=stg["N_target"],
+                                              N_discarded=stg["N_discarded"]),
+                     bound_tokens_per_s=len(X) / (t_d * n_draft + t_t * n_target), t_draft_ms=t_d * 1e3,
+                     t_target_ms=t_t * 1e3)
     print(f"greedy hindsight bound: {hindsight}", file=sys.stderr, flush=True)
     best = max(rows, key=lambda r: r["tokens_per_s"])
     print(json.dumps(dict(
@@ -383,6 +400,235 @@ def _sweep(args):
         sweep=rows, greedy_hindsight=hindsight)))
 
 
+def _draft_step_bytes(shape, head_dims, P, esz=2):
+    """Bytes one draft step must move: every draft weight once, the draft's KV cache of P positions, the head."""
+    kv_token = 2 * shape.n_layers * shape.n_kv * esz
+    head = sum(a * b for a, b in zip(head_dims[:-1], head_dims[1:])) * esz
+    return shape.streamed_params() * esz + kv_token * P + head
+
+
+def _rates(K_list, n_list, seconds):
+    tok = sum(n + 1 for n in n_list)
+    return dict(tokens_per_s=tok / seconds, mean_K=sum(K_list) / len(K_list), mean_n=sum(n_list) / len(n_list),
+                discard_rate=(sum(K_list) - sum(n_list)) / tok, verification_rate=len(K_list) / tok)
+
+
+def _metric_label(name, nb):
+    shapes = {"paper": "70B/7B shape", "paper-aligned": "70B/7B shape, aligned synthetic weights", "mid": "7B/1.1B shape",
+              "batch8": "70B/7B shape"}[name]
+    if nb == 1:
+        return f"generated tokens/s (batch 1, {shapes}) + verify-pass HBM GB/s % of peak"
+    return f"generated tokens/s (batch {nb}, ragged prompts, whole batch, {shapes}) + verify-pass HBM GB/s % of peak"
+
+
+def _run_workload(name, args, steps, warmup, models=None, full=False, top_k=None, profile_every=None):
+    """One workload: build (or take) the pair, prefill, `warmup` untimed rounds, EXACTLY `steps` timed rounds between
+    synchronisations, phase times of those same rounds from the library's HIP events.  full = the headline's extras
+    (threshold sweep, pass time by row count, target-only decoding, the oracle on the host cores).
+    Returns (result dict, models) so that another workload on the same shapes can reuse the weights."""
+    import torch
+    from paper_2405_19715_amd import binding as B
+    from paper_2405_19715_amd import synth
+
+    wl = _workload(name)
+    dev = "cuda:0"
+    top_k = args.top_k if top_k is None else top_k
+    profile_every = args.profile_every if profile_every is None else profile_every
+    t_build = time.perf_counter()
+    if models is None:
+        tgt = synth.make_model(wl["target"], args.seed, device=dev, dtype=torch.bfloat16)
+        drf = synth.make_model(wl["draft"], args.seed + 1, device=dev, dtype=torch.bfloat16)
+        head = synth.make_head(wl["head"], args.seed + 2, device=dev, dtype=torch.bfloat16, residual=True)
+    else:
+        tgt, drf, head = models
+    if "align" in wl:
+        synth.align_narrow_draft(tgt, drf, *wl["align"])       # in place: this pair serves no other workload afterwards
+    torch.cuda.synchronize()
+    t_build = time.perf_counter() - t_build
+    nb = wl.get("batch", 1)
+    sweep_h = [h for h in (0.3, 0.5, 0.7, 0.9) if abs(h - args.h) > 1e-9] if (nb == 1 and full) else []
+    sweep_rounds, forced_rounds = 16, 6
+    max_seq = -(-(wl["prompt"] + wl["gen"] + (steps + warmup + 16 + forced_rounds + len(sweep_h) * sweep_rounds)
+                  * (wl["k_max"] + 1) + 2) // 64) * 64
+    lens = wl.get("prompts", [wl["prompt"]])
+    ctx = B.Context(tgt, drf, head, batch=nb, max_seq=max_seq, k_max=wl["k_max"])
+    prompts = [synth.make_prompt(lens[b], wl["target"].vocab, args.seed + 3 + b) for b in range(nb)]
+    ctx.sd_prefill(0, prompts[0][:8])                   # warm-up of the prompt-pass kernels, overwritten below
+    torch.cuda.synchronize()
+    t_prefill = time.perf_counter()
+    for b in range(nb):
+        ctx.sd_prefill(b, prompts[b])                   # untimed for the metric; reported on its own
+    torch.cuda.synchronize()
+    t_prefill = time.perf_counter() - t_prefill
+    rows = sum(lens) - nb
+    prefill_flops = 2.0 * rows * sum(sh.n_layers * sh.layer_params() for sh in (wl["target"], wl["draft"]))
+    params = B.make_params(h=args.h, temperature=1.0, greedy=False, seed=args.seed, top_k=top_k)
+
+    for _ in range(warmup):
+        ctx.specdec_round(params)
+    ctx.sd_profile_enable(profile_every)
+    ctx.sd_profile_read()
+    P0 = sum(ctx.sd_seq_state(b)["P"] for b in range(nb))
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    # the timed region: exactly `steps` rounds (each over the whole batch); the phase times of each round are read
+    # from the library after the round has ended (it ends with a synchronisation of its own)
+    Ks, ns, phases = [], [], []
+    for _ in range(steps):
+        for r in ctx.specdec_round(params):
+            Ks.append(r["K"])
+            ns.append(r["n"])
+        phases.append(ctx.sd_last_round_times())
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    prof = ctx.sd_profile_read()
+    ctx.sd_profile_enable(0)
+    n_tok = sum(n + 1 for n in ns)
+    k_mean, n_mean = sum(Ks) / len(Ks), sum(ns) / len(ns)
+    P_mid = (P0 + sum(ctx.sd_seq_state(b)["P"] for b in range(nb))) // 2      # summed over the batch
+    t_target = sum(p["t_target_s"] for p in phases) / steps
+    t_accept = sum(p["t_accept_s"] for p in phases) / steps
+    # draft steps of a round = the largest K of the batch in that round
+    draft_steps = [max(Ks[i * nb:(i + 1) * nb]) for i in range(steps)]
+    t_draft = sum(p["t_draft_s"] for p in phases) / max(sum(draft_steps), 1)
+    rows_mean = sum(p["target_rows"] for p in phases) / steps
+
+    def vbytes(P_sum, K):
+        return _algorithmic_bytes_verify(wl["target"], P_sum, K, batch=nb)
+
+    def bucket(samples, P_sum):          # samples: (rows, seconds) of target passes with one sequence
+        if not samples:
+            return None
+        r = sum(a for a, _ in samples) / len(samples)
+        sec = sum(b for _, b in samples) / len(samples)
+        nbytes = vbytes(P_sum, r - 1)
+        return dict(passes=len(samples), mean_rows=r, ms=sec * 1e3, achieved_GBs=nbytes / sec / 1e9,
+                    frac=nbytes / sec / 1e9 / HBM_PEAK_GBS)
+
+    h_table, by_rows, t_ar, cpu = None, None, None, None
+    if full and nb == 1:
+        # the other thresholds of the paper's sweep (Sec. 5.1), a few rounds each on the same context
+        h_table = [dict(h=args.h, rounds=steps, **_rates(Ks, ns, dt))]
+        samples = [(p["target_rows"], p["t_target_s"]) for p in phases]
+        for hh in sweep_h:
+            ph = B.make_params(h=hh, temperature=1.0, greedy=False, seed=args.seed, top_k=top_k)
+            torch.cuda.synchronize()
+            th = time.perf_counter()
+            got = []
+            for _ in range(sweep_rounds):
+                got.append(ctx.specdec_round(ph)[0])
+                p = ctx.sd_last_round_times()
+                samples.append((p["target_rows"], p["t_target_s"]))
+            torch.cuda.synchronize()
+            h_table.append(dict(h=hh, rounds=sweep_rounds,
+                                **_rates([g["K"] for g in got], [g["n"] for g in got], time.perf_counter() - th)))
+        h_table.sort(key=lambda e: e["h"])
+        # the target pass by row count: K+1 = 17 rows forced with h = 1 (every round drafts K_max candidates),
+        # a 12-row pass on a context whose cap is 11 candidates; the rest from the rounds above
+        p1 = B.make_params(h=1.0, temperature=1.0, greedy=False, seed=args.seed, top_k=top_k)
+        ctx.specdec_round(p1)
+        for _ in range(forced_rounds - 1):
+            ctx.specdec_round(p1)
+            p = ctx.sd_last_round_times()
+            samples.append((p["target_rows"], p["t_target_s"]))
+        c12 = B.Context(tgt, drf, head, batch=1, max_seq=-(-(wl["prompt"] + 8 * 12 + 2) // 64) * 64, k_max=11)
+        c12.sd_prefill(0, prompts[0])
+        c12.specdec_round(p1)
+        for _ in range(forced_rounds - 1):
+            c12.specdec_round(p1)
+            p = c12.sd_last_round_times()
+            samples.append((p["target_rows"], p["t_target_s"]))
+        c12.close()
+        by_rows = {"1-8": bucket([x for x in samples if x[0] <= 8], P_mid),
+                   "9-16": bucket([x for x in samples if 9 <= x[0] <= 16], P_mid),
+                   "17": bucket([x for x in samples if x[0] == 17], P_mid)}
+        # target-only decoding on the same context (what the paper's speedups are measured against, Sec. 5.1):
+        # one target forward of one row per token; its logits row comes back to the host like a sampler would
+        # need it.  Last use of the context: the rows it writes replace the target cache's tail.
+        seq_len = ctx.sd_seq_state(0)["P"]
+        ctx.sd_forward(0, 0, seq_len - 1, [1])
+        torch.cuda.synchronize()
+        ta = time.perf_counter()
+        for j in range(8):
+            ctx.sd_forward(0, 0, seq_len - 1 + j, [1])
+        torch.cuda.synchronize()
+        t_ar = (time.perf_counter() - ta) / 8
+
+    tot_b = sum(v["weight_bytes"] for v in prof.values())
+    tot_s = sum(v["seconds"] for v in prof.values())
+    tot_n = sum(v["launches"] for v in prof.values())
+    L = wl["target"].n_layers
+    counts = dict(qkv=L, o=L, gate_up=L, down=L, lm_head=1)
+    est_avg_us = None
+    if all(prof[k]["launches"] for k in counts):
+        est_avg_us = sum(counts[k] * prof[k]["seconds"] / prof[k]["launches"] for k in counts) / sum(counts.values()) * 1e6
+    achieved = tot_b / tot_s / 1e9 if tot_s > 0 else None
+    verify_bytes = vbytes(P_mid, k_mean)
+    draft_bytes = _draft_step_bytes(wl["draft"], wl["head"], P_mid)        # P_mid: positions summed over the batch
+    kernel = ("weight-streaming GEMMs of the target pass with their fused sweeps: gemm_bf16_stripe<M> (K+1 <= 8 rows, "
+              "vector-ALU dot products) and gemm_bf16_mstripe (9..17 rows, matrix cores on LDS-transposed half tiles)"
+              if rows_mean <= 17.5 else
+              "gemm_bf16_tile<2,1,..> / <2,2,..> (target pass of the batch, M = sum of K_b+1 rows packed in groups "
+              "of 4: one 128x64 or 128x128 m-tile holds every row, so each weight is read once)")
+    traffic = _measured_traffic() if name == "paper" else None
+    roofline = dict(bound="hbm", kernel=kernel, achieved=achieved, peak=HBM_PEAK_GBS, unit="GB/s",
+                    frac=(achieved / HBM_PEAK_GBS) if achieved else None, traffic=traffic,
+                    traffic_source=("profiles/gemm_traffic_paper_workload.txt: rocprofv3 --pmc FETCH_SIZE + WRITE_SIZE of "
+                                    "this workload's GEMM launches, collected separately, not in this run") if traffic else None,
+                    algorithmic_bytes_per_launch=(tot_b / tot_n) if tot_n else None,
+                    sampled_launches=tot_n, avg_launch_us=est_avg_us,
+                    per_matrix_GBs={k: (v["weight_bytes"] / v["seconds"] / 1e9 if v["seconds"] > 0 else None)
+                                    for k, v in prof.items()},
+                    verify_pass=dict(algorithmic_bytes=verify_bytes, seconds=t_target, mean_rows=rows_mean,
+                                     achieved_GBs=verify_bytes / t_target / 1e9,
+                                     frac=verify_bytes / t_target / 1e9 / HBM_PEAK_GBS),
+                    verify_pass_by_rows=by_rows,
+                    draft_step=dict(algorithmic_bytes=draft_bytes, seconds=t_draft, achieved_GBs=draft_bytes / t_draft / 1e9,
+                                    frac=draft_bytes / t_draft / 1e9 / HBM_PEAK_GBS))
+    if full:
+        box = _measured_stream_GBs()
+        roofline["measured_stream"] = dict(box, frac_of_copy=(achieved / box["copy_GBs"]) if achieved else None,
+                                           frac_of_read=(achieved / box["read_GBs"]) if achieved else None)
+        if not args.no_cpu_baseline and nb == 1:
+            cpu = _cpu_baseline(tgt, drf, k_mean, n_mean, wl["prompt"], wl["k_max"])
+    out = dict(metric=_metric_label(name, nb),
+               value=n_tok / dt, unit="tokens/s", n_gpus=1, steps=steps, warmup=warmup,
+               ms_per_step=dt / steps * 1e3, higher_is_better=True, scaling="weak", vs_baseline=None,
+               dtype="bf16", data="synthetic",
+               config=dict(workload=wl["label"], h=args.h, temperature=1.0, top_k=top_k, mean_K=k_mean, mean_n=n_mean,
+                           discard_rate=(sum(Ks) - sum(ns)) / n_tok, verification_rate=len(Ks) / n_tok,
+                           t_draft_ms=t_draft * 1e3, t_target_ms=t_target * 1e3, t_accept_ms=t_accept * 1e3,
+                           eq4_tokens_per_s=1.0 / (t_draft + t_draft * (sum(Ks) - sum(ns)) / n_tok
+                                                   + (t_target - t_draft) * len(Ks) / n_tok),
+                           h_sweep=h_table,
+                           target_only_tokens_per_s=(1.0 / t_ar) if t_ar else None,
+                           speedup_vs_target_only=(n_tok / dt * t_ar) if t_ar else None,
+                           weights_init_s=t_build,
+                           prompt_pass=dict(seconds=t_prefill, rows=rows, gemm_tflops=prefill_flops / t_prefill / 1e12,
+                                            frac_of_bf16_mfma_peak=prefill_flops / t_prefill / 2.5e15)),
+               roofline=roofline, cpu_baseline=cpu)
+    if full:
+        out["config"]["paper_context"] = (
+            "the paper reports 2.04x-2.26x over target-only decoding with llama-2-chat 7B/70B, bf16, on 2 x A100-80G "
+            "(Sec. 5.2): context only, a random-init pair is unaligned (few candidates are accepted), so no speedup is "
+            "expected on it; configs.paper_aligned runs the same shapes with weights arranged so that the draft predicts "
+            "the target, bench.py --sweep --learnable a synthetic pair on which the head helps")
+    ctx.close()
+    return out, (tgt, drf, head)
+
+
+def _brief(r):
+    """What a secondary configuration contributes to the headline's JSON line."""
+    c, rf = r["config"], r["roofline"]
+    return dict(workload=c["workload"], value=r["value"], unit=r["unit"], steps=r["steps"], ms_per_step=r["ms_per_step"],
+                h=c["h"], top_k=c["top_k"], mean_K=c["mean_K"], mean_n=c["mean_n"], discard_rate=c["discard_rate"],
+                verification_rate=c["verification_rate"], t_draft_ms=c["t_draft_ms"], t_target_ms=c["t_target_ms"],
+                t_accept_ms=c["t_accept_ms"],
+                roofline=dict(bound="hbm", kernel=rf["kernel"], achieved=rf["achieved"], peak=rf["peak"], unit="GB/s",
+                              frac=rf["frac"], algorithmic_bytes_per_launch=rf["algorithmic_bytes_per_launch"],
+                              avg_launch_us=rf["avg_launch_us"], verify_pass=rf["verify_pass"], draft_step=rf["draft_step"]))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -392,6 +638,9 @@ def main():
     ap.add_argument("--h", type=float, default=0.7)
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-configs", action="store_true",
+                    help="paper workload only: leave out the secondary configurations (isolated accept step, 7B/1.1B pair, "
+                         "batch of 8, aligned pair, top-k 50) that the default run adds under `configs`")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="first run four 1 GiB device-to-device copies (a kernel of known traffic, to scale "
                          "rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
@@ -424,165 +673,41 @@ def main():
             args.hard_frac, args.hard_c, args.align_std, args.head_layers = 0.3, 1.0, 0.0005, 0
             args.train_head, args.train_epochs, args.lr, args.sweep_tokens = 48, 30, 1e-3, 384
         return _sweep(args)
-    if args.workload == "accept":
-        return _accept_bench(args)
-
     import torch
-    from paper_2405_19715_amd import binding as B
-    from paper_2405_19715_amd import synth
-
-    wl = _workload(args.workload)
-    dev = "cuda:0"
     torch.cuda.set_device(0)
+    if args.workload == "accept":
+        print(json.dumps(_accept_bench(args)))
+        return
     if args.calibrate_copy:
-        a = torch.ones(1 << 30, dtype=torch.uint8, device=dev)
+        a = torch.ones(1 << 30, dtype=torch.uint8, device="cuda:0")
         b = torch.empty_like(a)
         for _ in range(4):
             b.copy_(a)
         torch.cuda.synchronize()
         del a, b
-    t_build = time.perf_counter()
-    tgt = synth.make_model(wl["target"], args.seed, device=dev, dtype=torch.bfloat16)
-    drf = synth.make_model(wl["draft"], args.seed + 1, device=dev, dtype=torch.bfloat16)
-    head = synth.make_head(wl["head"], args.seed + 2, device=dev, dtype=torch.bfloat16, residual=True)
-    if "align" in wl:
-        synth.align_narrow_draft(tgt, drf, *wl["align"])
-    torch.cuda.synchronize()
-    t_build = time.perf_counter() - t_build
-    nb = wl.get("batch", 1)
-    sweep_h = [h for h in (0.3, 0.5, 0.7, 0.9) if abs(h - args.h) > 1e-9] if nb == 1 else []
-    sweep_rounds = 16
-    max_seq = -(-(wl["prompt"] + wl["gen"] + (args.steps + args.warmup + 16 + len(sweep_h) * sweep_rounds)
-                  * (wl["k_max"] + 1) + 2) // 64) * 64
-    lens = wl.get("prompts", [wl["prompt"]])
-    ctx = B.Context(tgt, drf, head, batch=nb, max_seq=max_seq, k_max=wl["k_max"])
-    prompts = [synth.make_prompt(lens[b], wl["target"].vocab, args.seed + 3 + b) for b in range(nb)]
-    ctx.sd_prefill(0, prompts[0][:8])                   # warm-up of the prompt-pass kernels, overwritten below
-    torch.cuda.synchronize()
-    t_prefill = time.perf_counter()
-    for b in range(nb):
-        ctx.sd_prefill(b, prompts[b])                   # untimed for the metric; reported on its own
-    torch.cuda.synchronize()
-    t_prefill = time.perf_counter() - t_prefill
-    rows = sum(lens) - nb
-    prefill_flops = 2.0 * rows * sum(sh.n_layers * sh.layer_params() for sh in (wl["target"], wl["draft"]))
-    params = B.make_params(h=args.h, temperature=1.0, greedy=False, seed=args.seed, top_k=args.top_k)
-
-    for _ in range(args.warmup):
-        ctx.specdec_round(params)
-    ctx.sd_profile_enable(args.profile_every)
-    ctx.sd_profile_read()
-    P0 = sum(ctx.sd_seq_state(b)["P"] for b in range(nb))
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    # the timed region: exactly `steps` rounds (each over the whole batch)
-    Ks, ns = [], []
-    for _ in range(args.steps):
-        for r in ctx.specdec_round(params):
-            Ks.append(r["K"])
-            ns.append(r["n"])
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
-    prof = ctx.sd_profile_read()
-    ctx.sd_profile_enable(0)
-    n_tok = sum(n + 1 for n in ns)
-    k_mean, n_mean = sum(Ks) / len(Ks), sum(ns) / len(ns)
-    P_mid = (P0 + sum(ctx.sd_seq_state(b)["P"] for b in range(nb))) // 2      # summed over the batch
-
-    # phase times of a few more rounds (events inside the library, same stream)
-    _, st2 = ctx.specdec_generate(params, max(8, 4 * int(n_mean + 1)))
-    t_target = st2["t_target_s"] / st2["rounds"]
-    t_draft = st2["t_draft_s"] / max(st2["N_draft"], 1)
-    t_accept = st2["t_accept_s"] / st2["rounds"]
-
-    # the other thresholds of the paper's sweep (Sec. 5.1), a few rounds each on the same context: rates and tokens/s
-    def _rates(K_list, n_list, seconds):
-        tok = sum(n + 1 for n in n_list)
-        return dict(tokens_per_s=tok / seconds, mean_K=sum(K_list) / len(K_list), mean_n=sum(n_list) / len(n_list),
-                    discard_rate=(sum(K_list) - sum(n_list)) / tok, verification_rate=len(K_list) / tok)
-    h_table = [dict(h=args.h, rounds=args.steps, **_rates(Ks, ns, dt))]
-    for hh in sweep_h:
-        ph = B.make_params(h=hh, temperature=1.0, greedy=False, seed=args.seed, top_k=args.top_k)
-        torch.cuda.synchronize()
-        th = time.perf_counter()
-        got = [ctx.specdec_round(ph)[0] for _ in range(sweep_rounds)]
-        torch.cuda.synchronize()
-        h_table.append(dict(h=hh, rounds=sweep_rounds,
-                            **_rates([g["K"] for g in got], [g["n"] for g in got], time.perf_counter() - th)))
-    h_table.sort(key=lambda e: e["h"])
-
-    # target-only decoding on the same context (what the paper's speedups are measured against, Sec. 5.1):
-    # one target forward of one row per token; its logits row comes back to the host like a sampler would need it.
-    # Last use of the context: the rows it writes replace the target cache's tail.
-    t_ar = None
-    if nb == 1:
-        seq_len = ctx.sd_seq_state(0)["P"]
-        tok = 1
-        ctx.sd_forward(0, 0, seq_len - 1, [tok])
-        torch.cuda.synchronize()
-        ta = time.perf_counter()
-        for j in range(8):
-            ctx.sd_forward(0, 0, seq_len - 1 + j, [tok])
-        torch.cuda.synchronize()
-        t_ar = (time.perf_counter() - ta) / 8
-
-
-    tot_b = sum(v["weight_bytes"] for v in prof.values())
-    tot_s = sum(v["seconds"] for v in prof.values())
-    tot_n = sum(v["launches"] for v in prof.values())
-    counts = dict(qkv=wl["target"].n_layers, o=wl["target"].n_layers, gate_up=wl["target"].n_layers,
-                  down=wl["target"].n_layers, lm_head=1)
-    est_avg_us = None
-    if all(prof[k]["launches"] for k in counts):
-        est_avg_us = sum(counts[k] * prof[k]["seconds"] / prof[k]["launches"] for k in counts) / sum(counts.values()) * 1e6
-    achieved = tot_b / tot_s / 1e9 if tot_s > 0 else None
-    verify_bytes = _algorithmic_bytes_verify(wl["target"], P_mid, wl["k_max"], batch=nb)
-    rows_pass = nb * (k_mean + 1)
-    kernel = ("weight-streaming GEMMs of the target pass: gemm_bf16_stripe<M> (q|k|v, o, gate|up, LM head with M = K+1 <= 8 "
-              "rows) and gemm_bf16_stream<1> (down; all five matrices with 9..16 rows; 17 rows take the tiled kernel)"
-              if rows_pass <= 32 else
-              "gemm_bf16_tile<2,1,..> / <2,2,..> (target pass of the batch, M = sum of K_b+1 rows packed in groups "
-              "of 4: one 128x64 or 128x128 m-tile holds every row, so each weight is read once)")
-    roofline = dict(bound="hbm", kernel=kernel,
-                    achieved=achieved, peak=HBM_PEAK_GBS, unit="GB/s",
-                    frac=(achieved / HBM_PEAK_GBS) if achieved else None,
-                    traffic=_measured_traffic() if args.workload == "paper" else None,
-                    algorithmic_bytes_per_launch=(tot_b / tot_n) if tot_n else None,
-                    sampled_launches=tot_n, avg_launch_us=est_avg_us,
-                    per_matrix_GBs={k: (v["weight_bytes"] / v["seconds"] / 1e9 if v["seconds"] > 0 else None)
-                                    for k, v in prof.items()},
-                    verify_pass=dict(algorithmic_bytes=verify_bytes, seconds=t_target,
-                                     achieved_GBs=verify_bytes / t_target / 1e9,
-                                     frac=verify_bytes / t_target / 1e9 / HBM_PEAK_GBS))
-    box = _measured_stream_GBs()
-    roofline["measured_stream"] = dict(box, frac_of_copy=(achieved / box["copy_GBs"]) if achieved else None,
-                                       frac_of_read=(achieved / box["read_GBs"]) if achieved else None)
-    cpu = None
-    if not args.no_cpu_baseline and nb == 1:
-        cpu = _cpu_baseline(tgt, drf, k_mean, n_mean, wl["prompt"], wl["k_max"])
-    metric = ("generated tokens/s (batch 1, 70B/7B shape) + verify-pass HBM GB/s % of peak" if nb == 1 else
-              f"generated tokens/s (batch {nb}, ragged prompts, whole batch) + verify-pass HBM GB/s % of peak")
-    out = dict(metric=metric,
-               value=n_tok / dt, unit="tokens/s", n_gpus=1, steps=args.steps, warmup=args.warmup,
-               ms_per_step=dt / args.steps * 1e3, higher_is_better=True, scaling="weak", vs_baseline=None,
-               dtype="bf16", data="synthetic",
-               config=dict(workload=wl["label"], h=args.h, temperature=1.0, top_k=args.top_k, mean_K=k_mean, mean_n=n_mean,
-                           discard_rate=(sum(Ks) - sum(ns)) / n_tok, verification_rate=len(Ks) / n_tok,
-                           t_draft_ms=t_draft * 1e3, t_target_ms=t_target * 1e3, t_accept_ms=t_accept * 1e3,
-                           eq4_tokens_per_s=1.0 / (t_draft + t_draft * (sum(Ks) - sum(ns)) / n_tok
-                                                   + (t_target - t_draft) * len(Ks) / n_tok),
-                           h_sweep=h_table if nb == 1 else None,
-                           target_only_tokens_per_s=(1.0 / t_ar) if t_ar else None,
-                           speedup_vs_target_only=(n_tok / dt * t_ar) if t_ar else None,
-                           paper_context="the paper reports 2.04x-2.26x over target-only decoding with llama-2-chat "
-                                         "7B/70B, bf16, on 2 x A100-80G (Sec. 5.2): context only, a random-init pair "
-                                         "is unaligned (few candidates are accepted), so no speedup is expected here; "
-                                         "bench.py --sweep --learnable runs a synthetic pair on which the head helps",
-                           weights_init_s=t_build,
-                           prompt_pass=dict(seconds=t_prefill, rows=rows, gemm_tflops=prefill_flops / t_prefill / 1e12,
-                                            frac_of_bf16_mfma_peak=prefill_flops / t_prefill / 2.5e15)),
-               roofline=roofline, cpu_baseline=cpu)
-    ctx.close()
+    out, models = _run_workload(args.workload, args, args.steps, args.warmup, full=True)
+    if args.workload == "paper" and not args.no_configs:
+        # the other configurations of the benchmark, shorter, in the same process and JSON line
+        few = max(4, min(args.steps, 24))
+        cfgs = {}
+        r, _ = _run_workload("paper", args, few, 2, models=models, top_k=50, profile_every=0)
+        cfgs["top_k50"] = _brief(r)
+        r, _ = _run_workload("batch8", args, max(4, min(args.steps, 16)), 2, models=models)
+        cfgs["batch8"] = _brief(r)
+        r, _ = _run_workload("paper-aligned", args, max(4, min(args.steps, 32)), 2, models=models)   # rearranges the weights
+        cfgs["paper_aligned"] = _brief(r)
+        cfgs["paper_aligned"]["speedup_vs_target_only_of_the_random_init_run"] = (
+            r["value"] / out["config"]["target_only_tokens_per_s"] if out["config"]["target_only_tokens_per_s"] else None)
+        del models, r
+        torch.cuda.empty_cache()
+        r, m2 = _run_workload("mid", args, max(4, min(args.steps, 32)), 2)
+        cfgs["mid"] = _brief(r)
+        del m2, r
+        torch.cuda.empty_cache()
+        a = _accept_bench(argparse.Namespace(seed=args.seed, top_k=0, steps=16), cases=[(1, 16), (16, 16), (64, 1), (64, 16)])
+        cfgs["accept"] = dict(workload=a["config"]["workload"], value=a["value"], unit=a["unit"], ms_per_step=a["ms_per_step"],
+                              roofline=a["roofline"], cases=a["cases"])
+        out["configs"] = cfgs
     print(json.dumps(out))
 
 

@@ -196,6 +196,14 @@ sd_status sd_accept_resample_static(const float *p_logits_dev, const float *q_lo
                                     int32_t *n_out_dev, int32_t *tok_out_dev,
                                     uint8_t *accept_flags_dev, int32_t **status_word_dev_out);
 
+/* Phase times of the most recent specdec_round / round of specdec_generate on this
+ * context, measured with HIP events on the context's stream (the decomposition of
+ * Sec. 3.2 / Eq. 1 needs per-forward times): seconds[0] = the draft loop, [1] = the
+ * target pass over the K+1 positions, [2] = accept / resample + commit.  HOST array of
+ * 3.  target_rows (may be NULL) receives the activation rows that target pass carried
+ * (K+1 for one sequence; the packed row slots of a batch).  Zeros before the first round. */
+sd_status sd_last_round_times(sd_ctx *ctx, double *seconds, int32_t *target_rows);
+
 /* Teacher-forced forward for parity checks and timing: ingest `n` tokens (HOST
  * ids) of sequence `seq` into model `which` (0 = target, 1 = draft) at cache
  * positions start .. start+n-1 (start <= that cache's current length; later

@@ -76,6 +76,7 @@ _PROTOS = {
                                               C.c_void_p, C.c_void_p, C.POINTER(C.c_void_p)]),
     "sd_forward": (C.c_int32, [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, _i32p, C.c_int32, _f32p, _f32p]),
     "sd_seq_state": (C.c_int32, [C.c_void_p, C.c_int32, _i32p, _i32p, _i32p, _i32p]),
+    "sd_last_round_times": (C.c_int32, [C.c_void_p, C.POINTER(C.c_double), _i32p]),
     "sd_last_round_rows": (C.c_int32, [C.c_void_p, C.c_int32, _f32p, _f32p, _f32p]),
     "sd_profile_enable": (C.c_int32, [C.c_void_p, C.c_int32]),
     "sd_profile_read": (C.c_int32, [C.c_void_p, C.POINTER(C.c_int64), C.POINTER(C.c_double), C.POINTER(C.c_double)]),
@@ -226,6 +227,12 @@ class Context:
         v = [C.c_int32() for _ in range(4)]
         _check(lib.sd_seq_state(self.handle, seq, *[C.byref(x) for x in v]), "sd_seq_state")
         return dict(P=v[0].value, kv_len_target=v[1].value, kv_len_draft=v[2].value, round=v[3].value)
+
+    def sd_last_round_times(self) -> dict:
+        t = (C.c_double * 3)()
+        rows = C.c_int32()
+        _check(lib.sd_last_round_times(self.handle, t, C.byref(rows)), "sd_last_round_times")
+        return dict(t_draft_s=t[0], t_target_s=t[1], t_accept_s=t[2], target_rows=rows.value)
 
     def sd_last_round_rows(self, seq: int, K: int):
         q = torch.empty((K, self.vocab), dtype=torch.float32)

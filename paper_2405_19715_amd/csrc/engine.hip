@@ -83,6 +83,8 @@ struct sd_ctx {
   std::vector<int> P, kv_t, kv_d, round, active;
 
   hipEvent_t ev[4]{};
+  double last_phase_s[3]{};       // draft loop, target pass, accept + commit of the most recent round
+  int last_rows = 0;              // row slots of the most recent target pass
   int prof_every = 0;
   int prof_pass = 0;              // profiled target passes since sd_profile_enable: rotates the sampled layers
   std::vector<ProfSample> prof_pool;
@@ -635,12 +637,14 @@ static sd_status round_impl(sd_ctx* c, const sd_params* params, sd_round_out* ou
     if (c->active[b]) n_groups += ((k_seq[b] ? k_seq[b] : k_round) + RAGGED_RS) / RAGGED_RS;
   if (B > 1 && n_groups * RAGGED_RS < B * rs && n_groups * RAGGED_RS <= MAX_ROWS) {
     const int Mv = n_groups * RAGGED_RS;
+    c->last_rows = Mv;
     SD_HIP(launch_plan_verify_ragged(st, c->s, c->rows, B, RAGGED_RS, n_groups, k_max, max_seq, c->lm_dst));
     if ((s = forward(c, c->target, Mv, RAGGED_RS, std::min(max_seq, maxP + k_round), nullptr, Mv, c->p_logits,
                      RAGGED_RS, 0, V, true, false, c->lm_dst)) != SD_OK)
       return s;
   } else {
     const int Mv = B * rs;
+    c->last_rows = Mv;
     SD_HIP(launch_plan_verify(st, c->s, c->rows, B, rs, max_seq));
     if ((s = forward(c, c->target, Mv, rs, std::min(max_seq, maxP + k_round), nullptr, Mv, c->p_logits, rs,
                      (int64_t)(k_max + 1) * V, V, true)) != SD_OK)
@@ -683,11 +687,14 @@ static sd_status round_impl(sd_ctx* c, const sd_params* params, sd_round_out* ou
       std::memcpy(&o.p_hat, &r[3], 4);
     }
   }
-  if (stats) {
+  for (int k = 0; k < 3; ++k) {
     float ms = 0.f;
-    if (hipEventElapsedTime(&ms, c->ev[0], c->ev[1]) == hipSuccess) stats->t_draft_s += ms * 1e-3;
-    if (hipEventElapsedTime(&ms, c->ev[1], c->ev[2]) == hipSuccess) stats->t_target_s += ms * 1e-3;
-    if (hipEventElapsedTime(&ms, c->ev[2], c->ev[3]) == hipSuccess) stats->t_accept_s += ms * 1e-3;
+    c->last_phase_s[k] = hipEventElapsedTime(&ms, c->ev[k], c->ev[k + 1]) == hipSuccess ? ms * 1e-3 : 0.0;
+  }
+  if (stats) {
+    stats->t_draft_s += c->last_phase_s[0];
+    stats->t_target_s += c->last_phase_s[1];
+    stats->t_accept_s += c->last_phase_s[2];
   }
   return nonfinite ? SD_ENONFINITE : SD_OK;
 }
@@ -917,6 +924,13 @@ sd_status sd_seq_state(sd_ctx* c, int32_t seq, int32_t* P, int32_t* kv_t, int32_
   if (kv_t) *kv_t = c->kv_t[seq];
   if (kv_d) *kv_d = c->kv_d[seq];
   if (round_idx) *round_idx = c->round[seq];
+  return SD_OK;
+}
+
+sd_status sd_last_round_times(sd_ctx* c, double* seconds, int32_t* target_rows) {
+  if (!c || !seconds) return SD_EINVAL;
+  for (int k = 0; k < 3; ++k) seconds[k] = c->last_phase_s[k];
+  if (target_rows) *target_rows = c->last_rows;
   return SD_OK;
 }
 

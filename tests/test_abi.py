@@ -42,17 +42,23 @@ def test_host_side_argument_checks_need_no_gpu():
     assert B.lib.sd_accept_workspace_bytes(4, 16) == 4 * 33 * 16 + 16
     assert B.lib.sd_gemm_workspace_bytes(B.SD_BF16, 17, 8192, 8192) % (17 * 8192 * 4) == 0
     assert B.lib.sd_gemm_workspace_bytes(B.SD_BF16, 500, 8192, 8192) == 0
-    # the gated activation's one-launch kernel: up to 8 rows, K a multiple of 2048 up to 8192
+    # the gated activation's one-launch kernel: up to 8 rows with K a multiple of 2048 up to 8192, 9 .. 17 rows
+    # with K a multiple of 512
     assert B.lib.sd_mlp_act_is_fused(B.SD_BF16, 1, 28672, 8192) == 1
     assert B.lib.sd_mlp_act_is_fused(B.SD_BF16, 8, 11008, 4096) == 1
-    assert B.lib.sd_mlp_act_is_fused(B.SD_BF16, 9, 28672, 8192) == 0
+    assert B.lib.sd_mlp_act_is_fused(B.SD_BF16, 9, 28672, 8192) == 1
+    assert B.lib.sd_mlp_act_is_fused(B.SD_BF16, 17, 28672, 8192) == 1
+    assert B.lib.sd_mlp_act_is_fused(B.SD_BF16, 18, 28672, 8192) == 0
+    assert B.lib.sd_mlp_act_is_fused(B.SD_BF16, 12, 28672, 8192 + 128) == 0
     assert B.lib.sd_mlp_act_is_fused(B.SD_BF16, 4, 512, 16384) == 0
     assert B.lib.sd_mlp_act_is_fused(B.SD_F32, 1, 688, 256) == 0
     assert B.lib.sd_mlp_act(B.SD_BF16, None, None, 1, 8, 128, None, None, -1, None) == B.SD_EINVAL
     # the q|k|v product that rotates and appends: the same row limits, head dimension a power of two
     assert B.lib.sd_qkv_rope_is_fused(B.SD_BF16, 8, 64, 8, 128, 8192) == 1
     assert B.lib.sd_qkv_rope_is_fused(B.SD_BF16, 1, 32, 32, 128, 4096) == 1
-    assert B.lib.sd_qkv_rope_is_fused(B.SD_BF16, 9, 64, 8, 128, 8192) == 0
+    assert B.lib.sd_qkv_rope_is_fused(B.SD_BF16, 9, 64, 8, 128, 8192) == 1
+    assert B.lib.sd_qkv_rope_is_fused(B.SD_BF16, 17, 64, 8, 128, 8192) == 1
+    assert B.lib.sd_qkv_rope_is_fused(B.SD_BF16, 18, 64, 8, 128, 8192) == 0
     assert B.lib.sd_qkv_rope_is_fused(B.SD_BF16, 2, 8, 2, 96, 2048) == 0
     assert B.lib.sd_qkv_rope_is_fused(B.SD_BF16, 2, 8, 2, 64, 1024) == 0
     assert B.lib.sd_qkv_rope_is_fused(B.SD_F32, 2, 8, 2, 64, 2048) == 0
