@@ -18,6 +18,7 @@ namespace {
 constexpr int SB = 1024;            // threads of the vocab-wide kernels
 constexpr int CAND_LD = 32;         // row stride of the per-sequence candidate arrays
 constexpr int RES_LD = 40;          // ints per sequence in the packed round result
+constexpr float LOG2E = 1.44269504088896340736f;
 
 struct ArgMax { float v; int i; };
 
@@ -375,17 +376,155 @@ __global__ __launch_bounds__(SB) void sample_stop_k(SeqState s, const float* __r
 }
 
 // ------------------------------------------------------------------ softmax statistics per row
-// stats[row] = {max, sum_v exp((l_v - max)/T), argmax (int bits), top-k threshold or -inf}.
+// stats[row] = {max, sum_v w_v, argmax (int bits), top-k threshold or -inf}, w_v = exp((l_v - max)/T) (row_weight).
 // One launch covers two logits arrays: blocks x < rows_a serve array A ([B, rows_a, V], row j
 // live when j < K[b] + extra_a), the rest array B ([B, rows_b, V], live when j < K[b] + extra_b).
-// Without top-k a row is read once: every thread keeps a running (max, sum) pair over its
-// strided 16-byte pieces and the pairs are rescaled to the row maximum at the end.
+// A row of up to 32768 16-byte-aligned elements is read once, into registers, in the layout of the inverse-CDF
+// walk (wavefront w owns the contiguous range [w CW, (w + 1) CW), lane l holds elements 4 l .. 4 l + 3 of each of
+// its 256-element rows: a load instruction covers 1 KB): block maximum first, then one weight per element.
+constexpr int NR = 8;                                  // 256-element rows per wavefront
+constexpr int REG_V_MAX = (SB / 64) * NR * 256;        // 32768: a row fits the registers of one workgroup
+
+struct RowStat { float mx, sum, thr; int arg; };
+
+// The weight of a logit x in a row with maximum mx: exp((x - mx) / T) as 2^((x - mx) k), k = log2(e) / T, on the
+// hardware's exp2 (1 ulp; results below 2^-126 are flushed to 0).  The product's rounding adds a relative error of
+// at most 2^-24 |(x - mx) k| ln 2: 4e-8 per unit of distance below the maximum, i.e. the weights that carry the
+// sum are as exact as expf's, and three instructions replace the library routine's fifteen (a workgroup per row is
+// bound by its CU's vector ALUs as much as by memory).  Every place that needs a row's weights calls this, so the
+// statistics, the residual and the draw see the same bits.
+__device__ __forceinline__ float row_weight(float x, float mx, float k) { return __builtin_amdgcn_exp2f((x - mx) * k); }
+
+// Row l[0..V) into x, sampling layout (V a multiple of 4, l 16-byte aligned).  Elements beyond the wavefront's
+// range get PAD: far below any logit (it never wins a maximum, its weight is 0) and finite, so nothing after the
+// load needs to know which elements are real.
+constexpr float PAD = -1.0e30f;
+template <bool STREAM>
+__device__ __forceinline__ void load_row_regs(const float* __restrict__ l, int beg, int end, int lane, float (&x)[NR][4]) {
+  typedef float f32x4 __attribute__((ext_vector_type(4)));
+#pragma unroll
+  for (int r = 0; r < NR; ++r) {
+    const int v0 = beg + r * 256 + 4 * lane;           // beg, end and v0 are multiples of 4
+    x[r][0] = x[r][1] = x[r][2] = x[r][3] = PAD;
+    if (v0 < end) {                                    // STREAM: first and only read from HBM, non-temporal
+      const f32x4* src = reinterpret_cast<const f32x4*>(l + v0);
+      const f32x4 t = STREAM ? __builtin_nontemporal_load(src) : *src;
+      x[r][0] = t.x;
+      x[r][1] = t.y;
+      x[r][2] = t.z;
+      x[r][3] = t.w;
+    }
+  }
+}
+
+// Statistics of the row held in x (maximum with the lowest index among equals, top-k threshold, sum of the kept
+// weights) and, in place, x <- the weights of the kept elements, 0 elsewhere.  sh_i: SB / 64 + 1 ints.
+template <bool TOPK>
+__device__ __forceinline__ RowStat row_stat_regs(float (&x)[NR][4], int V, int beg, int lane, float k, int top_k,
+                                                 bool& bad, float* sh_w, int* sh_i) {
+  float m = x[0][0], lo = x[0][0];
+#pragma unroll
+  for (int r = 0; r < NR; ++r) {
+    m = fmaxf(fmaxf(m, x[r][0]), fmaxf(x[r][1], fmaxf(x[r][2], x[r][3])));
+    lo = fminf(fminf(lo, x[r][0]), fminf(x[r][1], fminf(x[r][2], x[r][3])));
+  }
+  bad |= lo == -INFINITY;                              // NaN and +inf show in the sum of the weights below
+  const float mx = block_max(m, sh_w);
+  // lowest index of the maximum: only threads that hold it look
+  if (threadIdx.x == 0) sh_i[SB / 64] = 0x7fffffff;
+  __syncthreads();
+  if (m == mx) {
+    int slot = 0;
+#pragma unroll
+    for (int r = NR - 1; r >= 0; --r)
+#pragma unroll
+      for (int e = 3; e >= 0; --e)
+        if (x[r][e] == mx) slot = r * 4 + e;
+    atomicMin(&sh_i[SB / 64], beg + (slot >> 2) * 256 + 4 * lane + (slot & 3));
+  }
+  __syncthreads();
+  const int arg = sh_i[SB / 64];
+  float thr = -INFINITY;
+  float s = 0.f;
+  if (TOPK) {
+    // the k-th largest value, bit by bit on the order keys (see block_kth_largest); the keys take the place of
+    // the values in the registers and are turned back afterwards (the map is a bijection).  PAD's key lies below
+    // the key of every logit, and top_k < V logits exist, so the padding is never counted at the bit that decides
+#pragma unroll
+    for (int r = 0; r < NR; ++r)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) x[r][e] = __uint_as_float(order_key(x[r][e]));
+    uint32_t t = 0;
+    const int w = threadIdx.x >> 6;
+    for (int bit = 31; bit >= 0; --bit) {
+      const uint32_t c = t | (1u << bit);
+      int cnt = 0;
+#pragma unroll
+      for (int r = 0; r < NR; ++r)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) cnt += __popcll(__ballot(__float_as_uint(x[r][e]) >= c));
+      if (lane == 0) sh_i[w] = cnt;
+      __syncthreads();
+      int tot = 0;
+      for (int i = 0; i < SB / 64; ++i) tot += sh_i[i];
+      __syncthreads();
+      if (tot >= top_k) t = c;
+    }
+    thr = key_to_float(t);
+#pragma unroll
+    for (int r = 0; r < NR; ++r)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const float v = key_to_float(__float_as_uint(x[r][e]));
+        const float wt = v >= thr ? row_weight(v, mx, k) : 0.f;
+        x[r][e] = wt;
+        s += wt;
+      }
+  } else {
+#pragma unroll
+    for (int r = 0; r < NR; ++r)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const float wt = row_weight(x[r][e], mx, k);   // padding: 0
+        x[r][e] = wt;
+        s += wt;
+      }
+  }
+  const float total = block_sum(s, sh_w);
+  bad |= !(total > 0.f && total < INFINITY);           // a NaN or +inf logit makes the sum NaN
+  return RowStat{mx, total, thr, arg};
+}
+
+// Any other row (longer, or not 16-byte aligned): strided walks over global memory.
+__device__ RowStat row_stat_global(const float* __restrict__ l, int V, float k, int top_k, bool& bad, float* sh_w,
+                                   int* sh_i) {
+  ArgMax am{-INFINITY, 0x7fffffff};
+  for (int v = threadIdx.x; v < V; v += SB) {
+    const float x = l[v];
+    bad |= !isfinite(x);
+    if (x > am.v) am = ArgMax{x, v};                   // strided indices grow, so ties keep the lowest id
+  }
+  am = block_argmax(am, sh_w, sh_i);
+  const float thr = (top_k > 0 && top_k < V) ? block_kth_largest(l, V, top_k, sh_i) : -INFINITY;
+  float s = 0.f;
+  for (int v = threadIdx.x; v < V; v += SB) s += l[v] >= thr ? row_weight(l[v], am.v, k) : 0.f;
+  const float total = block_sum(s, sh_w);
+  return RowStat{am.v, total, thr, am.i};
+}
+
+__device__ __forceinline__ bool rows_in_regs(const float* l, int V) {
+  return V <= REG_V_MAX && (V & 3) == 0 && (reinterpret_cast<uintptr_t>(l) & 15) == 0;
+}
+
 struct RowSet { const float* logits; float* stats; int rows, extra; };
 
-__global__ __launch_bounds__(SB) void row_stats_k(RowSet A, RowSet Bq, const int32_t* __restrict__ K, int V, float inv_t,
-                                                  int top_k, int32_t* __restrict__ err, int32_t* __restrict__ oob) {
+// REGS: every row of the call fits the registers (the launcher decides); TOPK: top_k is in (0, V).
+template <bool REGS, bool TOPK>
+__global__ __launch_bounds__(SB) __attribute__((amdgpu_waves_per_eu(8, 8))) void row_stats_k(
+    RowSet A, RowSet Bq, const int32_t* __restrict__ K, int V, float inv_t, int top_k, int32_t* __restrict__ err,
+    int32_t* __restrict__ oob) {
   __shared__ float sh_w[SB / 64];
-  __shared__ int sh_i[SB / 64];
+  __shared__ int sh_i[SB / 64 + 1];
   const int b = blockIdx.y;
   const bool first = (int)blockIdx.x < A.rows;
   const RowSet& R = first ? A : Bq;
@@ -395,89 +534,25 @@ __global__ __launch_bounds__(SB) void row_stats_k(RowSet A, RowSet Bq, const int
   if (j >= min(max(K[b], 0), Bq.rows) + R.extra) return;       // K_b is clamped into [0, Kmax] (accept_k reports it)
   const size_t row = (size_t)b * R.rows + j;
   const float* l = R.logits + row * V;
-  const bool warp = top_k > 0 && top_k < V;
-  ArgMax am{-INFINITY, 0x7fffffff};
-  float run = 0.f;                                   // sum of exp((x - am.v)/T) over this thread's elements
+  const float k2 = inv_t * LOG2E;
   bool bad = false;
-  auto take = [&](float x, int v) {
-    bad |= !isfinite(x);
-    if (x > am.v) {                                  // strided indices grow, so ties keep the lowest id
-      run = run * expf((am.v - x) * inv_t) + 1.0f;
-      am = ArgMax{x, v};
-    } else {
-      run += expf((x - am.v) * inv_t);
-    }
-  };
-  if ((V & 3) == 0 && (reinterpret_cast<uintptr_t>(l) & 15) == 0) {
-    // A chunk = NQ 16-byte pieces per thread, all requested before the first is consumed (the row is
-    // read once, from HBM).  From registers: the chunk's maximum first, then one exponential per
-    // element relative to it, no branches (one workgroup per row is bound by its CU's vector ALUs,
-    // not by memory); chunks are folded into the running pair like single elements.
-    constexpr int NQ = 8;                            // V = 32000: the whole row in one chunk
-    const float4* l4 = reinterpret_cast<const float4*>(l);
-    const int nq = V / 4;
-    for (int q0 = 0; q0 < nq; q0 += NQ * SB) {
-      float4 x[NQ];
-#pragma unroll
-      for (int u = 0; u < NQ; ++u) {
-        const int q = q0 + u * SB + threadIdx.x;
-        x[u] = float4{-INFINITY, -INFINITY, -INFINITY, -INFINITY};
-        if (q < nq) {                                // read once: non-temporal, whole 128-byte lines per instruction
-          const float* src = reinterpret_cast<const float*>(l4 + q);
-          x[u] = float4{__builtin_nontemporal_load(src), __builtin_nontemporal_load(src + 1),
-                        __builtin_nontemporal_load(src + 2), __builtin_nontemporal_load(src + 3)};
-        }
-      }
-      ArgMax cm{-INFINITY, 0x7fffffff};
-      float chk = 0.f;                               // NaN as soon as one element is NaN or infinite
-#pragma unroll
-      for (int u = 0; u < NQ; ++u) {
-        const int q = q0 + u * SB + threadIdx.x;
-        if (q < nq) {
-          chk = fmaf(x[u].x, 0.f, chk); chk = fmaf(x[u].y, 0.f, chk);
-          chk = fmaf(x[u].z, 0.f, chk); chk = fmaf(x[u].w, 0.f, chk);
-        }
-        if (x[u].x > cm.v) cm = ArgMax{x[u].x, 4 * q};         // indices grow: ties keep the lowest id
-        if (x[u].y > cm.v) cm = ArgMax{x[u].y, 4 * q + 1};
-        if (x[u].z > cm.v) cm = ArgMax{x[u].z, 4 * q + 2};
-        if (x[u].w > cm.v) cm = ArgMax{x[u].w, 4 * q + 3};
-      }
-      bad |= !(chk == 0.f);
-      if (cm.i == 0x7fffffff) continue;              // nothing finite and above -inf in this chunk
-      float cs = 0.f;
-#pragma unroll
-      for (int u = 0; u < NQ; ++u) {                 // padding elements are -inf: exp gives 0
-        cs += expf((x[u].x - cm.v) * inv_t); cs += expf((x[u].y - cm.v) * inv_t);
-        cs += expf((x[u].z - cm.v) * inv_t); cs += expf((x[u].w - cm.v) * inv_t);
-      }
-      if (cm.v > am.v) {
-        run = run * expf((am.v - cm.v) * inv_t) + cs;
-        am = cm;
-      } else {
-        run += cs * expf((cm.v - am.v) * inv_t);
-      }
-    }
+  RowStat st;
+  if constexpr (REGS) {
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const int CW = (((V + SB / 64 - 1) / (SB / 64)) + 255) & ~255;
+    const int beg = min(w * CW, V), end = min(beg + CW, V);
+    float x[NR][4];
+    load_row_regs<true>(l, beg, end, lane, x);
+    st = row_stat_regs<TOPK>(x, V, beg, lane, k2, top_k, bad, sh_w, sh_i);
   } else {
-    for (int v = threadIdx.x; v < V; v += SB) take(l[v], v);
+    st = row_stat_global(l, V, k2, TOPK ? top_k : 0, bad, sh_w, sh_i);
   }
-  const ArgMax mine = am;
-  am = block_argmax(am, sh_w, sh_i);
   if (bad && err) atomicOr(err, 1);
-  float thr = -INFINITY, total;
-  if (!warp) {
-    const float scaled = mine.i == 0x7fffffff ? 0.f : run * expf((mine.v - am.v) * inv_t);
-    total = block_sum(scaled, sh_w);
-  } else {
-    thr = block_kth_largest(l, V, top_k, sh_i);
-    float local = 0.f;
-    for (int v = threadIdx.x; v < V; v += SB) local += l[v] >= thr ? expf((l[v] - am.v) * inv_t) : 0.f;
-    total = block_sum(local, sh_w);
-  }
   if (threadIdx.x == 0) {
-    R.stats[row * 4 + 0] = am.v;
-    R.stats[row * 4 + 1] = total;
-    R.stats[row * 4 + 2] = __int_as_float(am.i);
-    R.stats[row * 4 + 3] = thr;
+    R.stats[row * 4 + 0] = st.mx;
+    R.stats[row * 4 + 1] = st.sum;
+    R.stats[row * 4 + 2] = __int_as_float(st.arg);
+    R.stats[row * 4 + 3] = st.thr;
   }
 }
 
@@ -535,6 +610,91 @@ __global__ void mix_k(const int32_t* __restrict__ X, const int32_t* __restrict__
 }
 
 // ------------------------------------------------------------------ accept + resample
+// block_sample on weights held in registers (sampling layout): the same additions in the same order.
+__device__ __forceinline__ int block_sample_regs(const float (&f)[NR][4], int beg, int end, int lane, float u,
+                                                 float* sh_w, int* sh_res) {
+  const int t = threadIdx.x, w = t >> 6;
+  constexpr int NW = SB / 64;
+  // lane sum, inclusive lane scan and total of row r
+  auto row_scan = [&](int r, float& ls, float& incl, float& tot) {
+    float a = 0.f;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) a += f[r][e];
+    ls = a;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+      const float n = __shfl_up(a, o, WAVE);
+      if (lane >= o) a += n;
+    }
+    incl = a;
+    tot = __shfl(a, 63, WAVE);
+  };
+  float cw = 0.f;
+#pragma unroll
+  for (int r = 0; r < NR; ++r) {
+    float ls, incl, tot;
+    row_scan(r, ls, incl, tot);
+    if (beg + r * 256 < end) cw += tot;
+  }
+  if (lane == 0) sh_w[w] = cw;
+  if (t == 0) *sh_res = -1;
+  __syncthreads();
+  float off = 0.f, total = 0.f;
+  for (int k = 0; k < NW; ++k) {
+    if (k == w) off = total;
+    total += sh_w[k];
+  }
+  if (!(total > 0.f)) {                                // uniform: every thread sees the same total
+    __syncthreads();
+    return -1;
+  }
+  const float target = u * total;
+  if (off <= target && target < off + cw) {            // wave-uniform: the wavefront whose range holds the target
+    float run = 0.f;                                   // repeats its scans (the same additions) to find the element
+    bool found = false;
+#pragma unroll
+    for (int r = 0; r < NR; ++r) {
+      if (found || beg + r * 256 >= end) continue;
+      float ls, incl, tot;
+      row_scan(r, ls, incl, tot);
+      if (off + (run + tot) > target) {
+        const unsigned long long m = __ballot(off + (run + incl) > target);
+        if (lane == __ffsll((long long)m) - 1) {
+          float acc = run + (incl - ls);
+          int pick = -1, last_pos = -1;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            acc += f[r][e];
+            if (f[r][e] > 0.f) last_pos = e;
+            if (pick < 0 && off + acc > target) pick = e;
+          }
+          *sh_res = beg + r * 256 + 4 * lane + (pick >= 0 ? pick : last_pos);
+        }
+        found = true;
+      } else {
+        run += tot;
+      }
+    }
+  }
+  __syncthreads();
+  int res = *sh_res;
+  if (res < 0) {                                       // rounding left no bucket: largest v with mass
+    int best = -1;
+#pragma unroll
+    for (int r = 0; r < NR; ++r)
+#pragma unroll
+      for (int e = 0; e < 4; ++e)
+        if (f[r][e] > 0.f) best = r * 4 + e;                         // indices grow
+    if (best >= 0) best = beg + (best >> 2) * 256 + 4 * lane + (best & 3);
+    __syncthreads();
+    atomicMax(sh_res, best);
+    __syncthreads();
+    res = *sh_res;
+  }
+  __syncthreads();                                     // sh_w and sh_res are free again
+  return res;
+}
+
 __global__ __launch_bounds__(SB) void accept_k(const float* __restrict__ p_logits, const float* __restrict__ q_logits,
                                                const float* __restrict__ p_stats, const float* __restrict__ q_stats,
                                                const int32_t* __restrict__ cand, int cand_ld,
@@ -592,26 +752,55 @@ __global__ __launch_bounds__(SB) void accept_k(const float* __restrict__ p_logit
   if (p.greedy) {
     y = __float_as_int(ps[n * 4 + 2]);
   } else {
+    const int nq = min(n, Kmax - 1);                     // the draft row is read when n < K only
     const float* prow = pl + (size_t)n * V;
+    const float* qrow = ql + (size_t)nq * V;
     const float pmx = ps[n * 4], pinv = 1.0f / ps[n * 4 + 1], pthr = ps[n * 4 + 3];
+    const float qmx = qs[nq * 4], qinv = 1.0f / qs[nq * 4 + 1], qthr = qs[nq * 4 + 3];
+    const float k2 = inv_t * LOG2E;
     const float u = philox_uniform(p.seed, (uint32_t)(n + 1), (uint32_t)rnd, (uint32_t)b, STREAM_RESAMPLE);
     y = -1;
-    if (n < K) {                                         // residual Norm[(p_{n+1} - q_{n+1})_+]
-      const float* qrow = ql + (size_t)n * V;
-      const float qmx = qs[n * 4], qinv = 1.0f / qs[n * 4 + 1], qthr = qs[n * 4 + 3];
-      y = block_sample(
-          [&](int v) {
-            const float pv = prow[v] >= pthr ? expf((prow[v] - pmx) * inv_t) * pinv : 0.f;
-            const float qv = qrow[v] >= qthr ? expf((qrow[v] - qmx) * inv_t) * qinv : 0.f;
-            return fmaxf(pv - qv, 0.f);
-          },
-          V, u, sh_w, &sh_res);
-      __syncthreads();
+    if (rows_in_regs(prow, V) && rows_in_regs(qrow, V)) {
+      // both rows were read a moment ago by row_stats_k: they come from L2 or the memory-side cache, into registers
+      // in the layout of the walk, and every weight is evaluated once
+      const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+      const int CW = (((V + SB / 64 - 1) / (SB / 64)) + 255) & ~255;
+      const int beg = min(w * CW, V), end = min(beg + CW, V);
+      float x[NR][4], f[NR][4];
+      load_row_regs<false>(prow, beg, end, lane, x);
+      if (n < K) load_row_regs<false>(qrow, beg, end, lane, f);
+#pragma unroll
+      for (int r = 0; r < NR; ++r)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) x[r][e] = x[r][e] >= pthr ? row_weight(x[r][e], pmx, k2) * pinv : 0.f;   // padding: 0
+      if (n < K) {                                       // residual Norm[(p_{n+1} - q_{n+1})_+]
+#pragma unroll
+        for (int r = 0; r < NR; ++r)
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const float qv = f[r][e] >= qthr ? row_weight(f[r][e], qmx, k2) * qinv : 0.f;
+            f[r][e] = fmaxf(x[r][e] - qv, 0.f);
+          }
+        y = block_sample_regs(f, beg, end, lane, u, sh_w, &sh_res);
+      }
+      if (y < 0) y = block_sample_regs(x, beg, end, lane, u, sh_w, &sh_res);     // bonus token from p_{K+1}, or a residual with no mass
+    } else {
+      if (n < K) {
+        y = block_sample(
+            [&](int v) {
+              const float pv = prow[v] >= pthr ? row_weight(prow[v], pmx, k2) * pinv : 0.f;
+              const float qv = qrow[v] >= qthr ? row_weight(qrow[v], qmx, k2) * qinv : 0.f;
+              return fmaxf(pv - qv, 0.f);
+            },
+            V, u, sh_w, &sh_res);
+        __syncthreads();
+      }
+      if (y < 0)
+        y = block_sample([&](int v) { return prow[v] >= pthr ? row_weight(prow[v], pmx, k2) * pinv : 0.f; }, V, u, sh_w, &sh_res);
     }
-    if (y < 0)                                           // bonus token from p_{K+1}, or a residual with no mass
-      y = block_sample([&](int v) { return prow[v] >= pthr ? expf((prow[v] - pmx) * inv_t) * pinv : 0.f; }, V, u, sh_w, &sh_res);
     if (y < 0) y = __float_as_int(ps[n * 4 + 2]);
   }
+  if (y < 0 || y >= V) y = 0;                            // a row without a finite logit has no argmax
   if (threadIdx.x == 0) {
     n_out[b] = n;
     tok_out[b] = y;
@@ -703,8 +892,20 @@ hipError_t launch_row_stats(hipStream_t st, const float* p_logits, const float* 
       !(temperature > 0.f))
     return hipErrorInvalidValue;
   const RowSet A{p_logits, p_stats, Kmax + 1, 1}, Bq{q_logits, q_stats, Kmax, 0};
-  hipLaunchKernelGGL(row_stats_k, dim3(2 * Kmax + 1, B), dim3(SB), 0, st, A, Bq, K, V, 1.0f / temperature, top_k, err,
-                     bad);
+  // rows of up to 32768 16-byte-aligned elements are held in registers
+  const bool regs = V <= REG_V_MAX && (V & 3) == 0 &&
+                    ((reinterpret_cast<uintptr_t>(p_logits) | reinterpret_cast<uintptr_t>(q_logits)) & 15) == 0;
+  const bool topk = top_k > 0 && top_k < V;
+  const dim3 grid(2 * Kmax + 1, B), block(SB);
+  const float inv_t = 1.0f / temperature;
+  if (regs && topk)
+    hipLaunchKernelGGL((row_stats_k<true, true>), grid, block, 0, st, A, Bq, K, V, inv_t, top_k, err, bad);
+  else if (regs)
+    hipLaunchKernelGGL((row_stats_k<true, false>), grid, block, 0, st, A, Bq, K, V, inv_t, top_k, err, bad);
+  else if (topk)
+    hipLaunchKernelGGL((row_stats_k<false, true>), grid, block, 0, st, A, Bq, K, V, inv_t, top_k, err, bad);
+  else
+    hipLaunchKernelGGL((row_stats_k<false, false>), grid, block, 0, st, A, Bq, K, V, inv_t, top_k, err, bad);
   return hipGetLastError();
 }
 

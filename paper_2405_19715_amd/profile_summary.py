@@ -3,6 +3,7 @@ short text summary per phase of a round.
 
     python -m paper_2405_19715_amd.profile_summary <..._kernel_trace.csv> [--skip-rounds W]
     python -m paper_2405_19715_amd.profile_summary <..._counter_collection.csv> --pmc | --counters
+    python -m paper_2405_19715_amd.profile_summary <..._kernel_trace.csv> --by-grid accept_k,row_stats_k
 
 The whole-process statistics rocprofv3 prints mix the untimed prefill (which runs the
 same GEMM kernel over 32-row prompt chunks of both models) into every average.  This
@@ -18,7 +19,11 @@ import re
 import sys
 
 
-STREAMING = "gemm_bf16_str"          # gemm_bf16_stripe<M> and gemm_bf16_stream<NT>
+STREAMING = ("gemm_bf16_str", "gemm_bf16_mstripe")     # gemm_bf16_stripe<M>, gemm_bf16_stream<NT>, gemm_bf16_mstripe<..>
+
+
+def is_streaming(name: str) -> bool:
+    return any(s in name for s in STREAMING)
 
 
 def short_name(name: str) -> str:
@@ -51,10 +56,10 @@ def table(segments, title, out):
     for name, (n, t) in sorted(agg.items(), key=lambda kv: -kv[1][1]):
         out.write(f"  {name:48s} calls {n:6d}  avg {t / n / 1e3:9.2f} us  total {t / 1e6:9.3f} ms  {100.0 * t / span:5.1f}%\n")
     # the weight-streaming GEMMs come as several kernels (one stripe instantiation per row count, the MFMA kernel)
-    ws = [(n, t) for name, (n, t) in agg.items() if STREAMING in name]
+    ws = [(n, t) for name, (n, t) in agg.items() if is_streaming(name)]
     if len(ws) > 1:
         n, t = sum(a for a, _ in ws), sum(b for _, b in ws)
-        out.write(f"  {'all weight-streaming GEMMs (stripe<*> + stream<*>)':48s} calls {n:6d}  avg {t / n / 1e3:9.2f} us  "
+        out.write(f"  {'all weight-streaming GEMMs (stripe / mstripe / stream)':48s} calls {n:6d}  avg {t / n / 1e3:9.2f} us  "
                   f"total {t / 1e6:9.3f} ms  {100.0 * t / span:5.1f}%\n")
 
 
@@ -84,8 +89,8 @@ def pmc_summary(path, skip_rounds, out):
             continue
         n_pass += 1
         for _, n, _, v in rnd[cut:end]:
-            if STREAMING in n:
-                a2 = per_grid.setdefault("gemm_bf16_stripe<*> + gemm_bf16_stream<*> (target pass)", [0, 0.0])
+            if is_streaming(n):
+                a2 = per_grid.setdefault("gemm_bf16_stripe<*> + gemm_bf16_mstripe<*> + gemm_bf16_stream<*> (target pass)", [0, 0.0])
                 a2[0] += 1
                 a2[1] += v
     for k, (n, tot) in per_grid.items():
@@ -125,6 +130,24 @@ def counters_summary(path, skip_rounds, out):
         out.write(f"{n:40s} {c:36s} {tot / len(ds):18.1f} per launch ({len(ds)} launches)\n")
 
 
+def by_grid(path, patterns, out):
+    """Average duration per (kernel, grid in workgroups) of the kernels whose name holds one of
+    `patterns`: for benchmarks that run one kernel over several problem sizes."""
+    agg = collections.OrderedDict()
+    with open(path, newline="") as f:
+        for r in csv.DictReader(f):
+            name = short_name(r["Kernel_Name"])
+            if not any(p in name for p in patterns):
+                continue
+            wx, wy = max(int(r.get("Workgroup_Size_X", 1) or 1), 1), max(int(r.get("Workgroup_Size_Y", 1) or 1), 1)
+            key = (name.replace("sd::", ""), int(r["Grid_Size_X"]) // wx, int(r.get("Grid_Size_Y", 1) or 1) // wy)
+            a = agg.setdefault(key, [0, 0])
+            a[0] += 1
+            a[1] += int(r["End_Timestamp"]) - int(r["Start_Timestamp"])
+    for (name, gx, gy), (n, t) in sorted(agg.items()):
+        out.write(f"{name:28s} grid ({gx:3d}, {gy:3d})  calls {n:4d}  avg {t / n / 1e3:8.2f} us\n")
+
+
 def main(argv=None):
     ap = argparse.ArgumentParser()
     ap.add_argument("trace")
@@ -132,7 +155,12 @@ def main(argv=None):
     ap.add_argument("--pmc", action="store_true", help="the file is a counter_collection.csv of a --pmc run")
     ap.add_argument("--counters", action="store_true",
                     help="the file is a counter_collection.csv: average every counter over the target pass's GEMM launches")
+    ap.add_argument("--by-grid", default="", metavar="NAMES",
+                    help="comma-separated kernel name fragments: average duration per (kernel, grid) instead of per round")
     args = ap.parse_args(argv)
+    if args.by_grid:
+        by_grid(args.trace, [p for p in args.by_grid.split(",") if p], sys.stdout)
+        return
     if args.pmc:
         pmc_summary(args.trace, args.skip_rounds, sys.stdout)
         return
