@@ -191,6 +191,230 @@ __device__ int block_sample(F f, int V, float u, float* sh_w, int* sh_res) {
   return res;
 }
 
+// ------------------------------------------------------------------ logits rows held in registers
+// A row of up to 32768 16-byte-aligned elements is read once, into the registers of one 1024-thread workgroup, in
+// the layout of the inverse-CDF walk: wavefront w owns the contiguous range [w CW, (w + 1) CW), lane l holds elements
+// 4 l .. 4 l + 3 of each of its 256-element rows, so a load instruction covers 1 KB.  Statistics (block maximum
+// first, then one weight per element) and the draw work on those registers.
+constexpr int NR = 8;                                  // 256-element rows per wavefront
+constexpr int REG_V_MAX = (SB / 64) * NR * 256;        // 32768: a row fits the registers of one workgroup
+
+struct RowStat { float mx, sum, thr; int arg; };
+
+// The weight of a logit x in a row with maximum mx: exp((x - mx) / T) as 2^((x - mx) k), k = log2(e) / T, on the
+// hardware's exp2 (1 ulp; results below 2^-126 are flushed to 0).  The product's rounding adds a relative error of
+// at most 2^-24 |(x - mx) k| ln 2: 4e-8 per unit of distance below the maximum, i.e. the weights that carry the
+// sum are as exact as expf's, and three instructions replace the library routine's fifteen (a workgroup per row is
+// bound by its CU's vector ALUs as much as by memory).  Every place that needs a row's weights calls this, so the
+// statistics, the residual and the draw see the same bits.
+__device__ __forceinline__ float row_weight(float x, float mx, float k) { return __builtin_amdgcn_exp2f((x - mx) * k); }
+
+// Row l[0..V) into x, sampling layout (V a multiple of 4, l 16-byte aligned).  Elements beyond the wavefront's
+// range get PAD: far below any logit (it never wins a maximum, its weight is 0) and finite, so nothing after the
+// load needs to know which elements are real.
+constexpr float PAD = -1.0e30f;
+template <bool STREAM>
+__device__ __forceinline__ void load_row_regs(const float* __restrict__ l, int beg, int end, int lane, float (&x)[NR][4]) {
+  typedef float f32x4 __attribute__((ext_vector_type(4)));
+#pragma unroll
+  for (int r = 0; r < NR; ++r) {
+    const int v0 = beg + r * 256 + 4 * lane;           // beg, end and v0 are multiples of 4
+    x[r][0] = x[r][1] = x[r][2] = x[r][3] = PAD;
+    if (v0 < end) {                                    // STREAM: first and only read from HBM, non-temporal
+      const f32x4* src = reinterpret_cast<const f32x4*>(l + v0);
+      const f32x4 t = STREAM ? __builtin_nontemporal_load(src) : *src;
+      x[r][0] = t.x;
+      x[r][1] = t.y;
+      x[r][2] = t.z;
+      x[r][3] = t.w;
+    }
+  }
+}
+
+// Statistics of the row held in x (maximum with the lowest index among equals, top-k threshold, sum of the kept
+// weights) and, in place, x <- the weights of the kept elements, 0 elsewhere.  sh_i: SB / 64 + 1 ints.
+template <bool TOPK>
+__device__ __forceinline__ RowStat row_stat_regs(float (&x)[NR][4], int V, int beg, int lane, float k, int top_k,
+                                                 bool& bad, float* sh_w, int* sh_i) {
+  float m = x[0][0], lo = x[0][0];
+#pragma unroll
+  for (int r = 0; r < NR; ++r) {
+    m = fmaxf(fmaxf(m, x[r][0]), fmaxf(x[r][1], fmaxf(x[r][2], x[r][3])));
+    lo = fminf(fminf(lo, x[r][0]), fminf(x[r][1], fminf(x[r][2], x[r][3])));
+  }
+  bad |= lo == -INFINITY;                              // NaN and +inf show in the sum of the weights below
+  const float mx = block_max(m, sh_w);
+  // lowest index of the maximum: only threads that hold it look
+  if (threadIdx.x == 0) sh_i[SB / 64] = 0x7fffffff;
+  __syncthreads();
+  if (m == mx) {
+    int slot = 0;
+#pragma unroll
+    for (int r = NR - 1; r >= 0; --r)
+#pragma unroll
+      for (int e = 3; e >= 0; --e)
+        if (x[r][e] == mx) slot = r * 4 + e;
+    atomicMin(&sh_i[SB / 64], beg + (slot >> 2) * 256 + 4 * lane + (slot & 3));
+  }
+  __syncthreads();
+  const int arg = sh_i[SB / 64];
+  float thr = -INFINITY;
+  float s = 0.f;
+  if (TOPK) {
+    // the k-th largest value, bit by bit on the order keys (see block_kth_largest); the keys take the place of
+    // the values in the registers and are turned back afterwards (the map is a bijection).  PAD's key lies below
+    // the key of every logit, and top_k < V logits exist, so the padding is never counted at the bit that decides
+#pragma unroll
+    for (int r = 0; r < NR; ++r)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) x[r][e] = __uint_as_float(order_key(x[r][e]));
+    uint32_t t = 0;
+    const int w = threadIdx.x >> 6;
+    for (int bit = 31; bit >= 0; --bit) {
+      const uint32_t c = t | (1u << bit);
+      int cnt = 0;
+#pragma unroll
+      for (int r = 0; r < NR; ++r)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) cnt += __popcll(__ballot(__float_as_uint(x[r][e]) >= c));
+      if (lane == 0) sh_i[w] = cnt;
+      __syncthreads();
+      int tot = 0;
+      for (int i = 0; i < SB / 64; ++i) tot += sh_i[i];
+      __syncthreads();
+      if (tot >= top_k) t = c;
+    }
+    thr = key_to_float(t);
+#pragma unroll
+    for (int r = 0; r < NR; ++r)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const float v = key_to_float(__float_as_uint(x[r][e]));
+        const float wt = v >= thr ? row_weight(v, mx, k) : 0.f;
+        x[r][e] = wt;
+        s += wt;
+      }
+  } else {
+#pragma unroll
+    for (int r = 0; r < NR; ++r)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const float wt = row_weight(x[r][e], mx, k);   // padding: 0
+        x[r][e] = wt;
+        s += wt;
+      }
+  }
+  const float total = block_sum(s, sh_w);
+  bad |= !(total > 0.f && total < INFINITY);           // a NaN or +inf logit makes the sum NaN
+  return RowStat{mx, total, thr, arg};
+}
+
+// Any other row (longer, or not 16-byte aligned): strided walks over global memory.
+__device__ RowStat row_stat_global(const float* __restrict__ l, int V, float k, int top_k, bool& bad, float* sh_w,
+                                   int* sh_i) {
+  ArgMax am{-INFINITY, 0x7fffffff};
+  for (int v = threadIdx.x; v < V; v += SB) {
+    const float x = l[v];
+    bad |= !isfinite(x);
+    if (x > am.v) am = ArgMax{x, v};                   // strided indices grow, so ties keep the lowest id
+  }
+  am = block_argmax(am, sh_w, sh_i);
+  const float thr = (top_k > 0 && top_k < V) ? block_kth_largest(l, V, top_k, sh_i) : -INFINITY;
+  float s = 0.f;
+  for (int v = threadIdx.x; v < V; v += SB) s += l[v] >= thr ? row_weight(l[v], am.v, k) : 0.f;
+  const float total = block_sum(s, sh_w);
+  return RowStat{am.v, total, thr, am.i};
+}
+
+__device__ __forceinline__ bool rows_in_regs(const float* l, int V) {
+  return V <= REG_V_MAX && (V & 3) == 0 && (reinterpret_cast<uintptr_t>(l) & 15) == 0;
+}
+
+// block_sample on weights held in registers (sampling layout): the same additions in the same order.
+__device__ __forceinline__ int block_sample_regs(const float (&f)[NR][4], int beg, int end, int lane, float u,
+                                                 float* sh_w, int* sh_res) {
+  const int t = threadIdx.x, w = t >> 6;
+  constexpr int NW = SB / 64;
+  // lane sum, inclusive lane scan and total of row r
+  auto row_scan = [&](int r, float& ls, float& incl, float& tot) {
+    float a = 0.f;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) a += f[r][e];
+    ls = a;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+      const float n = __shfl_up(a, o, WAVE);
+      if (lane >= o) a += n;
+    }
+    incl = a;
+    tot = __shfl(a, 63, WAVE);
+  };
+  float cw = 0.f;
+#pragma unroll
+  for (int r = 0; r < NR; ++r) {
+    float ls, incl, tot;
+    row_scan(r, ls, incl, tot);
+    if (beg + r * 256 < end) cw += tot;
+  }
+  if (lane == 0) sh_w[w] = cw;
+  if (t == 0) *sh_res = -1;
+  __syncthreads();
+  float off = 0.f, total = 0.f;
+  for (int k = 0; k < NW; ++k) {
+    if (k == w) off = total;
+    total += sh_w[k];
+  }
+  if (!(total > 0.f)) {                                // uniform: every thread sees the same total
+    __syncthreads();
+    return -1;
+  }
+  const float target = u * total;
+  if (off <= target && target < off + cw) {            // wave-uniform: the wavefront whose range holds the target
+    float run = 0.f;                                   // repeats its scans (the same additions) to find the element
+    bool found = false;
+#pragma unroll
+    for (int r = 0; r < NR; ++r) {
+      if (found || beg + r * 256 >= end) continue;
+      float ls, incl, tot;
+      row_scan(r, ls, incl, tot);
+      if (off + (run + tot) > target) {
+        const unsigned long long m = __ballot(off + (run + incl) > target);
+        if (lane == __ffsll((long long)m) - 1) {
+          float acc = run + (incl - ls);
+          int pick = -1, last_pos = -1;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            acc += f[r][e];
+            if (f[r][e] > 0.f) last_pos = e;
+            if (pick < 0 && off + acc > target) pick = e;
+          }
+          *sh_res = beg + r * 256 + 4 * lane + (pick >= 0 ? pick : last_pos);
+        }
+        found = true;
+      } else {
+        run += tot;
+      }
+    }
+  }
+  __syncthreads();
+  int res = *sh_res;
+  if (res < 0) {                                       // rounding left no bucket: largest v with mass
+    int best = -1;
+#pragma unroll
+    for (int r = 0; r < NR; ++r)
+#pragma unroll
+      for (int e = 0; e < 4; ++e)
+        if (f[r][e] > 0.f) best = r * 4 + e;                         // indices grow
+    if (best >= 0) best = beg + (best >> 2) * 256 + 4 * lane + (best & 3);
+    __syncthreads();
+    atomicMax(sh_res, best);
+    __syncthreads();
+    res = *sh_res;
+  }
+  __syncthreads();                                     // sh_w and sh_res are free again
+  return res;
+}
+
 // ------------------------------------------------------------------ round bookkeeping
 __global__ void begin_round_k(SeqState s, int B, int k_max, int max_seq) {
   const int b = blockIdx.x * blockDim.x + threadIdx.x;
@@ -344,11 +568,27 @@ __global__ __launch_bounds__(SB) void sample_stop_k(SeqState s, const float* __r
   if (p.greedy) {
     y = am.i;
   } else {
-    const float mx = am.v, inv_t = 1.0f / p.temperature;
-    const float thr = (p.top_k > 0 && p.top_k < V) ? block_kth_largest(l, V, p.top_k, sh_i) : -INFINITY;
+    const float mx = am.v, inv_t = 1.0f / p.temperature, k2 = inv_t * LOG2E;
+    const bool warp = p.top_k > 0 && p.top_k < V;
     const float u = philox_uniform(p.seed, (uint32_t)step, (uint32_t)s.round[b], (uint32_t)b, STREAM_DRAFT);
-    y = block_sample([&](int v) { return l[v] >= thr ? expf((l[v] - mx) * inv_t) : 0.f; }, V, u, sh_w,
-                     &sh_res);
+    if (rows_in_regs(l, V)) {
+      // the row (written a moment ago by the LM head's launch: it comes from L2) once more, into registers in the
+      // layout of the walk; every weight is evaluated once
+      const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+      const int CW = (((V + SB / 64 - 1) / (SB / 64)) + 255) & ~255;
+      const int beg = min(w * CW, V), end = min(beg + CW, V);
+      const float thr = warp ? block_kth_largest(l, V, p.top_k, sh_i) : -INFINITY;
+      float x[NR][4];
+      load_row_regs<false>(l, beg, end, lane, x);
+#pragma unroll
+      for (int r = 0; r < NR; ++r)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) x[r][e] = x[r][e] >= thr ? row_weight(x[r][e], mx, k2) : 0.f;     // padding: 0
+      y = block_sample_regs(x, beg, end, lane, u, sh_w, &sh_res);
+    } else {
+      const float thr = warp ? block_kth_largest(l, V, p.top_k, sh_i) : -INFINITY;
+      y = block_sample([&](int v) { return l[v] >= thr ? row_weight(l[v], mx, k2) : 0.f; }, V, u, sh_w, &sh_res);
+    }
     if (y < 0) y = am.i;                // only reachable with non-finite logits
   }
 
@@ -382,140 +622,6 @@ __global__ __launch_bounds__(SB) void sample_stop_k(SeqState s, const float* __r
 // A row of up to 32768 16-byte-aligned elements is read once, into registers, in the layout of the inverse-CDF
 // walk (wavefront w owns the contiguous range [w CW, (w + 1) CW), lane l holds elements 4 l .. 4 l + 3 of each of
 // its 256-element rows: a load instruction covers 1 KB): block maximum first, then one weight per element.
-constexpr int NR = 8;                                  // 256-element rows per wavefront
-constexpr int REG_V_MAX = (SB / 64) * NR * 256;        // 32768: a row fits the registers of one workgroup
-
-struct RowStat { float mx, sum, thr; int arg; };
-
-// The weight of a logit x in a row with maximum mx: exp((x - mx) / T) as 2^((x - mx) k), k = log2(e) / T, on the
-// hardware's exp2 (1 ulp; results below 2^-126 are flushed to 0).  The product's rounding adds a relative error of
-// at most 2^-24 |(x - mx) k| ln 2: 4e-8 per unit of distance below the maximum, i.e. the weights that carry the
-// sum are as exact as expf's, and three instructions replace the library routine's fifteen (a workgroup per row is
-// bound by its CU's vector ALUs as much as by memory).  Every place that needs a row's weights calls this, so the
-// statistics, the residual and the draw see the same bits.
-__device__ __forceinline__ float row_weight(float x, float mx, float k) { return __builtin_amdgcn_exp2f((x - mx) * k); }
-
-// Row l[0..V) into x, sampling layout (V a multiple of 4, l 16-byte aligned).  Elements beyond the wavefront's
-// range get PAD: far below any logit (it never wins a maximum, its weight is 0) and finite, so nothing after the
-// load needs to know which elements are real.
-constexpr float PAD = -1.0e30f;
-template <bool STREAM>
-__device__ __forceinline__ void load_row_regs(const float* __restrict__ l, int beg, int end, int lane, float (&x)[NR][4]) {
-  typedef float f32x4 __attribute__((ext_vector_type(4)));
-#pragma unroll
-  for (int r = 0; r < NR; ++r) {
-    const int v0 = beg + r * 256 + 4 * lane;           // beg, end and v0 are multiples of 4
-    x[r][0] = x[r][1] = x[r][2] = x[r][3] = PAD;
-    if (v0 < end) {                                    // STREAM: first and only read from HBM, non-temporal
-      const f32x4* src = reinterpret_cast<const f32x4*>(l + v0);
-      const f32x4 t = STREAM ? __builtin_nontemporal_load(src) : *src;
-      x[r][0] = t.x;
-      x[r][1] = t.y;
-      x[r][2] = t.z;
-      x[r][3] = t.w;
-    }
-  }
-}
-
-// Statistics of the row held in x (maximum with the lowest index among equals, top-k threshold, sum of the kept
-// weights) and, in place, x <- the weights of the kept elements, 0 elsewhere.  sh_i: SB / 64 + 1 ints.
-template <bool TOPK>
-__device__ __forceinline__ RowStat row_stat_regs(float (&x)[NR][4], int V, int beg, int lane, float k, int top_k,
-                                                 bool& bad, float* sh_w, int* sh_i) {
-  float m = x[0][0], lo = x[0][0];
-#pragma unroll
-  for (int r = 0; r < NR; ++r) {
-    m = fmaxf(fmaxf(m, x[r][0]), fmaxf(x[r][1], fmaxf(x[r][2], x[r][3])));
-    lo = fminf(fminf(lo, x[r][0]), fminf(x[r][1], fminf(x[r][2], x[r][3])));
-  }
-  bad |= lo == -INFINITY;                              // NaN and +inf show in the sum of the weights below
-  const float mx = block_max(m, sh_w);
-  // lowest index of the maximum: only threads that hold it look
-  if (threadIdx.x == 0) sh_i[SB / 64] = 0x7fffffff;
-  __syncthreads();
-  if (m == mx) {
-    int slot = 0;
-#pragma unroll
-    for (int r = NR - 1; r >= 0; --r)
-#pragma unroll
-      for (int e = 3; e >= 0; --e)
-        if (x[r][e] == mx) slot = r * 4 + e;
-    atomicMin(&sh_i[SB / 64], beg + (slot >> 2) * 256 + 4 * lane + (slot & 3));
-  }
-  __syncthreads();
-  const int arg = sh_i[SB / 64];
-  float thr = -INFINITY;
-  float s = 0.f;
-  if (TOPK) {
-    // the k-th largest value, bit by bit on the order keys (see block_kth_largest); the keys take the place of
-    // the values in the registers and are turned back afterwards (the map is a bijection).  PAD's key lies below
-    // the key of every logit, and top_k < V logits exist, so the padding is never counted at the bit that decides
-#pragma unroll
-    for (int r = 0; r < NR; ++r)
-#pragma unroll
-      for (int e = 0; e < 4; ++e) x[r][e] = __uint_as_float(order_key(x[r][e]));
-    uint32_t t = 0;
-    const int w = threadIdx.x >> 6;
-    for (int bit = 31; bit >= 0; --bit) {
-      const uint32_t c = t | (1u << bit);
-      int cnt = 0;
-#pragma unroll
-      for (int r = 0; r < NR; ++r)
-#pragma unroll
-        for (int e = 0; e < 4; ++e) cnt += __popcll(__ballot(__float_as_uint(x[r][e]) >= c));
-      if (lane == 0) sh_i[w] = cnt;
-      __syncthreads();
-      int tot = 0;
-      for (int i = 0; i < SB / 64; ++i) tot += sh_i[i];
-      __syncthreads();
-      if (tot >= top_k) t = c;
-    }
-    thr = key_to_float(t);
-#pragma unroll
-    for (int r = 0; r < NR; ++r)
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        const float v = key_to_float(__float_as_uint(x[r][e]));
-        const float wt = v >= thr ? row_weight(v, mx, k) : 0.f;
-        x[r][e] = wt;
-        s += wt;
-      }
-  } else {
-#pragma unroll
-    for (int r = 0; r < NR; ++r)
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        const float wt = row_weight(x[r][e], mx, k);   // padding: 0
-        x[r][e] = wt;
-        s += wt;
-      }
-  }
-  const float total = block_sum(s, sh_w);
-  bad |= !(total > 0.f && total < INFINITY);           // a NaN or +inf logit makes the sum NaN
-  return RowStat{mx, total, thr, arg};
-}
-
-// Any other row (longer, or not 16-byte aligned): strided walks over global memory.
-__device__ RowStat row_stat_global(const float* __restrict__ l, int V, float k, int top_k, bool& bad, float* sh_w,
-                                   int* sh_i) {
-  ArgMax am{-INFINITY, 0x7fffffff};
-  for (int v = threadIdx.x; v < V; v += SB) {
-    const float x = l[v];
-    bad |= !isfinite(x);
-    if (x > am.v) am = ArgMax{x, v};                   // strided indices grow, so ties keep the lowest id
-  }
-  am = block_argmax(am, sh_w, sh_i);
-  const float thr = (top_k > 0 && top_k < V) ? block_kth_largest(l, V, top_k, sh_i) : -INFINITY;
-  float s = 0.f;
-  for (int v = threadIdx.x; v < V; v += SB) s += l[v] >= thr ? row_weight(l[v], am.v, k) : 0.f;
-  const float total = block_sum(s, sh_w);
-  return RowStat{am.v, total, thr, am.i};
-}
-
-__device__ __forceinline__ bool rows_in_regs(const float* l, int V) {
-  return V <= REG_V_MAX && (V & 3) == 0 && (reinterpret_cast<uintptr_t>(l) & 15) == 0;
-}
-
 struct RowSet { const float* logits; float* stats; int rows, extra; };
 
 // REGS: every row of the call fits the registers (the launcher decides); TOPK: top_k is in (0, V).
@@ -610,91 +716,6 @@ __global__ void mix_k(const int32_t* __restrict__ X, const int32_t* __restrict__
 }
 
 // ------------------------------------------------------------------ accept + resample
-// block_sample on weights held in registers (sampling layout): the same additions in the same order.
-__device__ __forceinline__ int block_sample_regs(const float (&f)[NR][4], int beg, int end, int lane, float u,
-                                                 float* sh_w, int* sh_res) {
-  const int t = threadIdx.x, w = t >> 6;
-  constexpr int NW = SB / 64;
-  // lane sum, inclusive lane scan and total of row r
-  auto row_scan = [&](int r, float& ls, float& incl, float& tot) {
-    float a = 0.f;
-#pragma unroll
-    for (int e = 0; e < 4; ++e) a += f[r][e];
-    ls = a;
-#pragma unroll
-    for (int o = 1; o < 64; o <<= 1) {
-      const float n = __shfl_up(a, o, WAVE);
-      if (lane >= o) a += n;
-    }
-    incl = a;
-    tot = __shfl(a, 63, WAVE);
-  };
-  float cw = 0.f;
-#pragma unroll
-  for (int r = 0; r < NR; ++r) {
-    float ls, incl, tot;
-    row_scan(r, ls, incl, tot);
-    if (beg + r * 256 < end) cw += tot;
-  }
-  if (lane == 0) sh_w[w] = cw;
-  if (t == 0) *sh_res = -1;
-  __syncthreads();
-  float off = 0.f, total = 0.f;
-  for (int k = 0; k < NW; ++k) {
-    if (k == w) off = total;
-    total += sh_w[k];
-  }
-  if (!(total > 0.f)) {                                // uniform: every thread sees the same total
-    __syncthreads();
-    return -1;
-  }
-  const float target = u * total;
-  if (off <= target && target < off + cw) {            // wave-uniform: the wavefront whose range holds the target
-    float run = 0.f;                                   // repeats its scans (the same additions) to find the element
-    bool found = false;
-#pragma unroll
-    for (int r = 0; r < NR; ++r) {
-      if (found || beg + r * 256 >= end) continue;
-      float ls, incl, tot;
-      row_scan(r, ls, incl, tot);
-      if (off + (run + tot) > target) {
-        const unsigned long long m = __ballot(off + (run + incl) > target);
-        if (lane == __ffsll((long long)m) - 1) {
-          float acc = run + (incl - ls);
-          int pick = -1, last_pos = -1;
-#pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            acc += f[r][e];
-            if (f[r][e] > 0.f) last_pos = e;
-            if (pick < 0 && off + acc > target) pick = e;
-          }
-          *sh_res = beg + r * 256 + 4 * lane + (pick >= 0 ? pick : last_pos);
-        }
-        found = true;
-      } else {
-        run += tot;
-      }
-    }
-  }
-  __syncthreads();
-  int res = *sh_res;
-  if (res < 0) {                                       // rounding left no bucket: largest v with mass
-    int best = -1;
-#pragma unroll
-    for (int r = 0; r < NR; ++r)
-#pragma unroll
-      for (int e = 0; e < 4; ++e)
-        if (f[r][e] > 0.f) best = r * 4 + e;                         // indices grow
-    if (best >= 0) best = beg + (best >> 2) * 256 + 4 * lane + (best & 3);
-    __syncthreads();
-    atomicMax(sh_res, best);
-    __syncthreads();
-    res = *sh_res;
-  }
-  __syncthreads();                                     // sh_w and sh_res are free again
-  return res;
-}
-
 __global__ __launch_bounds__(SB) void accept_k(const float* __restrict__ p_logits, const float* __restrict__ q_logits,
                                                const float* __restrict__ p_stats, const float* __restrict__ q_stats,
                                                const int32_t* __restrict__ cand, int cand_ld,
