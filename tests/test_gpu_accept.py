@@ -206,6 +206,19 @@ def test_odd_vocabulary_sizes(V):
         assert exempt <= 2
 
 
+def test_vocabulary_beyond_the_register_rows():
+    """A vocabulary of more than 32768 entries does not fit the registers of one workgroup: statistics and
+    the draw then walk the rows in global memory (same weights, same summation order).  Same parity as the
+    other cases, with and without top-k, and in greedy mode."""
+    V = 33000
+    _, exempt, _ = _run_case(2, 3, V, seed=31, rounds=3)
+    assert exempt <= 2
+    _, exempt, _ = _run_case(2, 3, V, seed=32, rounds=2, top_k=50)
+    assert exempt <= 2
+    _, exempt, _ = _run_case(2, 2, V, seed=33, rounds=2, greedy=True)
+    assert exempt == 0
+
+
 def test_sequences_without_candidates():
     """K_b = 0 (a sequence that drafted nothing): no accept test, n = 0, and y' is drawn from
     p_1 with the bonus-token uniform; mixed with sequences that do have candidates."""
