@@ -136,6 +136,43 @@ __global__ __launch_bounds__(ROW_THREADS) void add_norm_row_k(const float* __res
   }
 }
 
+// Embedding gather + RMSNorm of one row by one workgroup (same conditions as add_norm_row_k): one launch
+// instead of two at the head of every forward pass.
+template <typename T>
+__global__ __launch_bounds__(ROW_THREADS) void embed_norm_row_k(const T* __restrict__ emb, const int32_t* __restrict__ tok,
+                                                                const T* __restrict__ g, float eps,
+                                                                float* __restrict__ x, T* __restrict__ xn, int d,
+                                                                int vocab) {
+  __shared__ float red[ROW_THREADS / 64];
+  const int m = blockIdx.x;
+  int t = tok[m];
+  t = t < 0 ? 0 : (t >= vocab ? vocab - 1 : t);
+  const T* e = emb + (size_t)t * d;
+  float4 v[ROW_MAXU];
+  float ss = 0.f;
+#pragma unroll
+  for (int u = 0; u < ROW_MAXU; ++u) {
+    const int i = (u * ROW_THREADS + threadIdx.x) * 4;
+    if (i < d) {
+      const float4 a = Pack4<T>::ld(e + i);
+      *reinterpret_cast<float4*>(x + (size_t)m * d + i) = a;
+      v[u] = a;
+      ss += a.x * a.x + a.y * a.y + a.z * a.z + a.w * a.w;
+    }
+  }
+  ss = block_sum(ss, red);
+  const float inv = 1.0f / sqrtf(ss / (float)d + eps);
+#pragma unroll
+  for (int u = 0; u < ROW_MAXU; ++u) {
+    const int i = (u * ROW_THREADS + threadIdx.x) * 4;
+    if (i < d) {
+      const float4 gg = Pack4<T>::ld(g + i);
+      Pack4<T>::st(xn + (size_t)m * d + i,
+                   float4{v[u].x * inv * gg.x, v[u].y * inv * gg.y, v[u].z * inv * gg.z, v[u].w * inv * gg.w});
+    }
+  }
+}
+
 // One block per (row, head slot): slots [0, Hq) are query heads, [Hq, Hq+Hkv) key
 // heads, [Hq+Hkv, Hq+2Hkv) value heads.
 template <typename T>
@@ -245,6 +282,16 @@ hipError_t launch_embed_norm(hipStream_t st, int dtype, const void* emb, const v
   if (bad_rows(M) || d < 1 || !emb || !g || !tok || !x || !xn || !ssq) return hipErrorInvalidValue;
   const dim3 grid((d + NORM_COLS - 1) / NORM_COLS, M);
   if (grid.x > NORM_MAX_BLOCKS) return hipErrorInvalidValue;
+  if (d % 4 == 0 && d <= ROW_THREADS * 4 * ROW_MAXU &&
+      ((reinterpret_cast<uintptr_t>(emb) | reinterpret_cast<uintptr_t>(g) | reinterpret_cast<uintptr_t>(x) |
+        reinterpret_cast<uintptr_t>(xn)) & 15) == 0) {
+    SD_DISPATCH_T(dtype,
+                  hipLaunchKernelGGL(embed_norm_row_k<float>, dim3(M), dim3(ROW_THREADS), 0, st, (const float*)emb, tok,
+                                     (const float*)g, eps, x, (float*)xn, d, vocab),
+                  hipLaunchKernelGGL(embed_norm_row_k<bf16_t>, dim3(M), dim3(ROW_THREADS), 0, st, (const bf16_t*)emb,
+                                     tok, (const bf16_t*)g, eps, x, (bf16_t*)xn, d, vocab));
+    return hipGetLastError();
+  }
   SD_DISPATCH_T(dtype,
                 hipLaunchKernelGGL(embed_k<float>, grid, dim3(EW_THREADS), 0, st, (const float*)emb, tok, x, ssq, d,
                                    vocab);

@@ -76,6 +76,9 @@ struct sd_ctx {
   SeqState s{};
   int32_t* result = nullptr;       // device, [B, RESULT_INTS]
   int32_t* pinned = nullptr;       // host, pinned staging
+  int32_t* hflags = nullptr;       // host, pinned and coherent: [B] stop flags the draft step's last kernel writes itself
+  int32_t* hflags_dev = nullptr;   // the same memory as the device addresses it
+  uint32_t tick = 0;               // draft steps issued so far: tags the flag words
   size_t pinned_ints = 0;
   std::vector<void*> allocs;
 
@@ -229,9 +232,9 @@ void prof_collect(sd_ctx* c) {      // stream must be idle
 
 // One GEMM, optionally bracketed by events.
 sd_status gemm(sd_ctx* c, const ModelRt& rt, const void* W, const void* X, int ldx, const int* xrow, int M, int N,
-               int K, int prof_kind) {
+               int K, int prof_kind, float* out = nullptr) {
   ProfSample* ps = prof_kind >= 0 ? prof_begin(c, prof_kind, (double)N * K * rt.esz) : nullptr;
-  SD_HIP(launch_gemm(c->st, rt.m.dtype, W, X, ldx, xrow, c->part, M, N, K));
+  SD_HIP(launch_gemm(c->st, rt.m.dtype, W, X, ldx, xrow, out ? out : c->part, M, N, K));
   if (ps) (void)hipEventRecord(ps->b, c->st);
   return SD_OK;
 }
@@ -322,11 +325,14 @@ sd_status forward(sd_ctx* c, ModelRt& rt, int M, int RS, int max_kv_len, const i
   }
   if (logits_out) {
     sd_status s;
-    if ((s = gemm(c, rt, m.lm_head, c->xn, d, lm_rows, n_lm, m.vocab, d, profile && c->prof_every > 0 ? 4 : -1)) !=
-        SD_OK)
+    // one slice whose rows land back to back in the logits array (one sequence): the product writes them itself
+    const int S = gemm_splits(dt, n_lm, m.vocab, d);
+    const bool direct = S == 1 && !lm_dst && ld_row == m.vocab && n_lm <= lm_rs && m.vocab % 4 == 0;
+    if ((s = gemm(c, rt, m.lm_head, c->xn, d, lm_rows, n_lm, m.vocab, d, profile && c->prof_every > 0 ? 4 : -1,
+                  direct ? logits_out : nullptr)) != SD_OK)
       return s;
-    SD_HIP(launch_reduce_rows(st, c->part, gemm_splits(dt, n_lm, m.vocab, d), logits_out, lm_rs, ld_group, ld_row, n_lm,
-                              m.vocab, lm_dst));
+    if (!direct)
+      SD_HIP(launch_reduce_rows(st, c->part, S, logits_out, lm_rs, ld_group, ld_row, n_lm, m.vocab, lm_dst));
   }
   if (profile && c->prof_every > 0) ++c->prof_pass;        // the next pass samples the layers one further
   return SD_OK;
@@ -418,6 +424,7 @@ sd_status sd_destroy(sd_ctx* c) {
   (void)hipStreamSynchronize(c->st);
   for (void* p : c->allocs) (void)hipFree(p);
   if (c->pinned) (void)hipHostFree(c->pinned);
+  if (c->hflags) (void)hipHostFree(c->hflags);
   for (auto& e : c->ev)
     if (e) (void)hipEventDestroy(e);
   for (auto& ps : c->prof_pool) {
@@ -530,6 +537,10 @@ sd_status sd_create(sd_ctx** out, const sd_model* target, const sd_model* draft,
 #undef SD_ALLOC
   c->pinned_ints = std::max<size_t>(3 * MAX_PREFILL_ROWS + 2, (size_t)B * RESULT_INTS) + 64;
   if (hipHostMalloc((void**)&c->pinned, c->pinned_ints * 4, hipHostMallocDefault) != hipSuccess) return fail(SD_ENOMEM);
+  if (hipHostMalloc((void**)&c->hflags, (size_t)B * 4, hipHostMallocCoherent | hipHostMallocMapped) != hipSuccess)
+    return fail(SD_ENOMEM);
+  std::memset(c->hflags, 0, (size_t)B * 4);
+  if (hipHostGetDevicePointer((void**)&c->hflags_dev, c->hflags, 0) != hipSuccess) return fail(SD_EDEVICE);
   for (auto& e : c->ev)
     if (hipEventCreate(&e) != hipSuccess) return fail(SD_EDEVICE);
   c->P.assign(B, 0);
@@ -576,6 +587,30 @@ sd_status sd_prefill(sd_ctx* c, int32_t seq, const int32_t* prompt, int32_t n) {
   return SD_OK;
 }
 
+// Stop flags of the draft step tagged `tick` into c->pinned[0..B).  The flag words arrive in host memory when the
+// step's last kernel ends; the wait is a bounded watch of those words (a step takes milliseconds), and if they do not
+// show within the bound (a runtime that does not make such stores visible before a synchronisation, a failed
+// launch) the stream is synchronised and the flags are copied from the device instead, so a wrong answer is not possible.
+static sd_status wait_stop_flags(sd_ctx* c, uint32_t tick) {
+  const int B = c->B;
+  volatile const int32_t* hf = c->hflags;
+  const auto t0 = std::chrono::steady_clock::now();
+  for (uint32_t spins = 0;; ++spins) {
+    bool ready = true;
+    for (int b = 0; b < B; ++b) ready = ready && ((uint32_t)hf[b] >> 1) == tick;
+    if (ready) {
+      for (int b = 0; b < B; ++b) c->pinned[b] = hf[b] & 1;
+      return SD_OK;
+    }
+    if ((spins & 0x3ff) == 0x3ff &&
+        std::chrono::duration<double>(std::chrono::steady_clock::now() - t0).count() > 0.25)
+      break;
+  }
+  SD_HIP(hipMemcpyAsync(c->pinned, c->s.stopped, B * sizeof(int32_t), hipMemcpyDeviceToHost, c->st));
+  SD_HIP(hipStreamSynchronize(c->st));
+  return SD_OK;
+}
+
 static sd_status round_impl(sd_ctx* c, const sd_params* params, sd_round_out* out, sd_stats* stats) {
   const int B = c->B, k_max = c->cfg.k_max, max_seq = c->cfg.max_seq, V = c->target.m.vocab;
   int maxP = 0, n_active = 0;
@@ -607,13 +642,15 @@ static sd_status round_impl(sd_ctx* c, const sd_params* params, sd_round_out* ou
     int z_dim = 0;
     const bool use_head = c->head.present && step > 1;
     if (use_head && (s = head_hidden(c, &z, &z_rows, &z_dim)) != SD_OK) return s;
+    // the step's last kernel writes every sequence's stop flag, tagged with the step's number, into coherent host
+    // memory: the host watches that word instead of draining the stream through a copy and a synchronisation
+    const uint32_t tick = (++c->tick) & 0x3fffffffu;
     SD_HIP(launch_sample_stop(st, c->draft.m.dtype, c->s, c->q_logits, (int64_t)k_max * V, z, z_rows, z_dim,
                               use_head ? c->head.W[c->head.n_layers - 1] : nullptr,
                               use_head ? c->head.b[c->head.n_layers - 1] : nullptr, use_head ? 1 : 0, dp, B, V,
-                              step));
+                              step, c->hflags_dev, tick));
     if (step < k_max) {
-      SD_HIP(hipMemcpyAsync(c->pinned, c->s.stopped, B * sizeof(int32_t), hipMemcpyDeviceToHost, st));
-      SD_HIP(hipStreamSynchronize(st));
+      if ((s = wait_stop_flags(c, tick)) != SD_OK) return s;
       bool all = true;
       for (int b = 0; b < B; ++b) {
         all = all && c->pinned[b] != 0;

@@ -151,10 +151,12 @@ hipError_t launch_plan_verify(hipStream_t st, const SeqState& s, const RowPlan& 
 hipError_t launch_plan_verify_ragged(hipStream_t st, const SeqState& s, const RowPlan& rows, int B, int RS,
                                      int n_groups, int k_max, int max_seq, int32_t* dst);
 // draw y_i from the draft logits row, update p_hat with the head's logit, apply the stop rule
+// host_flags (may be null): B words in host-mapped coherent memory; word b becomes (tick << 1) | stopped_b when the
+// kernel ends, also for a sequence that had stopped before (tick < 2^30)
 hipError_t launch_sample_stop(hipStream_t st, int dtype, const SeqState& s, const float* q_logits,
                               int64_t ld_seq, const void* z, const int* z_rows, int z_dim, const void* w_last,
                               const void* b_last, int have_head, const DecodeParams& p, int B, int V,
-                              int step);
+                              int step, int32_t* host_flags = nullptr, uint32_t tick = 0);
 // softmax statistics of the live rows of the target logits [B, Kmax + 1, V] (row j of sequence b
 // is live when j <= K[b]) and the draft logits [B, Kmax, V] (live when j < K[b]), in one launch:
 // stats[row] = {max, sum exp((l-max)/T), argmax, top-k threshold}.  With top_k > 0 only logits >=

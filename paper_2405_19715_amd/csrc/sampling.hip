@@ -519,12 +519,19 @@ template <typename T>
 __global__ __launch_bounds__(SB) void sample_stop_k(SeqState s, const float* __restrict__ q_logits, int64_t ld_seq,
                                                     const T* __restrict__ z, const int* __restrict__ z_rows, int z_dim,
                                                     const T* __restrict__ w_last, const T* __restrict__ b_last,
-                                                    int have_head, DecodeParams p, int V, int step) {
+                                                    int have_head, DecodeParams p, int V, int step,
+                                                    int32_t* __restrict__ host_flags, uint32_t tick) {
   __shared__ float sh_w[SB / 64];
   __shared__ int sh_i[SB / 64];
   __shared__ int sh_res;
   const int b = blockIdx.x;
-  if (s.stopped[b]) return;
+  if (s.stopped[b]) {
+    if (host_flags && threadIdx.x == 0) {
+      host_flags[b] = (int32_t)((tick << 1) | 1u);
+      __threadfence_system();
+    }
+    return;
+  }
   const float* l = q_logits + (size_t)b * ld_seq + (size_t)(step - 1) * V;
 
   // row maximum (and argmax), non-finite check
@@ -612,6 +619,10 @@ __global__ __launch_bounds__(SB) void sample_stop_k(SeqState s, const float* __r
     s.K[b] = step;
     const bool stop = (1.0f - ph > p.h) || (p.eos_id >= 0 && y == p.eos_id) || (step >= s.kcap[b]);
     s.stopped[b] = stop ? 1 : 0;
+    if (host_flags) {                    // for the host, which watches this word instead of synchronising
+      host_flags[b] = (int32_t)((tick << 1) | (stop ? 1u : 0u));
+      __threadfence_system();
+    }
   }
 }
 
@@ -892,15 +903,17 @@ hipError_t launch_plan_verify_ragged(hipStream_t st, const SeqState& s, const Ro
 
 hipError_t launch_sample_stop(hipStream_t st, int dtype, const SeqState& s, const float* q_logits, int64_t ld_seq,
                               const void* z, const int* z_rows, int z_dim, const void* w_last, const void* b_last,
-                              int have_head, const DecodeParams& p, int B, int V, int step) {
+                              int have_head, const DecodeParams& p, int B, int V, int step, int32_t* host_flags,
+                              uint32_t tick) {
   if (B < 1 || V < 1 || step < 1 || step > CAND_LD || !q_logits || !(p.temperature > 0.f)) return hipErrorInvalidValue;
+  if (tick >= (1u << 30)) return hipErrorInvalidValue;
   if (have_head && (!z || !w_last || !b_last || z_dim < 1)) return hipErrorInvalidValue;
   if (dtype == DT_F32)
     hipLaunchKernelGGL(sample_stop_k<float>, dim3(B), dim3(SB), 0, st, s, q_logits, ld_seq, (const float*)z, z_rows,
-                       z_dim, (const float*)w_last, (const float*)b_last, have_head, p, V, step);
+                       z_dim, (const float*)w_last, (const float*)b_last, have_head, p, V, step, host_flags, tick);
   else if (dtype == DT_BF16)
     hipLaunchKernelGGL(sample_stop_k<bf16_t>, dim3(B), dim3(SB), 0, st, s, q_logits, ld_seq, (const bf16_t*)z, z_rows,
-                       z_dim, (const bf16_t*)w_last, (const bf16_t*)b_last, have_head, p, V, step);
+                       z_dim, (const bf16_t*)w_last, (const bf16_t*)b_last, have_head, p, V, step, host_flags, tick);
   else
     return hipErrorInvalidValue;
   return hipGetLastError();
