@@ -390,11 +390,7 @@ hipError_t launch_attention(hipStream_t st, int dtype, const void* qbuf, const v
     }
     return hipGetLastError();
   }
-  if (hd == 128) {
-    if (sh.QTW == 1) SD_ATTN_LAUNCH(128, 1, false); else SD_ATTN_LAUNCH(128, 2, false);
-  } else {
-    if (sh.QTW == 1) SD_ATTN_LAUNCH(64, 1, false); else SD_ATTN_LAUNCH(64, 2, false);
-  }
+  if (hd == 128) SD_ATTN_LAUNCH(128, 1, false); else SD_ATTN_LAUNCH(64, 1, false);      // split keys: one tile per wavefront
 #undef SD_ATTN_LAUNCH
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
