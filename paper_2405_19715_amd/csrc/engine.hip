@@ -346,10 +346,16 @@ sd_status head_hidden(sd_ctx* c, const void** z, const int** z_rows, int* z_dim)
   const int* cur_rows = c->s.last_row;
   for (int j = 0; j + 1 < h.n_layers; ++j) {
     const int K = h.dims[j], N = h.dims[j + 1];
-    SD_HIP(launch_gemm(c->st, h.dtype, h.W[j], cur, K, cur_rows, c->part, c->B, N, K));
     void* out = c->hz[j & 1];
-    SD_HIP(launch_head_act(c->st, h.dtype, c->part, gemm_splits(h.dtype, c->B, N, K), h.b[j], cur, cur_rows, out,
-                           (h.residual && N == K) ? 1 : 0, c->B, N));
+    const bool skip = h.residual && N == K;
+    if (gemm_head_fused(h.dtype, c->B, N, K)) {        // bias, SiLU and the skip connection ride on the product
+      SD_HIP(launch_gemm_head(c->st, h.dtype, h.W[j], cur, K, cur_rows, h.b[j], skip ? cur : nullptr, cur_rows, out,
+                              c->B, N, K));
+    } else {
+      SD_HIP(launch_gemm(c->st, h.dtype, h.W[j], cur, K, cur_rows, c->part, c->B, N, K));
+      SD_HIP(launch_head_act(c->st, h.dtype, c->part, gemm_splits(h.dtype, c->B, N, K), h.b[j], cur, cur_rows, out,
+                             skip ? 1 : 0, c->B, N));
+    }
     cur = out;
     cur_rows = nullptr;
   }

@@ -678,6 +678,22 @@ hipError_t launch_gemm_rope(hipStream_t st, int dtype, const void* W, const void
                                  plan_stripe(M, N, K, false, true));
 }
 
+bool gemm_head_fused(int dtype, int M, int N, int K) { return dtype == DT_BF16 && plan_stripe(M, N, K).S == 1; }
+
+hipError_t launch_gemm_head(hipStream_t st, int dtype, const void* W, const void* X, int ldx, const int* xrow,
+                            const void* bias, const void* z_in, const int* z_rows, void* z_out, int M, int N, int K) {
+  if (!W || !X || !bias || !z_out || ldx < K || ldx % 8 != 0 || !gemm_head_fused(dtype, M, N, K)) return hipErrorInvalidValue;
+  if (z_in && N != K) return hipErrorInvalidValue;              // a skip connection needs a square layer
+  if ((reinterpret_cast<uintptr_t>(W) | reinterpret_cast<uintptr_t>(X)) & 15) return hipErrorInvalidValue;
+  StripeEpi epi{};
+  epi.act = (bf16_t*)z_out;
+  epi.bias = (const bf16_t*)bias;
+  epi.z_in = (const bf16_t*)z_in;
+  epi.z_rows = z_rows;
+  return launch_stripe<EPI_HEAD>(st, (const bf16_t*)W, (const bf16_t*)X, ldx, xrow, nullptr, epi, M, N, K,
+                                 plan_stripe(M, N, K));
+}
+
 int gemm_resid_groups(int dtype, int M, int N, int K) {
   if (dtype != DT_BF16) return 0;
   if (M > STRIPE_MAX_M) return mstripe_groups(M, N, K, EPI_RESID);

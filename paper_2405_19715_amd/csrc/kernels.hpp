@@ -61,6 +61,12 @@ hipError_t launch_gemm_rope(hipStream_t st, int dtype, const void* W, const void
                             float eps);
 hipError_t launch_gemm_resid(hipStream_t st, int dtype, const void* W, const void* X, int ldx, const int* xrow,
                              float* x, const void* gain, void* xg, float* ssq, int M, int N, int K);
+// A hidden layer of the acceptance head in one launch: z_out[m, n] = silu(X[m, :] . W[n, :] + bias[n]) (+ z_in[row, n]
+// with row = z_rows ? z_rows[m] : m when z_in is set; needs N == K), in bf16.  Same sums and roundings as launch_gemm
+// + launch_head_act on such a shape.  Row-stripe shapes with one slice only (gemm_head_fused).
+bool gemm_head_fused(int dtype, int M, int N, int K);
+hipError_t launch_gemm_head(hipStream_t st, int dtype, const void* W, const void* X, int ldx, const int* xrow,
+                            const void* bias, const void* z_in, const int* z_rows, void* z_out, int M, int N, int K);
 
 // ---------------------------------------------------------------- tiled GEMM (prompt pass, wide target passes)
 // C[s, m, n] = sum over the s-th K-slice of X[m, k] * W[n, k], bf16 in, fp32 out [S][M][N] with

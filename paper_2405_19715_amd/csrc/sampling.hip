@@ -5,9 +5,10 @@
 //
 // A sample from non-negative weights f with one uniform u is the inverse CDF in
 // index order: the first v whose running sum exceeds u * total.  The running sum
-// is taken in a fixed order (each of 1024 threads sums one contiguous chunk left to
-// right, chunk totals are scanned in thread order), so a draw never depends on
-// scheduling.
+// is taken in a fixed order (each of 16 wavefronts owns a contiguous range and walks it in
+// rows of 256 elements, a row's sum is an inclusive lane scan, row totals and wavefront
+// totals are added in order), so a draw never depends on scheduling.  The weights of a
+// softmax row are 2^((l - max) log2(e) / T) on the hardware's exp2 (row_weight).
 #include "common.hpp"
 #include "kernels.hpp"
 

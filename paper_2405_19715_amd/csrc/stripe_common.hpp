@@ -24,9 +24,12 @@ namespace sd {
 //             so the two sums of a rotary pair (i, i + hd/2) sit side by side in one wavefront's tile, and the sweep
 //             rotates them at the row's position and writes q (bf16 [M, Hq hd]), the key cache row and the
 //             (transposed) value cache column itself: no launch of its own for the rotary embedding and the KV append.
-enum { EPI_PART = 0, EPI_SILU = 1, EPI_RESID = 2, EPI_ROPE = 3 };
+//   EPI_HEAD  one slice: act[m, n] = bf16(silu(sum + bias[n]) (+ z_in[z_rows ? z_rows[m] : m][n] when z_in is set)): a
+//             hidden layer of the acceptance head (Sec. 4.2: a small ResNet with SiLU) without a launch of its own
+//             for the bias, the activation and the skip connection.
+enum { EPI_PART = 0, EPI_SILU = 1, EPI_RESID = 2, EPI_ROPE = 3, EPI_HEAD = 4 };
 struct StripeEpi {
-  bf16_t* act;             // SILU / RESID output [M][N]
+  bf16_t* act;             // SILU / RESID / HEAD output [M][N]
   float* x;                // RESID: residual rows [M][N], updated in place
   const bf16_t* gain;      // RESID: [N]
   float* ssq_out;          // RESID: [M][gridDim.x]
@@ -41,6 +44,10 @@ struct StripeEpi {
   bf16_t* kcache;          // [seq][Hkv][max_seq][hd]
   bf16_t* vcache;          // [seq][Hkv][hd][max_seq]
   int Hq, Hkv, hshift, max_seq;
+  // HEAD
+  const bf16_t* bias;      // [N]
+  const bf16_t* z_in;      // skip connection rows [.][N] (N = K) or null
+  const int32_t* z_rows;   // [M] row of z_in for activation row m, or null (row m)
 };
 
 typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2;
@@ -228,6 +235,21 @@ __device__ __forceinline__ void stripe_finish(const float* obuf, float* s_scale,
       }
       ssq = wave_sum(ssq);
       if (lane == 0) epi.ssq_out[m * gridDim.x + blockIdx.x] = ssq;
+    }
+  } else if constexpr (EPI == EPI_HEAD) {
+    for (int idx = threadIdx.x; idx < rpg * tile; idx += blockDim.x) {
+      const int l = idx / tile, rem = idx - l * tile;
+      const int m = rem / rpw, r = rem - m * rpw;
+      const int g = blockIdx.x * rpg + l;
+      const int n = g * rpw + r;
+      if (g >= ranges || n >= N) continue;
+      const float* src = obuf + (size_t)l * cs * tile + rem;
+      float sum = src[0];
+      for (int t = 1; t < cs; ++t) sum += src[(size_t)t * tile];
+      float a = bf2f(epi.bias[n]) + sum;
+      a = a / (1.0f + expf(-a));
+      if (epi.z_in) a += bf2f(epi.z_in[(size_t)(epi.z_rows ? epi.z_rows[m] : m) * N + n]);
+      epi.act[(size_t)m * N + n] = f2bf(a);
     }
   } else {
     for (int idx = threadIdx.x; idx < rpg * tile; idx += blockDim.x) {
