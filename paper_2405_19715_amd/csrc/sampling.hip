@@ -235,8 +235,8 @@ __device__ __forceinline__ void load_row_regs(const float* __restrict__ l, int b
 // Statistics of the row held in x (maximum with the lowest index among equals, top-k threshold, sum of the kept
 // weights) and, in place, x <- the weights of the kept elements, 0 elsewhere.  sh_i: SB / 64 + 1 ints.
 template <bool TOPK>
-__device__ __forceinline__ RowStat row_stat_regs(float (&x)[NR][4], int V, int beg, int lane, float k, int top_k,
-                                                 bool& bad, float* sh_w, int* sh_i) {
+__device__ __forceinline__ RowStat row_stat_regs(float (&x)[NR][4], int beg, int lane, float k, int top_k, bool& bad,
+                                                 float* sh_w, int* sh_i) {
   float m = x[0][0], lo = x[0][0];
 #pragma unroll
   for (int r = 0; r < NR; ++r) {
@@ -661,7 +661,7 @@ __global__ __launch_bounds__(SB) __attribute__((amdgpu_waves_per_eu(8, 8))) void
     const int beg = min(w * CW, V), end = min(beg + CW, V);
     float x[NR][4];
     load_row_regs<true>(l, beg, end, lane, x);
-    st = row_stat_regs<TOPK>(x, V, beg, lane, k2, top_k, bad, sh_w, sh_i);
+    st = row_stat_regs<TOPK>(x, beg, lane, k2, top_k, bad, sh_w, sh_i);
   } else {
     st = row_stat_global(l, V, k2, TOPK ? top_k : 0, bad, sh_w, sh_i);
   }
