@@ -242,9 +242,10 @@ sd_status sd_profile_read(sd_ctx *ctx, int64_t *launches, double *seconds, doubl
  * W: DEVICE [N, K] and X: DEVICE [M, K], both `dtype`; Y: DEVICE fp32 [M, N]; ws: DEVICE
  * scratch of sd_gemm_workspace_bytes(...) bytes (per-K-slice partial sums, added in
  * slice order).  1 <= M <= 160; for SD_BF16, K % 128 == 0 and N % 16 == 0, pointers
- * 16-byte aligned (more than 16 rows are handed to the tiled kernel below; up to 8 rows with
- * K >= 2048 (K % 8 == 0) go through a kernel that streams whole 1 KB pieces of single weight
- * rows and takes any N >= 1).  Enqueued on `hip_stream`; does not synchronise. */
+ * 16-byte aligned (more than 17 rows are handed to the tiled kernel below; up to 8 rows with
+ * K >= 2048 (K % 8 == 0), and 9 .. 17 rows with K % 512 == 0, go through kernels that stream whole
+ * 1 KB pieces of single weight rows and take any N >= 1).  Enqueued on `hip_stream`; does not
+ * synchronise. */
 sd_status sd_gemm_skinny(int32_t dtype, const void *W_dev, const void *X_dev, int32_t M, int32_t N, int32_t K,
                          float *Y_dev, void *ws_dev, void *hip_stream);
 
@@ -254,8 +255,8 @@ sd_status sd_gemm_skinny(int32_t dtype, const void *W_dev, const void *X_dev, in
  * Two ways to the same result, both rounding once, to `dtype`, at the end:
  *   mode 1: ONE launch, the row-stripe GEMM with the activation in its final sweep; ws is not used.  Possible
  *           (sd_mlp_act_is_fused returns 1) for SD_BF16, M <= 8, K >= 2048, K % 8 == 0, when a workgroup can hold a
- *           row range of gate and one of up (always for K <= 8192: up to four 2048-wide stripes per row);
- *           SD_EINVAL elsewhere.
+ *           row range of gate and one of up (always for K <= 8192: up to four 2048-wide stripes per row), and for
+ *           9 <= M <= 17 with K % 512 == 0; SD_EINVAL elsewhere.
  *   mode 0: sd_gemm_skinny's product followed by an activation kernel; ws is DEVICE scratch of
  *           sd_gemm_workspace_bytes(dtype, M, 2 ffn, K) bytes.
  *   mode -1: what the forward passes do: mode 1 where it is possible, else mode 0.
@@ -276,8 +277,8 @@ sd_status sd_mlp_act(int32_t dtype, const void *W_gate_up_dev, const void *X_dev
  * 0 <= row_pos[m] < max_seq and that row_seq[m] indexes the caches.  X: DEVICE [M, K] in `dtype`.
  *   mode 1: ONE launch: the row-stripe GEMM walks the rows of W so that both rows of a rotary pair land in one
  *           wavefront, and its final sweep rotates and writes q and the cache entries; ws is not used.  Possible
- *           (sd_qkv_rope_is_fused returns 1) for SD_BF16, M <= 8, K >= 2048, K % 8 == 0 and head_dim a power
- *           of two; SD_EINVAL elsewhere.
+ *           (sd_qkv_rope_is_fused returns 1) for SD_BF16 and head_dim a power of two, with M <= 8, K >= 2048,
+ *           K % 8 == 0, or with 9 <= M <= 17, K % 512 == 0; SD_EINVAL elsewhere.
  *   mode 0: sd_gemm_skinny's product followed by a rotary + append kernel; ws is DEVICE scratch of
  *           sd_gemm_workspace_bytes(dtype, M, N, K) bytes, N = (n_heads + 2 n_kv_heads) head_dim.
  *   mode -1: what the forward passes do: mode 1 where it is possible, else mode 0.

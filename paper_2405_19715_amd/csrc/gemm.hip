@@ -4,9 +4,11 @@
 // forward) and the draft steps (M = 1 or 2 rows) spend their time in: every weight
 // is read from HBM exactly once per call and used for M multiply-adds, so the
 // kernels are bound by HBM bandwidth and their design is about how the weight stream
-// is laid over workgroups, wavefronts and time.  Two of them: the row-stripe kernel
-// (up to 8 rows, vector-ALU dot products, described where it is defined below) and the
-// MFMA kernel described here (9 .. 16 rows, and K below 2048).
+// is laid over workgroups, wavefronts and time.  Three of them: the row-stripe kernel
+// (up to 8 rows, vector-ALU dot products, described where it is defined below), its sibling
+// for 9 .. 17 rows (matrix-core products on LDS-transposed half tiles, gemm_mstripe.hip) and
+// the older MFMA kernel described here (what is left up to 16 rows: K below 2048, or, beyond 8
+// rows, K not a multiple of 512).
 //
 // bf16 layout of the work of the MFMA kernel
 //   grid       = G row groups x S K-slices.  A workgroup (8 wavefronts) belongs to one

@@ -16,11 +16,10 @@ constexpr int MAX_PREFILL_ROWS = 1024; // most rows of one prompt-pass chunk (ti
 // W: [N, K] row-major in dtype; X: [M, K] rows (row stride ldx elements) in dtype,
 // optionally gathered through xrow (device int32 [M], may be null).
 // The number of K-slices is gemm_splits(dtype, M, N, K); consumers add the slices
-// in slice order.  bf16 products with more than 16 rows go through the tiled kernel
-// (launch_gemm_tile), which reads every weight once however many rows there are; up to 8
-// rows with K >= 2048 through the row-stripe kernel (vector-ALU dot products
-// on whole 1 KB row pieces: the access pattern that reads HBM fastest), the rest through the
-// MFMA streaming kernel.
+// in slice order.  bf16 products: up to 8 rows with K >= 2048 go through the row-stripe kernel (vector-ALU dot
+// products on whole 1 KB row pieces: the access pattern that reads HBM fastest), 9 .. 17 rows with K a multiple of
+// 512 through its matrix-core sibling (gemm_mstripe.hip), more rows through the tiled kernel (launch_gemm_tile),
+// which reads every weight once however many rows there are, the rest (up to 16 rows) through the MFMA streaming kernel.
 int gemm_splits(int dtype, int M, int N, int K);
 hipError_t launch_gemm(hipStream_t st, int dtype, const void* W, const void* X, int ldx, const int* xrow,
                        float* part, int M, int N, int K);
@@ -28,7 +27,8 @@ hipError_t launch_gemm(hipStream_t st, int dtype, const void* W, const void* X, 
 // act[m, f] = silu(X[m, :] . W[f, :]) * (X[m, :] . W[ffn + f, :]) in bf16, W = [gate; up] = [2 ffn, K]: the
 // row-stripe kernel with the MLP's activation in its final sweep (no partial sums, no activation launch).
 // Possible where gemm_silu_fused says so: bf16, up to 8 rows, K >= 2048 with a stripe count that leaves room for a
-// gate and an up range in one workgroup (always for K <= 8192); launch_gemm_silu returns
+// gate and an up range in one workgroup (always for K <= 8192), or 9 .. 17 rows with K a multiple of 512;
+// launch_gemm_silu returns
 // hipErrorInvalidValue elsewhere.  Same sums, same rounding as launch_gemm + launch_silu_mul on such a shape.
 // With `ssq` (device, [M][ssq_n]: per-workgroup sums of squares of the UNSCALED input rows, as launch_gemm_resid
 // leaves them) both sums are multiplied by r_m = rsqrt(sum_i ssq[m][i] / d_in + eps) first: the RMSNorm factor the
